@@ -1,0 +1,158 @@
+/*
+ * libvox: batched decode-step attention for SpeechLM serving on MI355X (gfx950).
+ *
+ * The operations are the two KV-cache touching pieces of the decode operation a
+ * serving Worker executes for a batch of concurrent streams (paper Section 3,
+ * "Worker ... prefill/decode/detokenize"; Section 3.1 "LLM Forward"; Section
+ * 3.1.1 names the attention backend as the optimised part of that stage):
+ *   1. append the K/V rows of the token just generated to a paged KV cache,
+ *   2. attend, for each stream, its single new query over its whole cached
+ *      context (grouped-query attention, one query row per stream).
+ * The paper fixes neither layout nor kernel design; both are defined here.
+ *
+ * Conventions
+ *   S    num_streams            Hq  num_q_heads      Hkv num_kv_heads
+ *   G    Hq / Hkv  (q head i reads kv head i / G;  1 <= G <= 8)
+ *   D    head_dim in {64, 128}  B   block_size == 16 tokens
+ *   P    num_blocks in each pool
+ *   L_s  context_lens[s]: tokens of stream s INCLUDING the one appended this
+ *        step.  L_s == 0 marks a padded / inactive slot.
+ *
+ * KV-cache layout (part of the ABI, bf16 elements, two separate pools):
+ *   K pool, element (blk, h, t, d), t in [0,B), d in [0,D):
+ *       (((blk*Hkv + h)*(D/8) + d/8)*B + t)*8 + d%8
+ *     i.e. [P][Hkv][D/8][B][8]: 8-dim slices of the 16 tokens are contiguous.
+ *   V pool, element (blk, h, t, d):
+ *       ((blk*Hkv + h)*D + d)*B + t
+ *     i.e. [P][Hkv][D][B]: each dim holds its 16 tokens contiguously.
+ *   Each (blk, h) pair is one contiguous granule of B*D*2 bytes in either pool.
+ *   block_tables is int32 [S][max_blocks_per_stream]; logical token t of
+ *   stream s lives in physical block block_tables[s][t / B], slot t % B.
+ *   Entries at or past ceil(L_s / B) are never read.  Slots t >= L_s of the
+ *   last block and blocks owned by no stream are never read either, whatever
+ *   bits they hold.
+ *
+ * Pointers are DEVICE pointers unless marked host.  The caller owns every
+ * buffer; the library allocates nothing, keeps no state between calls, and
+ * every call only enqueues work on `hip_stream` (a hipStream_t, may be NULL
+ * for the default stream) and returns: no synchronisation, no host copies.
+ * Contents of device-resident block_tables / context_lens are trusted (block
+ * ids outside [0,P) or L_s > max_blocks_per_stream*B are undefined behaviour).
+ *
+ * Every function returns VOX_OK (0) or a negative VOX_ERR_* code; the host-side
+ * checks (null pointers, shape rules, workspace size) run before any launch.
+ */
+#ifndef VOX_H_
+#define VOX_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VOX_OK 0
+#define VOX_ERR_NULL (-1)      /* a required pointer is NULL */
+#define VOX_ERR_SHAPE (-2)     /* S<=0, Hq%Hkv!=0, G>8, D not in {64,128}, B!=16, P<=0, ... */
+#define VOX_ERR_WORKSPACE (-3) /* workspace smaller than vox_paged_decode_min_workspace_bytes */
+#define VOX_ERR_HIP (-4)       /* a launch failed; hipGetLastError() still holds the cause */
+#define VOX_ERR_ARG (-5)       /* a scalar argument is out of range */
+
+/* Which decode kernel family runs; both give results within the same tolerance. */
+#define VOX_PATH_AUTO 0 /* the library's choice (MFMA) */
+#define VOX_PATH_MFMA 1 /* QK^T and PV on bf16 matrix cores, P split into hi+lo bf16 */
+#define VOX_PATH_VALU 2 /* fp32 vector ALU only; kept as the measured alternative */
+
+typedef struct {
+  int32_t num_streams;           /* S, may include padded slots with L_s == 0 */
+  int32_t num_q_heads;           /* Hq */
+  int32_t num_kv_heads;          /* Hkv */
+  int32_t head_dim;              /* D */
+  int32_t block_size;            /* B, must be 16 */
+  int32_t num_blocks;            /* P */
+  int32_t max_blocks_per_stream; /* row stride of block_tables */
+  float scale;                   /* softmax scale applied to the fp32 dot product */
+  int32_t decode_path;           /* VOX_PATH_* */
+  int32_t chunk_blocks;          /* split-K chunk length in blocks; 0 = library heuristic;
+                                    otherwise even and >= 2 */
+} vox_shape_t;
+
+/*
+ * KV append (first half of the decode step: the new token's K/V rows enter the
+ * cache before the query attends to them).  For every stream s with L_s > 0:
+ * p = L_s - 1, blk = block_tables[s][p / B], t = p % B, and for every kv head h
+ * and dim d the bf16 bit pattern k_new[s][h][d] is copied to K-pool element
+ * (blk, h, t, d), v_new likewise to the V pool.  Nothing else is written.
+ *   k_new, v_new : [S][Hkv][D] bf16, read only
+ *   k_pool,v_pool: layouts above, modified in place
+ */
+int vox_kv_append(const vox_shape_t* shape, const void* k_new, const void* v_new, void* k_pool,
+                  void* v_pool, const int32_t* block_tables, const int32_t* context_lens,
+                  void* hip_stream);
+
+/*
+ * Block gather (the paged read the decode kernels perform, exposed on its own so
+ * it can be checked bit for bit and used to export a stream's cache): for every
+ * stream s and t < L_s, row row_offsets[s] + t of k_out / v_out ([rows][Hkv][D]
+ * bf16, row-major) receives the K / V row of logical token t.
+ *   row_offsets : int64 [S] device; rows of different streams must not overlap.
+ */
+int vox_kv_gather(const vox_shape_t* shape, const void* k_pool, const void* v_pool,
+                  const int32_t* block_tables, const int32_t* context_lens,
+                  const int64_t* row_offsets, void* k_out, void* v_out, void* hip_stream);
+
+/*
+ * Workspace for vox_paged_decode / vox_decode_step: split-K work list and the
+ * partial (max, sum, accumulator) records.  `_workspace_bytes` is the size at
+ * which the library's preferred chunking always fits; any size down to
+ * `_min_workspace_bytes` works with coarser chunks.  Both return 0 on a bad shape.
+ * The workspace must be 256-byte aligned; its contents are scratch.
+ */
+size_t vox_paged_decode_workspace_bytes(const vox_shape_t* shape);
+size_t vox_paged_decode_min_workspace_bytes(const vox_shape_t* shape);
+
+/*
+ * Paged grouped-query attention decode (second half of the decode step).  For
+ * every stream s with L = L_s > 0 and q head i (kv head h = i / G):
+ *   z_t  = scale * sum_d q[s][i][d] * K(s,h,t,d)          t in [0, L)
+ *   p    = softmax(z)
+ *   out[s][i][:] = sum_t p_t * V(s,h,t,:)
+ *   lse[s][i]    = log(sum_t exp(z_t))                     (natural log)
+ * where K(s,h,t,d) / V(...) are read through block_tables.  Streams with
+ * L_s == 0 get out = 0 and lse = -inf.  Inputs are bf16, accumulation fp32.
+ *   q                 : [S][Hq][D] bf16
+ *   context_lens_host : HOST copy of context_lens or NULL.  When given, the
+ *                       launch grid and chunk length are sized from it;
+ *                       it must equal the device array.
+ *   out               : [S][Hq][D] fp32
+ *   lse               : [S][Hq] fp32 or NULL
+ * The context is split into chunks (split-K); each chunk's partial softmax
+ * state goes to the workspace and a merge kernel combines them.
+ */
+int vox_paged_decode(const vox_shape_t* shape, const void* q, const void* k_pool,
+                     const void* v_pool, const int32_t* block_tables,
+                     const int32_t* context_lens, const int32_t* context_lens_host, float* out,
+                     float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Whole decode step over `num_layers` backbone layers that share block_tables
+ * and context_lens (one allocation per stream, a pool pair per layer): for
+ * l = 0..num_layers-1 in order, vox_kv_append then vox_paged_decode on layer l's
+ * buffers.  The split-K work list is built once and reused by every layer.
+ * q, k_new, v_new, k_pool, v_pool, out are HOST arrays of num_layers device
+ * pointers with the per-layer shapes documented above.
+ */
+int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* const* q,
+                    const void* const* k_new, const void* const* v_new, void* const* k_pool,
+                    void* const* v_pool, const int32_t* block_tables, const int32_t* context_lens,
+                    const int32_t* context_lens_host, float* const* out, void* workspace,
+                    size_t workspace_bytes, void* hip_stream);
+
+/* Static, never-NULL description of a return code. */
+const char* vox_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VOX_H_ */

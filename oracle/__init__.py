@@ -1,0 +1,100 @@
+"""CPU fp64 oracle for the paged decode step (test infrastructure, not product code).
+
+Thin ctypes wrapper over ``vox_oracle.c``; arrays are numpy, bf16 values travel as
+uint16 bit patterns.  Importing this package never touches the HIP library.
+"""
+
+import ctypes
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(_build.build())
+        i, f, p = ctypes.c_int, ctypes.c_float, ctypes.c_void_p
+        lib.vox_oracle_kv_append.argtypes = [i] * 6 + [p] * 6
+        lib.vox_oracle_kv_append.restype = i
+        lib.vox_oracle_kv_gather.argtypes = [i] * 6 + [p] * 7
+        lib.vox_oracle_kv_gather.restype = i
+        lib.vox_oracle_paged_decode.argtypes = [i] * 7 + [f] + [p] * 5 + [i, i, p, p]
+        lib.vox_oracle_paged_decode.restype = i
+        lib.vox_oracle_num_threads.restype = i
+        _lib = lib
+    return _lib
+
+
+def _u16(a, shape=None):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.uint16:
+        raise TypeError("bf16 data must be passed as uint16 bit patterns")
+    return a
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"{what} failed with oracle status {rc}")
+
+
+def num_threads() -> int:
+    return int(_load().vox_oracle_num_threads())
+
+
+def kv_append(k_new, v_new, k_pool, v_pool, block_tables, context_lens, *, head_dim, block_size=16):
+    """In-place append on uint16 pools shaped [P, Hkv, B*D]."""
+    k_new, v_new = _u16(k_new), _u16(v_new)
+    bt, lens = _i32(block_tables), _i32(context_lens)
+    for pool in (k_pool, v_pool):
+        if pool.dtype != np.uint16 or not pool.flags.c_contiguous or not pool.flags.writeable:
+            raise TypeError("pools must be writable C-contiguous uint16 arrays")
+    s, hkv = k_new.shape[0], k_new.shape[1]
+    rc = _load().vox_oracle_kv_append(s, hkv, head_dim, block_size, k_pool.shape[0], bt.shape[1],
+                                      _ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool),
+                                      _ptr(bt), _ptr(lens))
+    _check(rc, "kv_append")
+
+
+def kv_gather(k_pool, v_pool, block_tables, context_lens, *, num_kv_heads, head_dim, block_size=16):
+    """Return (k, v, row_offsets): packed [T, Hkv, D] uint16 rows, stream s at row_offsets[s]."""
+    k_pool, v_pool = _u16(k_pool), _u16(v_pool)
+    bt, lens = _i32(block_tables), _i32(context_lens)
+    offs = np.zeros(lens.size, dtype=np.int64)
+    offs[1:] = np.cumsum(lens.astype(np.int64))[:-1]
+    total = int(lens.astype(np.int64).sum())
+    k = np.zeros((total, num_kv_heads, head_dim), dtype=np.uint16)
+    v = np.zeros_like(k)
+    rc = _load().vox_oracle_kv_gather(lens.size, num_kv_heads, head_dim, block_size,
+                                      k_pool.shape[0], bt.shape[1], _ptr(k_pool), _ptr(v_pool),
+                                      _ptr(bt), _ptr(lens), _ptr(offs), _ptr(k), _ptr(v))
+    _check(rc, "kv_gather")
+    return k, v, offs
+
+
+def paged_decode(q, k_pool, v_pool, block_tables, context_lens, scale, *, num_kv_heads,
+                 block_size=16, streams=None):
+    """fp64 (out [n, Hq, D], lse [n, Hq]) for streams ``range(*streams)`` (default: all)."""
+    q, k_pool, v_pool = _u16(q), _u16(k_pool), _u16(v_pool)
+    bt, lens = _i32(block_tables), _i32(context_lens)
+    s, hq, d = q.shape
+    s0, s1 = (0, s) if streams is None else streams
+    out = np.zeros((s1 - s0, hq, d), dtype=np.float64)
+    lse = np.zeros((s1 - s0, hq), dtype=np.float64)
+    rc = _load().vox_oracle_paged_decode(s, hq, num_kv_heads, d, block_size, k_pool.shape[0],
+                                         bt.shape[1], np.float32(scale), _ptr(q), _ptr(k_pool),
+                                         _ptr(v_pool), _ptr(bt), _ptr(lens), s0, s1 - s0,
+                                         _ptr(out), _ptr(lse))
+    _check(rc, "paged_decode")
+    return out, lse

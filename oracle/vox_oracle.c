@@ -1,0 +1,191 @@
+/*
+ * CPU oracle for the decode step's KV-cache operations.  TEST INFRASTRUCTURE
+ * ONLY: it is called by tests/, by the smoke check and by the benchmark's
+ * cpu_baseline leg; the product path never links, loads or calls it.  It shares
+ * no code with the HIP library.
+ *
+ * What it computes is the plain definition of the operations the paper places
+ * in the decode operation of the serving Worker (Section 3; Section 3.1 "LLM
+ * Forward"; Section 3.1.1 attention backend).  The paper gives no formula for
+ * them, so the definition is textbook softmax attention, one query row per
+ * stream, read through a block table, written out in fp64 with no blocking,
+ * fusion or reordering:
+ *
+ *   z_t = scale * sum_d q[d] * K[t][d],  p = softmax(z),  out = sum_t p_t V[t]
+ *
+ * bf16 inputs are widened exactly; `scale` arrives as the fp32 value the caller
+ * passes to the library and is widened exactly too.
+ *
+ * Cache layout (the library ABI this oracle is the reference for):
+ *   K element (blk,h,t,d) at (((blk*Hkv+h)*(D/8) + d/8)*B + t)*8 + d%8
+ *   V element (blk,h,t,d) at  ((blk*Hkv+h)*D + d)*B + t
+ *
+ * Parity pins (tests/test_oracle_pins.py): brute-force dense attention in
+ * numpy and in exact rational arithmetic on tiny inputs, single-key and
+ * equal-score closed forms, block permutation invariance, NaN poisoning of
+ * unread slots, power-of-two rescaling (bit-exact), score-shift invariance,
+ * GQA-vs-MHA reduction, convexity, lse consistency.  Against values printed in
+ * the paper: none exist for this path, so parity is unpinned in that sense.
+ */
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG (-1)
+#define ORACLE_ERR_BLOCK (-2) /* a block id that must be read is outside [0,P) */
+#define ORACLE_ERR_MEM (-3)
+
+static double bf16_to_f64(uint16_t bits) {
+  uint32_t u = (uint32_t)bits << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
+static size_t k_index(int Hkv, int D, int B, int64_t blk, int h, int t, int d) {
+  return ((((size_t)blk * Hkv + h) * (size_t)(D / 8) + (size_t)(d / 8)) * B + t) * 8 + (d % 8);
+}
+
+static size_t v_index(int Hkv, int D, int B, int64_t blk, int h, int t, int d) {
+  return (((size_t)blk * Hkv + h) * (size_t)D + d) * B + t;
+}
+
+static int shape_ok(int S, int Hq, int Hkv, int D, int B, int P, int max_nb) {
+  return S > 0 && Hq > 0 && Hkv > 0 && Hq % Hkv == 0 && D > 0 && D % 8 == 0 && B > 0 && P > 0 &&
+         max_nb > 0;
+}
+
+/* Physical block of logical token t of stream s, or -1 if the table entry is invalid. */
+static int64_t block_of(const int32_t* bt, int max_nb, int P, int B, int s, int t) {
+  int j = t / B;
+  if (j >= max_nb) return -1;
+  int32_t blk = bt[(size_t)s * max_nb + j];
+  return (blk < 0 || blk >= P) ? -1 : (int64_t)blk;
+}
+
+/* Append: position L_s - 1 of every active stream receives k_new / v_new bit for bit. */
+int vox_oracle_kv_append(int S, int Hkv, int D, int B, int P, int max_nb, const uint16_t* k_new,
+                         const uint16_t* v_new, uint16_t* k_pool, uint16_t* v_pool,
+                         const int32_t* bt, const int32_t* lens) {
+  if (!shape_ok(S, Hkv, Hkv, D, B, P, max_nb)) return ORACLE_ERR_ARG;
+  for (int s = 0; s < S; ++s) {
+    int L = lens[s];
+    if (L < 0) return ORACLE_ERR_ARG;
+    if (L == 0) continue;
+    int p = L - 1;
+    int64_t blk = block_of(bt, max_nb, P, B, s, p);
+    if (blk < 0) return ORACLE_ERR_BLOCK;
+    int t = p % B;
+    for (int h = 0; h < Hkv; ++h)
+      for (int d = 0; d < D; ++d) {
+        size_t src = ((size_t)s * Hkv + h) * D + d;
+        k_pool[k_index(Hkv, D, B, blk, h, t, d)] = k_new[src];
+        v_pool[v_index(Hkv, D, B, blk, h, t, d)] = v_new[src];
+      }
+  }
+  return ORACLE_OK;
+}
+
+/* Gather: rows row_offsets[s] + t of k_out / v_out ([rows][Hkv][D]) get token t of stream s. */
+int vox_oracle_kv_gather(int S, int Hkv, int D, int B, int P, int max_nb, const uint16_t* k_pool,
+                         const uint16_t* v_pool, const int32_t* bt, const int32_t* lens,
+                         const int64_t* row_offsets, uint16_t* k_out, uint16_t* v_out) {
+  if (!shape_ok(S, Hkv, Hkv, D, B, P, max_nb)) return ORACLE_ERR_ARG;
+  for (int s = 0; s < S; ++s) {
+    for (int t = 0; t < lens[s]; ++t) {
+      int64_t blk = block_of(bt, max_nb, P, B, s, t);
+      if (blk < 0) return ORACLE_ERR_BLOCK;
+      for (int h = 0; h < Hkv; ++h)
+        for (int d = 0; d < D; ++d) {
+          size_t dst = (((size_t)row_offsets[s] + t) * Hkv + h) * D + d;
+          k_out[dst] = k_pool[k_index(Hkv, D, B, blk, h, t % B, d)];
+          v_out[dst] = v_pool[v_index(Hkv, D, B, blk, h, t % B, d)];
+        }
+    }
+  }
+  return ORACLE_OK;
+}
+
+/*
+ * Decode for streams [s0, s0+ns): out is fp64 [ns][Hq][D], lse fp64 [ns][Hq] (may be NULL).
+ * Inactive streams (L == 0) give out = 0, lse = -inf.
+ */
+int vox_oracle_paged_decode(int S, int Hq, int Hkv, int D, int B, int P, int max_nb, float scale,
+                            const uint16_t* q, const uint16_t* k_pool, const uint16_t* v_pool,
+                            const int32_t* bt, const int32_t* lens, int s0, int ns, double* out,
+                            double* lse) {
+  if (!shape_ok(S, Hq, Hkv, D, B, P, max_nb) || s0 < 0 || ns < 0 || s0 + ns > S)
+    return ORACLE_ERR_ARG;
+  const int G = Hq / Hkv;
+  int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int item = 0; item < ns * Hq; ++item) {
+    const int s = s0 + item / Hq, i = item % Hq, h = i / G;
+    const int L = lens[s];
+    double* o = out + (size_t)item * D;
+    for (int d = 0; d < D; ++d) o[d] = 0.0;
+    if (L <= 0) {
+      if (lse) lse[item] = -INFINITY;
+      continue;
+    }
+    double* z = (double*)malloc((size_t)L * sizeof(double));
+    if (!z) {
+#pragma omp atomic write
+      status = ORACLE_ERR_MEM;
+      continue;
+    }
+    const uint16_t* qrow = q + ((size_t)s * Hq + i) * D;
+    int bad = 0;
+    double zmax = -INFINITY;
+    for (int t = 0; t < L; ++t) {
+      int64_t blk = block_of(bt, max_nb, P, B, s, t);
+      if (blk < 0) {
+        bad = 1;
+        break;
+      }
+      double dot = 0.0;
+      for (int d = 0; d < D; ++d)
+        dot += bf16_to_f64(qrow[d]) * bf16_to_f64(k_pool[k_index(Hkv, D, B, blk, h, t % B, d)]);
+      z[t] = (double)scale * dot;
+      if (z[t] > zmax) zmax = z[t];
+    }
+    if (bad) {
+#pragma omp atomic write
+      status = ORACLE_ERR_BLOCK;
+      free(z);
+      continue;
+    }
+    double denom = 0.0;
+    for (int t = 0; t < L; ++t) {
+      z[t] = exp(z[t] - zmax);
+      denom += z[t];
+    }
+    for (int t = 0; t < L; ++t) {
+      int64_t blk = block_of(bt, max_nb, P, B, s, t);
+      double p = z[t] / denom;
+      for (int d = 0; d < D; ++d)
+        o[d] += p * bf16_to_f64(v_pool[v_index(Hkv, D, B, blk, h, t % B, d)]);
+    }
+    if (lse) lse[item] = zmax + log(denom);
+    free(z);
+  }
+  return status;
+}
+
+/* Threads the decode loop would use (for reporting the baseline's core count). */
+int vox_oracle_num_threads(void) {
+  int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+  {
+#pragma omp single
+    n = omp_get_num_threads();
+  }
+#endif
+  return n;
+}
