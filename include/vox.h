@@ -136,6 +136,18 @@ int vox_paged_decode(const vox_shape_t* shape, const void* q, const void* k_pool
                      float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Measurement aid: vox_paged_decode that also records two caller-created hipEvent_t on
+ * hip_stream, one immediately before and one immediately after the split-K attention kernel
+ * (the launch that reads the KV cache), so its duration can be read with
+ * hipEventElapsedTime.  Either event may be NULL.
+ */
+int vox_paged_decode_profiled(const vox_shape_t* shape, const void* q, const void* k_pool,
+                              const void* v_pool, const int32_t* block_tables,
+                              const int32_t* context_lens, const int32_t* context_lens_host,
+                              float* out, float* lse, void* workspace, size_t workspace_bytes,
+                              void* hip_stream, void* event_before, void* event_after);
+
+/*
  * Whole decode step over `num_layers` backbone layers that share block_tables
  * and context_lens (one allocation per stream, a pool pair per layer): for
  * l = 0..num_layers-1 in order, vox_kv_append then vox_paged_decode on layer l's

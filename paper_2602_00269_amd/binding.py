@@ -1,0 +1,218 @@
+"""ctypes binding to libvox.so: argument marshalling only.
+
+Tensors are torch CUDA tensors (device memory owner); every step of the decode path runs in
+the HIP kernels behind the C ABI declared in ``include/vox.h``.  There is no fallback: if the
+library is missing, loading raises.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvox.so")
+
+PATH_AUTO, PATH_MFMA, PATH_VALU = 0, 1, 2
+
+
+class VoxShape(ctypes.Structure):
+    _fields_ = [
+        ("num_streams", ctypes.c_int32),
+        ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("block_size", ctypes.c_int32),
+        ("num_blocks", ctypes.c_int32),
+        ("max_blocks_per_stream", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+        ("decode_path", ctypes.c_int32),
+        ("chunk_blocks", ctypes.c_int32),
+    ]
+
+
+class VoxError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libvox.so from the package directory; raise if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2602_00269_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    sp = ctypes.POINTER(VoxShape)
+    lib.vox_kv_append.argtypes = [sp] + [vp] * 7
+    lib.vox_kv_append.restype = ctypes.c_int
+    lib.vox_kv_gather.argtypes = [sp] + [vp] * 8
+    lib.vox_kv_gather.restype = ctypes.c_int
+    lib.vox_paged_decode_workspace_bytes.argtypes = [sp]
+    lib.vox_paged_decode_workspace_bytes.restype = ctypes.c_size_t
+    lib.vox_paged_decode_min_workspace_bytes.argtypes = [sp]
+    lib.vox_paged_decode_min_workspace_bytes.restype = ctypes.c_size_t
+    lib.vox_paged_decode.argtypes = [sp] + [vp] * 9 + [ctypes.c_size_t, vp]
+    lib.vox_paged_decode.restype = ctypes.c_int
+    lib.vox_paged_decode_profiled.argtypes = [sp] + [vp] * 9 + [ctypes.c_size_t, vp, vp, vp]
+    lib.vox_paged_decode_profiled.restype = ctypes.c_int
+    lib.vox_decode_step.argtypes = [sp, i32] + [vp] * 10 + [ctypes.c_size_t, vp]
+    lib.vox_decode_step.restype = ctypes.c_int
+    lib.vox_strerror.argtypes = [ctypes.c_int]
+    lib.vox_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load().vox_strerror(code).decode()
+
+
+def make_shape(num_streams, num_q_heads, num_kv_heads, head_dim, num_blocks,
+               max_blocks_per_stream, scale, block_size=16, decode_path=PATH_AUTO,
+               chunk_blocks=0) -> VoxShape:
+    return VoxShape(num_streams, num_q_heads, num_kv_heads, head_dim, block_size, num_blocks,
+                    max_blocks_per_stream, float(scale), decode_path, chunk_blocks)
+
+
+def shape_of(w, decode_path=PATH_AUTO, chunk_blocks=0) -> VoxShape:
+    """VoxShape of a ``synth.Workload``."""
+    return make_shape(w.num_streams, w.num_q_heads, w.num_kv_heads, w.head_dim, w.num_blocks,
+                      w.max_blocks_per_stream, w.scale, w.block_size, decode_path, chunk_blocks)
+
+
+def _dev(t: Optional[torch.Tensor], dtype, what: str, optional=False):
+    if t is None:
+        if optional:
+            return None
+        raise TypeError(f"{what} is required")
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{what} must be a contiguous CUDA tensor of dtype {dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _host_lens(a):
+    if a is None:
+        return None, None
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data_as(ctypes.c_void_p)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise VoxError(rc, what)
+
+
+def kv_append(shape, k_new, v_new, k_pool, v_pool, block_tables, context_lens, stream=None):
+    bf, i32 = torch.bfloat16, torch.int32
+    rc = load().vox_kv_append(ctypes.byref(shape), _dev(k_new, bf, "k_new"),
+                              _dev(v_new, bf, "v_new"), _dev(k_pool, bf, "k_pool"),
+                              _dev(v_pool, bf, "v_pool"), _dev(block_tables, i32, "block_tables"),
+                              _dev(context_lens, i32, "context_lens"), _stream(stream))
+    _check(rc, "vox_kv_append")
+
+
+def kv_gather(shape, k_pool, v_pool, block_tables, context_lens, row_offsets, k_out, v_out,
+              stream=None):
+    bf, i32 = torch.bfloat16, torch.int32
+    rc = load().vox_kv_gather(ctypes.byref(shape), _dev(k_pool, bf, "k_pool"),
+                              _dev(v_pool, bf, "v_pool"), _dev(block_tables, i32, "block_tables"),
+                              _dev(context_lens, i32, "context_lens"),
+                              _dev(row_offsets, torch.int64, "row_offsets"),
+                              _dev(k_out, bf, "k_out"), _dev(v_out, bf, "v_out"), _stream(stream))
+    _check(rc, "vox_kv_gather")
+
+
+def paged_decode_workspace_bytes(shape) -> int:
+    n = load().vox_paged_decode_workspace_bytes(ctypes.byref(shape))
+    if n == 0:
+        raise VoxError(-2, "vox_paged_decode_workspace_bytes")
+    return int(n)
+
+
+def paged_decode_min_workspace_bytes(shape) -> int:
+    n = load().vox_paged_decode_min_workspace_bytes(ctypes.byref(shape))
+    if n == 0:
+        raise VoxError(-2, "vox_paged_decode_min_workspace_bytes")
+    return int(n)
+
+
+def alloc_workspace(shape, device="cuda", nbytes: Optional[int] = None) -> torch.Tensor:
+    n = paged_decode_workspace_bytes(shape) if nbytes is None else nbytes
+    return torch.empty(n, dtype=torch.uint8, device=device)  # torch allocations are 256-B aligned
+
+
+def paged_decode(shape, q, k_pool, v_pool, block_tables, context_lens, out, workspace, lse=None,
+                 context_lens_host=None, stream=None, events=None):
+    """``events``: optional pair of recorded-once ``torch.cuda.Event(enable_timing=True)``;
+    the library re-records them around the attention kernel."""
+    bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+    keep, host = _host_lens(context_lens_host)
+    ev0 = ev1 = None
+    if events is not None:
+        ev0, ev1 = (ctypes.c_void_p(e.cuda_event) for e in events)
+    rc = load().vox_paged_decode_profiled(
+        ctypes.byref(shape), _dev(q, bf, "q"), _dev(k_pool, bf, "k_pool"),
+        _dev(v_pool, bf, "v_pool"), _dev(block_tables, i32, "block_tables"),
+        _dev(context_lens, i32, "context_lens"), host, _dev(out, f32, "out"),
+        _dev(lse, f32, "lse", optional=True), _dev(workspace, torch.uint8, "workspace"),
+        workspace.numel(), _stream(stream), ev0, ev1)
+    del keep
+    _check(rc, "vox_paged_decode")
+
+
+class StepArgs:
+    """Host arrays of per-layer device pointers for ``decode_step``, built once and reused."""
+
+    def __init__(self, q: Sequence[torch.Tensor], k_new, v_new, k_pool, v_pool, out):
+        bf, f32 = torch.bfloat16, torch.float32
+        n = len(q)
+        if not all(len(x) == n for x in (k_new, v_new, k_pool, v_pool, out)):
+            raise ValueError("per-layer lists must have the same length")
+        self.num_layers = n
+        self._keep = (q, k_new, v_new, k_pool, v_pool, out)
+
+        def arr(ts, dtype, what):
+            a = (ctypes.c_void_p * n)()
+            for i, t in enumerate(ts):
+                a[i] = _dev(t, dtype, f"{what}[{i}]").value
+            return a
+
+        self.q = arr(q, bf, "q")
+        self.k_new = arr(k_new, bf, "k_new")
+        self.v_new = arr(v_new, bf, "v_new")
+        self.k_pool = arr(k_pool, bf, "k_pool")
+        self.v_pool = arr(v_pool, bf, "v_pool")
+        self.out = arr(out, f32, "out")
+
+
+def decode_step(shape, args: StepArgs, block_tables, context_lens, workspace,
+                context_lens_host=None, stream=None):
+    i32 = torch.int32
+    keep, host = _host_lens(context_lens_host)
+    rc = load().vox_decode_step(ctypes.byref(shape), args.num_layers, args.q, args.k_new,
+                                args.v_new, args.k_pool, args.v_pool,
+                                _dev(block_tables, i32, "block_tables"),
+                                _dev(context_lens, i32, "context_lens"), host, args.out,
+                                _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                _stream(stream))
+    del keep
+    _check(rc, "vox_decode_step")

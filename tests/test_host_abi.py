@@ -1,0 +1,107 @@
+"""Host-only checks of the C-ABI library: it loads, exports what the header declares, and its
+argument validation and workspace planning answer without touching a GPU."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_00269_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2602_00269_amd import build
+        build.build(verbose=False)
+    return binding.load()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "vox.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vox_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert {"vox_kv_append", "vox_kv_gather", "vox_paged_decode", "vox_decode_step",
+            "vox_paged_decode_workspace_bytes", "vox_paged_decode_min_workspace_bytes",
+            "vox_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_matches_header():
+    assert ctypes.sizeof(binding.VoxShape) == 40
+    text = open(os.path.join(ROOT, "include", "vox.h")).read()
+    body = text[text.index("typedef struct {"):text.index("} vox_shape_t;")]
+    fields = re.findall(r"(?:int32_t|float)\s+(\w+);", body)
+    assert fields == [f[0] for f in binding.VoxShape._fields_]
+
+
+def _shape(**kw):
+    a = dict(num_streams=4, num_q_heads=8, num_kv_heads=2, head_dim=64, num_blocks=128,
+             max_blocks_per_stream=16, scale=0.125)
+    a.update(kw)
+    return binding.make_shape(**a)
+
+
+@pytest.mark.parametrize("kw", [dict(num_streams=0), dict(num_q_heads=7), dict(head_dim=96),
+                                dict(block_size=32), dict(num_q_heads=18, num_kv_heads=2),
+                                dict(num_blocks=0), dict(max_blocks_per_stream=0)])
+def test_bad_shapes_are_rejected_before_any_launch(lib, kw):
+    sh = _shape(**kw)
+    one = ctypes.c_void_p(256)
+    rc = lib.vox_kv_append(ctypes.byref(sh), one, one, one, one, one, one, None)
+    assert rc == -2
+    assert lib.vox_paged_decode_workspace_bytes(ctypes.byref(sh)) == 0
+    rc = lib.vox_paged_decode(ctypes.byref(sh), one, one, one, one, one, None, one, None, one,
+                              1 << 20, None)
+    assert rc == -2
+
+
+def test_null_pointers_and_bad_scalars(lib):
+    sh = _shape()
+    one = ctypes.c_void_p(256)
+    assert lib.vox_kv_append(ctypes.byref(sh), None, one, one, one, one, one, None) == -1
+    assert lib.vox_paged_decode(ctypes.byref(sh), one, one, one, one, one, None, None, None, one,
+                                1 << 20, None) == -1
+    assert lib.vox_kv_append(None, one, one, one, one, one, one, None) == -1
+    assert lib.vox_kv_gather(ctypes.byref(sh), one, one, one, one, None, one, one, None) == -1
+    assert lib.vox_decode_step(ctypes.byref(sh), 0, one, one, one, one, one, one, one, None, one,
+                               one, 1 << 20, None) == -5
+    for kw in (dict(chunk_blocks=3), dict(chunk_blocks=66), dict(decode_path=9),
+               dict(scale=float("nan"))):
+        bad = _shape(**kw)
+        assert lib.vox_kv_append(ctypes.byref(bad), one, one, one, one, one, one, None) == -5
+    # misaligned workspace
+    assert lib.vox_paged_decode(ctypes.byref(sh), one, one, one, one, one, None, one, None,
+                                ctypes.c_void_p(257), 1 << 20, None) == -5
+
+
+def test_workspace_too_small_is_reported(lib):
+    sh = _shape()
+    one = ctypes.c_void_p(256)
+    need = binding.paged_decode_min_workspace_bytes(sh)
+    assert 0 < need <= binding.paged_decode_workspace_bytes(sh)
+    rc = lib.vox_paged_decode(ctypes.byref(sh), one, one, one, one, one, None, one, None, one, 64,
+                              None)
+    assert rc == -3
+
+
+def test_workspace_sizes_for_the_presets(lib):
+    # recommended sizes stay modest even when only the shape is known
+    for s, hq, hkv, d, p, mnb in [(256, 24, 8, 128, 45000, 250), (512, 24, 8, 128, 55000, 512),
+                                  (1024, 14, 2, 64, 170000, 256)]:
+        sh = binding.make_shape(s, hq, hkv, d, p, mnb, 0.1)
+        rec = binding.paged_decode_workspace_bytes(sh)
+        assert binding.paged_decode_min_workspace_bytes(sh) <= rec < (1 << 30)
+
+
+def test_strerror_is_total(lib):
+    for code in (0, -1, -2, -3, -4, -5, -99, 7):
+        assert binding.strerror(code)
