@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark: KV append + paged GQA decode on one MI355X.
+
+One step = one pass of the whole hot path (append, split-K plan, attention, merge) over one
+batch of synthetic streams, through ``vox_decode_step``; 28 layers in sequence for the
+small-backbone preset.  Prints ONE JSON line.
+
+  value      KV-cache bytes of valid tokens read per second (GB/s), inputs resident in HBM
+  roofline   the attention kernel alone: same bytes / its mean duration from HIP events
+             recorded around it on the launch stream in a second timed region
+  cpu_baseline  the fp64 oracle timed on the host cores over a bounded sample of the streams
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
+
+# HBM bytes per attention-kernel launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
+# the same counters on a plain copy kernel; filled in per workload from profiles/.
+MEASURED_TRAFFIC = {}
+
+
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--path", default="auto", choices=["auto", "mfma", "valu"])
+    ap.add_argument("--chunk-blocks", type=int, default=0)
+    ap.add_argument("--layers", type=int, default=None, help="override the preset's layer count")
+    ap.add_argument("--pool-copies", type=int, default=None,
+                    help="distinct pool sets rotated across steps (default: enough to exceed 1 GiB)")
+    ap.add_argument("--no-device-lens-only", dest="host_lens", action="store_true", default=True)
+    ap.add_argument("--device-lens-only", dest="host_lens", action="store_false",
+                    help="do not hand the host copy of context_lens to the library")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
+              "(the decode step shards by stream or by kv head with no exchange, see DESIGN.md)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2602_00269_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    binding.load()
+    dev = torch.device("cuda:0")
+    cfg = int(args.workload[3:])
+    path = {"auto": binding.PATH_AUTO, "mfma": binding.PATH_MFMA, "valu": binding.PATH_VALU}[args.path]
+
+    # ---- workload(s): distinct pool sets so small presets cannot live in the 256 MB cache
+    base = synth.make_workload(cfg, device=dev, layers=args.layers)
+    kv_bytes_layer = base.kv_bytes_per_layer
+    copies = args.pool_copies
+    if copies is None:
+        copies = 1 if kv_bytes_layer * base.layers >= (1 << 30) else \
+            int(min(16, -(-(1 << 30) // max(1, kv_bytes_layer * base.layers))))
+    import copy
+
+    sets = [base]
+    for _ in range(1, copies):  # same streams and tables, pool contents copied to fresh memory
+        w = copy.copy(base)
+        w.k_pool = [t.clone() for t in base.k_pool]
+        w.v_pool = [t.clone() for t in base.v_pool]
+        sets.append(w)
+    sh = binding.shape_of(base, decode_path=path, chunk_blocks=args.chunk_blocks)
+    bt = torch.from_numpy(base.block_tables).to(dev)
+    lens = torch.from_numpy(base.context_lens).to(dev)
+    host_lens = base.context_lens if args.host_lens else None
+    ws = binding.alloc_workspace(sh, dev)
+    outs = [[torch.zeros((base.num_streams, base.num_q_heads, base.head_dim), device=dev)
+             for _ in range(base.layers)] for _ in sets]
+    step_args = [binding.StepArgs(w.q, w.k_new, w.v_new, w.k_pool, w.v_pool, o)
+                 for w, o in zip(sets, outs)]
+
+    def step(i):
+        binding.decode_step(sh, step_args[i % copies], bt, lens, ws, context_lens_host=host_lens)
+
+    # ---- timed region A: the production entry point, whole step
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kv_bytes_step = kv_bytes_layer * base.layers
+    value = kv_bytes_step / (ms_per_step * 1e-3) / 1e9
+
+    # ---- timed region B: same steps, HIP events around the attention kernel of every layer
+    n_ev = args.steps * base.layers
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(n_ev)]
+    for a, b in evs:
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    e = 0
+    for i in range(args.steps):
+        w, o = sets[i % copies], outs[i % copies]
+        for l in range(base.layers):
+            binding.kv_append(sh, w.k_new[l], w.v_new[l], w.k_pool[l], w.v_pool[l], bt, lens)
+            binding.paged_decode(sh, w.q[l], w.k_pool[l], w.v_pool[l], bt, lens, o[l], ws,
+                                 context_lens_host=host_lens, events=evs[e])
+            e += 1
+    torch.cuda.synchronize()
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    achieved = kv_bytes_layer / (kern_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm",
+        "kernel": "decode_valu_kernel" if path == binding.PATH_VALU else "decode_mfma_kernel",
+        "achieved": round(achieved, 1),
+        "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "kernel_ms": round(kern_ms, 4),
+        "bytes_per_launch": kv_bytes_layer,
+        "traffic": MEASURED_TRAFFIC.get(args.workload),
+    }
+
+    # ---- CPU baseline: the oracle as it stands on a bounded sample of streams
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        def bits(t):
+            return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+        qb, kp, vp = bits(base.q[0]), bits(base.k_pool[0]), bits(base.v_pool[0])
+        per_tok = base.kv_bytes_per_token
+
+        def run(n):
+            t = time.perf_counter()
+            oracle.paged_decode(qb, kp, vp, base.block_tables, base.context_lens, base.scale,
+                                num_kv_heads=base.num_kv_heads, streams=(0, n))
+            return time.perf_counter() - t
+
+        probe_n = min(base.num_streams, 8)
+        probe_t = run(probe_n)
+        probe_tok = int(base.context_lens[:probe_n].astype(np.int64).sum())
+        rate = probe_tok / max(probe_t, 1e-6)
+        cum = np.cumsum(base.context_lens.astype(np.int64))
+        n = int(np.searchsorted(cum, rate * args.cpu_seconds) + 1)
+        n = max(probe_n, min(base.num_streams, n))
+        secs = run(n)
+        toks = int(cum[n - 1])
+        cpu = {
+            "value": round(toks * per_tok / secs / 1e9, 4),
+            "unit": "GB/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"fp64 oracle decode of streams [0,{n}) of {base.num_streams} "
+                      f"({toks} tokens, layer 0) in {secs:.2f} s",
+            "cpu_model": cpu_model(),
+            "host_cpus": os.cpu_count(),
+        }
+
+    line = {
+        "metric": METRIC,
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": base.name,
+            "streams": base.num_streams,
+            "q_heads": base.num_q_heads,
+            "kv_heads": base.num_kv_heads,
+            "head_dim": base.head_dim,
+            "layers": base.layers,
+            "total_tokens": base.total_tokens,
+            "kv_bytes_per_step": kv_bytes_step,
+            "pool_copies": copies,
+            "path": args.path,
+            "chunk_blocks": args.chunk_blocks,
+            "host_lens": bool(args.host_lens),
+        },
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "stream_steps_per_s": round(base.num_streams / (ms_per_step * 1e-3), 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

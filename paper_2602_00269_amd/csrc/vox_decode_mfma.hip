@@ -35,6 +35,12 @@ __device__ inline f32x4 mfma(u32x4 a, u32x4 b, f32x4 c) {
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// KV data is read exactly once per step: non-temporal loads keep it from displacing the
+// block tables, queries and partial records in the caches.
+__device__ inline u32x4 stream_load(const uint16_t* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
 __device__ inline uint32_t pack_bf16(float a, float b) {
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   bf16x2 v = {(__bf16)a, (__bf16)b};  // round to nearest even
@@ -102,11 +108,11 @@ __global__ __launch_bounds__(256, (NBUF <= 2 ? 2 : 1)) void decode_mfma_kernel(
     const uint16_t* kp = k_pool + granule_offset(k_second ? id_b : id_a, h, p.Hkv, D) + k_off; \
     const uint16_t* vp = v_pool + granule_offset(v_second ? id_b : id_a, h, p.Hkv, D) + v_off; \
     _Pragma("unroll") for (int kk = 0; kk < KK; ++kk) {                                       \
-      kr[B][kk] = *reinterpret_cast<const u32x4*>(kp + kk * (4 * kBlock * 8));                \
-      kr[B][KK + kk] = *reinterpret_cast<const u32x4*>(kp + kk * (4 * kBlock * 8) + 4 * 8);   \
+      kr[B][kk] = stream_load(kp + kk * (4 * kBlock * 8));                                    \
+      kr[B][KK + kk] = stream_load(kp + kk * (4 * kBlock * 8) + 4 * 8);                       \
     }                                                                                         \
     _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                         \
-        vr[B][nt] = *reinterpret_cast<const u32x4*>(vp + nt * (16 * kBlock));                 \
+        vr[B][nt] = stream_load(vp + nt * (16 * kBlock));                                     \
   }
 
 #pragma unroll

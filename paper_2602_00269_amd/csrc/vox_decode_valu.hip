@@ -37,6 +37,11 @@ __device__ inline float row_sum16(float v) {
   return v;
 }
 
+// KV data is read once per step; non-temporal loads keep it out of the way of reused data.
+__device__ inline u32x4 stream_load(const uint16_t* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
 __device__ inline float dot2(uint32_t a, uint32_t b, float c) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a),
                                          __builtin_bit_cast(bf16x2, b), c, false);
@@ -91,8 +96,8 @@ __global__ __launch_bounds__(256, 2) void decode_valu_kernel(
     const size_t g0 = granule_offset(row[0], h, p.Hkv, D);
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-      kb[i] = *reinterpret_cast<const u32x4*>(k_pool + g0 + (lane + 64 * i) * 8);
-      vb[i] = *reinterpret_cast<const u32x4*>(v_pool + g0 + (lane + 64 * i) * 8);
+      kb[i] = stream_load(k_pool + g0 + (lane + 64 * i) * 8);
+      vb[i] = stream_load(v_pool + g0 + (lane + 64 * i) * 8);
     }
   }
 
@@ -102,8 +107,8 @@ __global__ __launch_bounds__(256, 2) void decode_valu_kernel(
       const size_t g1 = granule_offset(row[b + 1], h, p.Hkv, D);
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
-        kn[i] = *reinterpret_cast<const u32x4*>(k_pool + g1 + (lane + 64 * i) * 8);
-        vn[i] = *reinterpret_cast<const u32x4*>(v_pool + g1 + (lane + 64 * i) * 8);
+        kn[i] = stream_load(k_pool + g1 + (lane + 64 * i) * 8);
+        vn[i] = stream_load(v_pool + g1 + (lane + 64 * i) * 8);
       }
     } else {
 #pragma unroll
