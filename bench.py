@@ -47,7 +47,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--path", default="auto", choices=["auto", "mfma", "valu"])
-    ap.add_argument("--chunk-blocks", type=int, default=0)
+    ap.add_argument("--split-waves", type=int, default=0)
     ap.add_argument("--layers", type=int, default=None, help="override the preset's layer count")
     ap.add_argument("--pool-copies", type=int, default=None,
                     help="distinct pool sets rotated across steps (default: enough to exceed 1 GiB)")
@@ -92,7 +92,7 @@ def main() -> int:
         w.k_pool = [t.clone() for t in base.k_pool]
         w.v_pool = [t.clone() for t in base.v_pool]
         sets.append(w)
-    sh = binding.shape_of(base, decode_path=path, chunk_blocks=args.chunk_blocks)
+    sh = binding.shape_of(base, decode_path=path, split_waves=args.split_waves)
     bt = torch.from_numpy(base.block_tables).to(dev)
     lens = torch.from_numpy(base.context_lens).to(dev)
     host_lens = base.context_lens if args.host_lens else None
@@ -210,7 +210,7 @@ def main() -> int:
             "kv_bytes_per_step": kv_bytes_step,
             "pool_copies": copies,
             "path": args.path,
-            "chunk_blocks": args.chunk_blocks,
+            "split_waves": args.split_waves,
             "host_lens": bool(args.host_lens),
         },
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),

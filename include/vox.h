@@ -54,8 +54,8 @@ extern "C" {
 
 #define VOX_OK 0
 #define VOX_ERR_NULL (-1)      /* a required pointer is NULL */
-#define VOX_ERR_SHAPE (-2)     /* S<=0, Hq%Hkv!=0, G>8, D not in {64,128}, B!=16, P<=0, ... */
-#define VOX_ERR_WORKSPACE (-3) /* workspace smaller than vox_paged_decode_min_workspace_bytes */
+#define VOX_ERR_SHAPE (-2)     /* S<=0, S>8192, Hq%Hkv!=0, G>8, D not in {64,128}, B!=16, P<=0, ... */
+#define VOX_ERR_WORKSPACE (-3) /* workspace too small for the steps of this call */
 #define VOX_ERR_HIP (-4)       /* a launch failed; hipGetLastError() still holds the cause */
 #define VOX_ERR_ARG (-5)       /* a scalar argument is out of range */
 
@@ -74,8 +74,9 @@ typedef struct {
   int32_t max_blocks_per_stream; /* row stride of block_tables */
   float scale;                   /* softmax scale applied to the fp32 dot product */
   int32_t decode_path;           /* VOX_PATH_* */
-  int32_t chunk_blocks;          /* split-K chunk length in blocks; 0 = library heuristic;
-                                    otherwise even and >= 2 */
+  int32_t split_waves;           /* split-K: number of equal ranges (one per wave) the context
+                                    steps of all streams are cut into; 0 = one per wave the
+                                    chip keeps resident (2048), the balanced single round */
 } vox_shape_t;
 
 /*
@@ -103,14 +104,14 @@ int vox_kv_gather(const vox_shape_t* shape, const void* k_pool, const void* v_po
                   const int64_t* row_offsets, void* k_out, void* v_out, void* hip_stream);
 
 /*
- * Workspace for vox_paged_decode / vox_decode_step: split-K work list and the
- * partial (max, sum, accumulator) records.  `_workspace_bytes` is the size at
- * which the library's preferred chunking always fits; any size down to
- * `_min_workspace_bytes` works with coarser chunks.  Both return 0 on a bad shape.
- * The workspace must be 256-byte aligned; its contents are scratch.
+ * Workspace for vox_paged_decode / vox_decode_step: split-K step descriptors and
+ * the partial (max, sum, accumulator) records.  The returned size is enough for
+ * any context_lens the shape admits (every stream at max_blocks_per_stream); a
+ * smaller workspace is accepted when context_lens_host shows that the actual
+ * number of 32-token steps fits.  Returns 0 on a bad shape.  The workspace must
+ * be 256-byte aligned; its contents are scratch.
  */
 size_t vox_paged_decode_workspace_bytes(const vox_shape_t* shape);
-size_t vox_paged_decode_min_workspace_bytes(const vox_shape_t* shape);
 
 /*
  * Paged grouped-query attention decode (second half of the decode step).  For
@@ -123,12 +124,15 @@ size_t vox_paged_decode_min_workspace_bytes(const vox_shape_t* shape);
  * L_s == 0 get out = 0 and lse = -inf.  Inputs are bf16, accumulation fp32.
  *   q                 : [S][Hq][D] bf16
  *   context_lens_host : HOST copy of context_lens or NULL.  When given, the
- *                       launch grid and chunk length are sized from it;
- *                       it must equal the device array.
+ *                       planning launch and the workspace check are sized
+ *                       from it; it must equal the device array.  The
+ *                       attention launch itself never depends on lengths.
  *   out               : [S][Hq][D] fp32
  *   lse               : [S][Hq] fp32 or NULL
- * The context is split into chunks (split-K); each chunk's partial softmax
- * state goes to the workspace and a merge kernel combines them.
+ * Split-K: the 32-token steps of all (stream, kv head) pairs are laid on one
+ * axis and cut into equal ranges, one per wave; each run of a pair inside a
+ * range leaves a partial softmax state in the workspace and a merge kernel
+ * combines them.
  */
 int vox_paged_decode(const vox_shape_t* shape, const void* q, const void* k_pool,
                      const void* v_pool, const int32_t* block_tables,
@@ -151,7 +155,7 @@ int vox_paged_decode_profiled(const vox_shape_t* shape, const void* q, const voi
  * Whole decode step over `num_layers` backbone layers that share block_tables
  * and context_lens (one allocation per stream, a pool pair per layer): for
  * l = 0..num_layers-1 in order, vox_kv_append then vox_paged_decode on layer l's
- * buffers.  The split-K work list is built once and reused by every layer.
+ * buffers.  The split-K step descriptors are built once and reused by every layer.
  * q, k_new, v_new, k_pool, v_pool, out are HOST arrays of num_layers device
  * pointers with the per-layer shapes documented above.
  */

@@ -31,7 +31,7 @@ class VoxShape(ctypes.Structure):
         ("max_blocks_per_stream", ctypes.c_int32),
         ("scale", ctypes.c_float),
         ("decode_path", ctypes.c_int32),
-        ("chunk_blocks", ctypes.c_int32),
+        ("split_waves", ctypes.c_int32),
     ]
 
 
@@ -62,8 +62,6 @@ def load() -> ctypes.CDLL:
     lib.vox_kv_gather.restype = ctypes.c_int
     lib.vox_paged_decode_workspace_bytes.argtypes = [sp]
     lib.vox_paged_decode_workspace_bytes.restype = ctypes.c_size_t
-    lib.vox_paged_decode_min_workspace_bytes.argtypes = [sp]
-    lib.vox_paged_decode_min_workspace_bytes.restype = ctypes.c_size_t
     lib.vox_paged_decode.argtypes = [sp] + [vp] * 9 + [ctypes.c_size_t, vp]
     lib.vox_paged_decode.restype = ctypes.c_int
     lib.vox_paged_decode_profiled.argtypes = [sp] + [vp] * 9 + [ctypes.c_size_t, vp, vp, vp]
@@ -82,15 +80,15 @@ def strerror(code: int) -> str:
 
 def make_shape(num_streams, num_q_heads, num_kv_heads, head_dim, num_blocks,
                max_blocks_per_stream, scale, block_size=16, decode_path=PATH_AUTO,
-               chunk_blocks=0) -> VoxShape:
+               split_waves=0) -> VoxShape:
     return VoxShape(num_streams, num_q_heads, num_kv_heads, head_dim, block_size, num_blocks,
-                    max_blocks_per_stream, float(scale), decode_path, chunk_blocks)
+                    max_blocks_per_stream, float(scale), decode_path, split_waves)
 
 
-def shape_of(w, decode_path=PATH_AUTO, chunk_blocks=0) -> VoxShape:
+def shape_of(w, decode_path=PATH_AUTO, split_waves=0) -> VoxShape:
     """VoxShape of a ``synth.Workload``."""
     return make_shape(w.num_streams, w.num_q_heads, w.num_kv_heads, w.head_dim, w.num_blocks,
-                      w.max_blocks_per_stream, w.scale, w.block_size, decode_path, chunk_blocks)
+                      w.max_blocks_per_stream, w.scale, w.block_size, decode_path, split_waves)
 
 
 def _dev(t: Optional[torch.Tensor], dtype, what: str, optional=False):
@@ -145,13 +143,6 @@ def paged_decode_workspace_bytes(shape) -> int:
     n = load().vox_paged_decode_workspace_bytes(ctypes.byref(shape))
     if n == 0:
         raise VoxError(-2, "vox_paged_decode_workspace_bytes")
-    return int(n)
-
-
-def paged_decode_min_workspace_bytes(shape) -> int:
-    n = load().vox_paged_decode_min_workspace_bytes(ctypes.byref(shape))
-    if n == 0:
-        raise VoxError(-2, "vox_paged_decode_min_workspace_bytes")
     return int(n)
 
 

@@ -5,34 +5,58 @@ namespace vox {
 namespace {
 
 // ---------------------------------------------------------------------------------------
-// KV append: one thread per (stream, kv head, 8-dim slice).  The K slice of one token is a
-// contiguous 16 bytes in the K pool; the V slice is eight 2-byte slots 32 bytes apart.
-__global__ __launch_bounds__(256) void kv_append_kernel(Params p, const uint4* __restrict__ k_new,
-                                                        const uint4* __restrict__ v_new,
+// KV append: one wave per (stream, kv head).  A token's K row is 16-byte slices 256 bytes
+// apart and its V row is 2-byte slots 32 bytes apart, so storing only those bytes would leave
+// every cache line of the granule partially written, and lines in that state are slow to read
+// back by the attention kernel that follows.  The wave therefore reads the two granules of the
+// token's block, replaces the token's slots in registers and stores both granules back whole,
+// 16 bytes per lane: every line is written in full with bit-identical surroundings.  A block
+// that receives an append belongs to exactly one stream, so nothing else writes it meanwhile.
+typedef uint32_t au32x4 __attribute__((ext_vector_type(4)));
+
+template <int D>
+__global__ __launch_bounds__(256) void kv_append_kernel(Params p, const uint16_t* __restrict__ k_new,
+                                                        const uint16_t* __restrict__ v_new,
                                                         uint16_t* __restrict__ k_pool,
                                                         uint16_t* __restrict__ v_pool,
                                                         const int32_t* __restrict__ bt,
                                                         const int32_t* __restrict__ lens) {
-  const int slices = p.D >> 3;
-  const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (x >= (int64_t)p.S * p.Hkv * slices) return;
-  const int o = (int)(x % slices);
-  const int h = (int)((x / slices) % p.Hkv);
-  const int s = (int)(x / ((int64_t)slices * p.Hkv));
+  constexpr int NL = D / 32;  // 16-byte pieces per lane per granule
+  const int lane = threadIdx.x & (kWave - 1);
+  const int sigma = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
+  if (sigma >= p.S * p.Hkv) return;
+  const int s = sigma / p.Hkv, h = sigma % p.Hkv;
   const int L = lens[s];
   if (L <= 0) return;
   const int pos = L - 1;
   const int64_t blk = bt[(int64_t)s * p.max_nb + (pos >> 4)];
   const int t = pos & (kBlock - 1);
-  const size_t g = granule_offset(blk, h, p.Hkv, p.D);
-  const uint4 kv = k_new[x];
-  *reinterpret_cast<uint4*>(k_pool + g + k_elem(t, o * 8)) = kv;
-  const uint4 vv = v_new[x];
-  const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
+  const size_t g = granule_offset(blk, h, p.Hkv, D);
+  const uint16_t* krow = k_new + (size_t)sigma * D;
+  const uint16_t* vrow = v_new + (size_t)sigma * D;
+  au32x4 kr[NL], vr[NL];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const uint16_t bits = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
-    v_pool[g + v_elem(t, o * 8 + e)] = bits;
+  for (int j = 0; j < NL; ++j) {
+    kr[j] = *reinterpret_cast<const au32x4*>(k_pool + g + (lane + kWave * j) * 8);
+    vr[j] = *reinterpret_cast<const au32x4*>(v_pool + g + (lane + kWave * j) * 8);
+  }
+#pragma unroll
+  for (int j = 0; j < NL; ++j) {
+    // K piece lane + 64 j holds token lane % 16, dims 8 * (lane / 16 + 4 j) .. + 8
+    if ((lane & 15) == t)
+      kr[j] = *reinterpret_cast<const au32x4*>(krow + ((lane >> 4) + 4 * j) * 8);
+    // V piece lane + 64 j holds dim (lane + 64 j) / 2, tokens 8 * (lane % 2) .. + 8
+    if ((lane & 1) == (t >> 3)) {
+      const uint32_t bits = vrow[(lane + kWave * j) >> 1];
+      const int e = t & 7;
+      const uint32_t old = vr[j][e >> 1];
+      vr[j][e >> 1] = (e & 1) ? ((old & 0x0000FFFFu) | (bits << 16)) : ((old & 0xFFFF0000u) | bits);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NL; ++j) {
+    *reinterpret_cast<au32x4*>(k_pool + g + (lane + kWave * j) * 8) = kr[j];
+    *reinterpret_cast<au32x4*>(v_pool + g + (lane + kWave * j) * 8) = vr[j];
   }
 }
 
@@ -76,73 +100,92 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(Params p, const uint16_t
 }
 
 // ---------------------------------------------------------------------------------------
-// Plan: per stream, n = ceil(nb / chunk) items of equal even length ceil(nb / n) rounded up to
-// a multiple of two blocks (the last item takes the remainder).  One workgroup; streams are
-// scanned 1024 at a time.
-__global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ lens, int S,
-                                                    int chunk, int capacity,
-                                                    int32_t* __restrict__ header,
-                                                    int32_t* __restrict__ first_item,
-                                                    Item* __restrict__ items) {
-  __shared__ int scan[1024];
-  __shared__ int carry;
-  __shared__ int overflow;
+// Plan: writes the step prefix, the header (N, Q, W) and one descriptor per global step.
+// Every workgroup rebuilds the exclusive scan of n_s = ceil(ceil(L_s/16)/2) in LDS (S is
+// small), then its threads expand kPlanStepsPerGroup global steps: binary search for the
+// stream, then head and step inside the segment.  Workgroup 0 also publishes the scan.
+constexpr int kPlanThreads = 256;
+constexpr int kPlanStepsPerGroup = 2048;
+constexpr int kPlanMaxStreams = kMaxStreams;  // LDS-resident prefix
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(
+    Params p, const int32_t* __restrict__ bt, const int32_t* __restrict__ lens, int waves,
+    int64_t desc_capacity, int32_t* __restrict__ header, int32_t* __restrict__ step_prefix,
+    int4* __restrict__ desc) {
+  __shared__ int prefix[kPlanMaxStreams + 1];
+  __shared__ int wsum[kPlanThreads];
   const int tid = threadIdx.x;
-  if (tid == 0) {
-    carry = 0;
-    overflow = 0;
+  const int S = p.S;
+  // each thread scans a contiguous slice of streams, then the slice totals are scanned
+  const int per = (S + kPlanThreads - 1) / kPlanThreads;
+  const int lo = min(S, tid * per), hi = min(S, lo + per);
+  int run = 0;
+  for (int s = lo; s < hi; ++s) {
+    const int L = lens[s];
+    const int nb = L > 0 ? (L + kBlock - 1) / kBlock : 0;
+    prefix[s] = run;
+    run += (nb + 1) >> 1;
   }
+  wsum[tid] = run;
   __syncthreads();
-  for (int base = 0; base < S; base += 1024) {
-    const int s = base + tid;
-    int nb = 0, n = 0, len = 0;
-    if (s < S) {
-      const int L = lens[s];
-      nb = L > 0 ? (L + kBlock - 1) / kBlock : 0;
-      n = (nb + chunk - 1) / chunk;
-      if (n) len = (((nb + n - 1) / n) + 1) & ~1;
-    }
-    scan[tid] = n;
+  for (int off = 1; off < kPlanThreads; off <<= 1) {
+    const int v = tid >= off ? wsum[tid - off] : 0;
     __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {
-      const int v = tid >= off ? scan[tid - off] : 0;
-      __syncthreads();
-      scan[tid] += v;
-      __syncthreads();
-    }
-    const int first = carry + scan[tid] - n;
-    if (s < S) {
-      first_item[s] = min(first, capacity);
-      for (int c = 0; c < n; ++c) {
-        const int idx = first + c;
-        if (idx < capacity) {
-          Item it;
-          it.stream = s;
-          it.first_block = c * len;
-          it.nblocks = min(len, nb - c * len);
-          it.pad = 0;
-          items[idx] = it;
-        } else {
-          overflow = 1;
-        }
-      }
-    }
-    __syncthreads();
-    if (tid == 1023) carry += scan[1023];
+    wsum[tid] += v;
     __syncthreads();
   }
-  if (tid == 0) {
-    first_item[S] = min(carry, capacity);
-    header[0] = min(carry, capacity);
-    header[1] = chunk;
-    header[2] = overflow;
+  const int before = wsum[tid] - run;
+  for (int s = lo; s < hi; ++s) prefix[s] += before;
+  if (tid == kPlanThreads - 1) prefix[S] = wsum[tid];
+  __syncthreads();
+
+  const int64_t n_all = (int64_t)prefix[S] * p.Hkv;
+  const int64_t N = min(n_all, desc_capacity);
+  const int Q = (int)max((int64_t)1, (N + waves - 1) / waves);
+  if (blockIdx.x == 0) {
+    for (int s = tid; s <= S; s += kPlanThreads) step_prefix[s] = prefix[s];
+    if (tid == 0) {
+      header[kHdrSteps] = (int)N;
+      header[kHdrPerWave] = Q;
+      header[kHdrWaves] = waves;
+      header[kHdrOverflow] = n_all > desc_capacity;
+    }
+  }
+
+  const int64_t x_begin = (int64_t)blockIdx.x * kPlanStepsPerGroup;
+  for (int64_t x = x_begin + tid; x < min(N, x_begin + kPlanStepsPerGroup); x += kPlanThreads) {
+    // largest s with Hkv * prefix[s] <= x (streams with n_s == 0 share a prefix and are skipped)
+    int a = 0, b = S;
+    while (b - a > 1) {
+      const int mid = (a + b) >> 1;
+      if ((int64_t)prefix[mid] * p.Hkv <= x)
+        a = mid;
+      else
+        b = mid;
+    }
+    const int s = a;
+    const int n = prefix[s + 1] - prefix[s];
+    const int r = (int)(x - (int64_t)prefix[s] * p.Hkv);
+    const int h = r / n, st = r - h * n;
+    const int L = lens[s];
+    const int nb = (L + kBlock - 1) / kBlock;
+    const int32_t* row = bt + (size_t)s * p.max_nb;
+    const int ida = row[2 * st];
+    const int idb = (2 * st + 1 < nb) ? row[2 * st + 1] : ida;
+    const int ntok = min(kStepTokens, L - kStepTokens * st);
+    int meta = ntok;
+    if (st == 0 || x % Q == 0) meta |= kMetaFirst;
+    if (st == n - 1 || x % Q == Q - 1 || x == N - 1) meta |= kMetaLast;
+    if (st == n - 1) meta |= kMetaTail;
+    desc[x] = make_int4(ida * p.Hkv + h, idb * p.Hkv + h, meta, s * p.Hkv + h);
   }
 }
 
 // ---------------------------------------------------------------------------------------
-// Merge: one wave per (stream, q head).  Lanes hold the chunks' (max, sum) records; the global
-// max and the rescaled sum are wave reductions; the accumulators are then combined with each
-// lane owning D/64 output dims.
+// Merge: one wave per (stream, q head).  The runs of segment sigma lie in the ranges
+// w0 = P/Q .. w1 = (P+n-1)/Q (P = first global step of the segment); run j is slot w0+j+sigma.
+// Lanes hold the runs' (max, sum) records; the global max and the rescaled sum are wave
+// reductions; the accumulators are then combined with each lane owning D/64 output dims.
 __device__ inline float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
@@ -155,7 +198,8 @@ __device__ inline float wave_sum(float v) {
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void merge_kernel(Params p, const int32_t* __restrict__ first_item,
+__global__ __launch_bounds__(256) void merge_kernel(Params p, const int32_t* __restrict__ header,
+                                                    const int32_t* __restrict__ step_prefix,
                                                     const float2* __restrict__ pml,
                                                     const float* __restrict__ pacc,
                                                     float* __restrict__ out,
@@ -165,8 +209,20 @@ __global__ __launch_bounds__(256) void merge_kernel(Params p, const int32_t* __r
   const int w = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
   if (w >= p.S * p.Hq) return;
   const int s = w / p.Hq, i = w % p.Hq;
-  const int f0 = first_item[s];
-  const int n = first_item[s + 1] - f0;
+  const int h = i / p.G, g = i % p.G;
+  const int sigma = s * p.Hkv + h;
+  const int Q = header[kHdrPerWave];
+  const int64_t N = header[kHdrSteps];
+  const int nseg = step_prefix[s + 1] - step_prefix[s];
+  const int64_t first = (int64_t)step_prefix[s] * p.Hkv + (int64_t)h * nseg;
+  int n = 0;         // number of runs
+  int64_t slot0 = 0;  // slot of run 0
+  if (nseg > 0 && first < N) {
+    const int64_t last = min(N, first + nseg) - 1;
+    const int64_t w0 = first / Q, w1 = last / Q;
+    n = (int)(w1 - w0 + 1);
+    slot0 = w0 + sigma;
+  }
   float m_run = -INFINITY, l_run = 0.f;
   float acc[DPL];
 #pragma unroll
@@ -174,7 +230,7 @@ __global__ __launch_bounds__(256) void merge_kernel(Params p, const int32_t* __r
   for (int c0 = 0; c0 < n; c0 += kWave) {
     const int c = c0 + lane;
     float2 ml = make_float2(-INFINITY, 0.f);
-    if (c < n) ml = pml[(size_t)(f0 + c) * p.Hq + i];
+    if (c < n) ml = pml[(size_t)(slot0 + c) * p.G + g];
     const float m_new = fmaxf(m_run, wave_max(ml.x));
     const float wgt = (ml.x == -INFINITY) ? 0.f : exp2f(ml.x - m_new);
     const float alpha = (m_run == -INFINITY) ? 0.f : exp2f(m_run - m_new);
@@ -184,7 +240,7 @@ __global__ __launch_bounds__(256) void merge_kernel(Params p, const int32_t* __r
     const int cnt = min(kWave, n - c0);
     for (int j = 0; j < cnt; ++j) {
       const float wj = __shfl(wgt, j);
-      const float* src = pacc + ((size_t)(f0 + c0 + j) * p.Hq + i) * D + lane * DPL;
+      const float* src = pacc + ((size_t)(slot0 + c0 + j) * p.G + g) * D + lane * DPL;
       if (DPL == 2) {
         const float2 a = *reinterpret_cast<const float2*>(src);
         acc[0] += wj * a.x;
@@ -209,10 +265,15 @@ __global__ __launch_bounds__(256) void merge_kernel(Params p, const int32_t* __r
 hipError_t launch_kv_append(const Params& p, const void* k_new, const void* v_new, void* k_pool,
                             void* v_pool, const int32_t* bt, const int32_t* lens,
                             hipStream_t st) {
-  const int64_t n = (int64_t)p.S * p.Hkv * (p.D / 8);
-  const unsigned grid = (unsigned)((n + 255) / 256);
-  hipLaunchKernelGGL(kv_append_kernel, dim3(grid), dim3(256), 0, st, p, (const uint4*)k_new,
-                     (const uint4*)v_new, (uint16_t*)k_pool, (uint16_t*)v_pool, bt, lens);
+  const unsigned grid = (unsigned)(((int64_t)p.S * p.Hkv + kWavesPerGroup - 1) / kWavesPerGroup);
+  if (p.D == 128)
+    hipLaunchKernelGGL(kv_append_kernel<128>, dim3(grid), dim3(256), 0, st, p,
+                       (const uint16_t*)k_new, (const uint16_t*)v_new, (uint16_t*)k_pool,
+                       (uint16_t*)v_pool, bt, lens);
+  else
+    hipLaunchKernelGGL(kv_append_kernel<64>, dim3(grid), dim3(256), 0, st, p,
+                       (const uint16_t*)k_new, (const uint16_t*)v_new, (uint16_t*)k_pool,
+                       (uint16_t*)v_pool, bt, lens);
   return hipGetLastError();
 }
 
@@ -227,22 +288,27 @@ hipError_t launch_kv_gather(const Params& p, const void* k_pool, const void* v_p
   return hipGetLastError();
 }
 
-hipError_t launch_plan(const Params& p, const int32_t* lens, int chunk_blocks, int capacity,
-                       int32_t* header, int32_t* first_item, Item* items, hipStream_t st) {
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, lens, p.S, chunk_blocks, capacity,
-                     header, first_item, items);
+hipError_t launch_plan(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
+                       int64_t desc_capacity, int64_t max_steps, int32_t* header,
+                       int32_t* step_prefix, int4* desc, hipStream_t st) {
+  if (p.S > kPlanMaxStreams) return hipErrorInvalidValue;
+  const unsigned grid =
+      (unsigned)max((int64_t)1, (max_steps + kPlanStepsPerGroup - 1) / kPlanStepsPerGroup);
+  hipLaunchKernelGGL(plan_kernel, dim3(grid), dim3(kPlanThreads), 0, st, p, bt, lens, waves,
+                     desc_capacity, header, step_prefix, desc);
   return hipGetLastError();
 }
 
-hipError_t launch_merge(const Params& p, const int32_t* first_item, const float2* partial_ml,
-                        const float* partial_acc, float* out, float* lse, hipStream_t st) {
+hipError_t launch_merge(const Params& p, const int32_t* header, const int32_t* step_prefix,
+                        const float2* partial_ml, const float* partial_acc, float* out,
+                        float* lse, hipStream_t st) {
   const unsigned grid = (unsigned)(((int64_t)p.S * p.Hq + kWavesPerGroup - 1) / kWavesPerGroup);
   if (p.D == 128)
-    hipLaunchKernelGGL(merge_kernel<128>, dim3(grid), dim3(256), 0, st, p, first_item, partial_ml,
-                       partial_acc, out, lse);
+    hipLaunchKernelGGL(merge_kernel<128>, dim3(grid), dim3(256), 0, st, p, header, step_prefix,
+                       partial_ml, partial_acc, out, lse);
   else
-    hipLaunchKernelGGL(merge_kernel<64>, dim3(grid), dim3(256), 0, st, p, first_item, partial_ml,
-                       partial_acc, out, lse);
+    hipLaunchKernelGGL(merge_kernel<64>, dim3(grid), dim3(256), 0, st, p, header, step_prefix,
+                       partial_ml, partial_acc, out, lse);
   return hipGetLastError();
 }
 

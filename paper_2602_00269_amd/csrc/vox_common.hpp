@@ -1,5 +1,16 @@
 // Shared declarations of the HIP library: kernel parameter block, workspace map and the
 // cache-layout index helpers.  gfx950 only.
+//
+// Split-K decomposition.  The context of stream s is walked in steps of 32 tokens (two KV
+// blocks); n_s = ceil(ceil(L_s / 16) / 2).  Segment sigma = s * Hkv + h owns n_s steps.  All
+// segments are laid end to end on one axis of N = Hkv * sum_s n_s global steps, and that axis
+// is cut into W equal ranges of Q = ceil(N / W) steps, one per wave.  A wave therefore reads the
+// same number of KV bytes as every other wave whatever the length mix, and a range may cover
+// the tail of one segment, several whole short segments and the head of another.  Every
+// maximal run of one segment inside one range yields one partial record (max, sum,
+// accumulator); runs are numbered along the axis, so the record of the run of segment sigma in
+// range w is slot w + sigma.  The merge kernel recomputes which ranges a segment crosses from
+// the prefix sums alone.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -12,27 +23,35 @@ namespace vox {
 constexpr int kBlock = 16;         // tokens per KV block
 constexpr int kWave = 64;          // lanes per wavefront
 constexpr int kWavesPerGroup = 4;  // decode / merge workgroups are 4 independent waves
-constexpr int kMaxChunkBlocks = 64;  // a wave keeps its chunk's block ids in one VGPR
-constexpr int kStepTokens = 32;      // tokens consumed per MFMA step (two blocks)
+constexpr int kStepTokens = 32;    // tokens consumed per step (two blocks)
+constexpr int kMaxStreams = 8192;  // the plan kernel keeps the per-stream prefix in LDS
+constexpr int kDesignWaveSlots = 256 * 2 * kWavesPerGroup;  // 256 CUs x 2 workgroups x 4 waves
 
-// One split-K work item: `nblocks` consecutive logical blocks of one stream.  Each item is
-// processed once per kv head; wave-item id = item * Hkv + h.
-struct Item {
-  int32_t stream;
-  int32_t first_block;
-  int32_t nblocks;
-  int32_t pad;
-};
+// Step descriptor written by the plan kernels, one per global step (16 bytes).
+//   x: granule index (block id * Hkv + h) of the step's first block
+//   y: granule index of its second block (= x when the stream has no such block)
+//   z: bits 0..5 valid tokens in the step (1..32), bit 8 first step of a run, bit 9 last,
+//      bit 10 last step of the stream
+//   w: segment index sigma
+constexpr int kMetaFirst = 1 << 8;
+constexpr int kMetaLast = 1 << 9;
+constexpr int kMetaTail = 1 << 10;  // last step of its stream: holds the block appended to
+constexpr int kMetaTokMask = 63;
+
+// header words
+constexpr int kHdrSteps = 0;     // N
+constexpr int kHdrPerWave = 1;   // Q
+constexpr int kHdrWaves = 2;     // W
+constexpr int kHdrOverflow = 3;  // set when N exceeded the descriptor capacity
 
 // Workspace map (byte offsets from the 256-byte aligned workspace base).
 struct Workspace {
-  size_t header;       // int32[64]: [0] number of items, [1] chunk_blocks, [2] overflow flag
-  size_t first_item;   // int32[S + 1]: exclusive scan of per-stream item counts
-  size_t items;        // Item[capacity]
-  size_t partial_ml;   // float2[capacity * Hq]: (running max in log2 units, sum)
-  size_t partial_acc;  // float[capacity * Hq * D]
+  size_t header;       // int32[64]
+  size_t step_prefix;  // int32[S + 1]: exclusive scan of n_s
+  size_t desc;         // int4[desc_capacity]
+  size_t partial_ml;   // float2[slots * G]: (running max in log2 units, sum)
+  size_t partial_acc;  // float[slots * G * D]
   size_t total;
-  int32_t capacity;    // items the map has room for
 };
 
 // Everything a kernel needs besides its buffers.
@@ -57,17 +76,17 @@ hipError_t launch_kv_append(const Params& p, const void* k_new, const void* v_ne
 hipError_t launch_kv_gather(const Params& p, const void* k_pool, const void* v_pool,
                             const int32_t* bt, const int32_t* lens, const int64_t* row_offsets,
                             void* k_out, void* v_out, hipStream_t st);
-hipError_t launch_plan(const Params& p, const int32_t* lens, int chunk_blocks, int capacity,
-                       int32_t* header, int32_t* first_item, Item* items, hipStream_t st);
-hipError_t launch_decode_mfma(const Params& p, int max_wave_items, const void* q,
-                              const void* k_pool, const void* v_pool, const int32_t* bt,
-                              const int32_t* lens, const int32_t* header, const Item* items,
+hipError_t launch_plan(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
+                       int64_t desc_capacity, int64_t max_steps, int32_t* header,
+                       int32_t* step_prefix, int4* desc, hipStream_t st);
+hipError_t launch_decode_mfma(const Params& p, int waves, const void* q, const void* k_pool,
+                              const void* v_pool, const int32_t* header, const int4* desc,
                               float2* partial_ml, float* partial_acc, hipStream_t st);
-hipError_t launch_decode_valu(const Params& p, int max_wave_items, const void* q,
-                              const void* k_pool, const void* v_pool, const int32_t* bt,
-                              const int32_t* lens, const int32_t* header, const Item* items,
+hipError_t launch_decode_valu(const Params& p, int waves, const void* q, const void* k_pool,
+                              const void* v_pool, const int32_t* header, const int4* desc,
                               float2* partial_ml, float* partial_acc, hipStream_t st);
-hipError_t launch_merge(const Params& p, const int32_t* first_item, const float2* partial_ml,
-                        const float* partial_acc, float* out, float* lse, hipStream_t st);
+hipError_t launch_merge(const Params& p, const int32_t* header, const int32_t* step_prefix,
+                        const float2* partial_ml, const float* partial_acc, float* out,
+                        float* lse, hipStream_t st);
 
 }  // namespace vox

@@ -1,0 +1,109 @@
+// The split-K decode kernel skeleton shared by the MFMA and VALU arithmetic.
+//
+// A wave owns the global steps [w*Q, min(N, (w+1)*Q)) and walks them as one flat software
+// pipeline: the K/V loads of step i + NBUF are issued while step i is computed, across segment
+// boundaries, so the load queue never drains inside a wave.  Step descriptors are read 64 at a
+// time into registers (one per lane) and broadcast with v_readlane; two such windows are kept
+// so the load cursor may run ahead of the compute cursor into the next window.  When a run
+// of a segment ends inside the range its partial record is stored and the accumulators are
+// reset; the query rows of the next run are fetched one step ahead.
+//
+// `Math` supplies the registers and arithmetic of one step:
+//   struct Q (query rows in flight), struct Regs (one step of K/V), struct State;
+//   Math(lane, params); load_q(Q&, q, sigma); install_q(State&, Q&);
+//   issue(Regs&, k_pool, v_pool, ga, gb); reset(State&); compute(State&, Regs&, ntok);
+//   finish(State&, slot, pml, pacc);
+#pragma once
+
+#include "vox_common.hpp"
+
+namespace vox {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// KV data is read exactly once per step: non-temporal loads keep it from displacing the
+// descriptors, queries and partial records in the caches.
+template <bool STREAM>
+__device__ inline u32x4 kv_load(const uint16_t* p) {
+  if (STREAM) return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return *reinterpret_cast<const u32x4*>(p);
+}
+
+template <class Math>
+__global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
+    Params p, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_pool,
+    const uint16_t* __restrict__ v_pool, const int32_t* __restrict__ header,
+    const int4* __restrict__ desc, float2* __restrict__ pml, float* __restrict__ pacc) {
+  constexpr int NBUF = Math::kBuffers;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6));
+  const int N = header[kHdrSteps], Q = header[kHdrPerWave];
+  const int64_t x0 = (int64_t)w * Q;
+  if (x0 >= N) return;
+  const int nsteps = (int)min((int64_t)Q, (int64_t)N - x0);
+
+  const u32x4* dbase = reinterpret_cast<const u32x4*>(desc) + x0;
+  u32x4 dw0 = dbase[min(lane, nsteps - 1)];
+  u32x4 dw1 = dbase[min(kWave + lane, nsteps - 1)];
+#define VOX_DESC(I, C) \
+  __builtin_amdgcn_readlane((int)((((I) & kWave) ? dw1 : dw0).C), (I) & (kWave - 1))
+
+  Math math(lane, p);
+  typename Math::State st;
+  typename Math::Q qnext;
+  typename Math::Regs ring[NBUF];
+  math.load_q(qnext, q, VOX_DESC(0, w));
+  math.reset(st);
+#pragma unroll
+  for (int b = 0; b < NBUF; ++b) {
+    const bool more = b < nsteps;
+    math.template issue<true>(ring[b], k_pool, v_pool, more ? VOX_DESC(b, x) : 0,
+                              more ? VOX_DESC(b, y) : 0);
+  }
+
+  // One step of the pipeline.  In the steady-state loop every step refills its ring slot
+  // unconditionally: a load issued under a run-time condition makes the compiler's wait-count
+  // bookkeeping assume it was not issued and wait for every younger load, which serialises
+  // memory and arithmetic.  Refills past the end of the range are pointed at granule 0 of the
+  // pools (always mapped, cache resident after the first touch) and never consumed.
+#define VOX_STEP(I, B, REFILL)                                                             \
+  {                                                                                        \
+    const int i = (I);                                                                     \
+    const int meta = VOX_DESC(i, z);                                                       \
+    const int sigma = VOX_DESC(i, w);                                                      \
+    if (meta & kMetaFirst) {                                                               \
+      math.reset(st);                                                                      \
+      math.install_q(st, qnext);                                                           \
+    }                                                                                      \
+    math.compute(st, ring[B], meta & kMetaTokMask);                                        \
+    if (i + 1 < nsteps && (VOX_DESC(i + 1, z) & kMetaFirst))                               \
+      math.load_q(qnext, q, VOX_DESC(i + 1, w));                                           \
+    if (REFILL) {                                                                          \
+      const bool more = i + NBUF < nsteps;                                                 \
+      const int ga = more ? VOX_DESC(i + NBUF, x) : 0;                                     \
+      const int gb = more ? VOX_DESC(i + NBUF, y) : 0;                                     \
+      math.template issue<true>(ring[B], k_pool, v_pool, ga, gb);                          \
+    }                                                                                      \
+    if (meta & kMetaLast) math.finish(st, w + sigma, pml, pacc);                           \
+    if ((i & (kWave - 1)) == kWave - 1) { /* window i>>6 is spent: fetch window (i>>6)+2 */ \
+      const u32x4 nw = dbase[min(i + 1 + kWave + lane, nsteps - 1)];                       \
+      if (i & kWave)                                                                       \
+        dw1 = nw;                                                                          \
+      else                                                                                 \
+        dw0 = nw;                                                                          \
+    }                                                                                      \
+  }
+
+  int i0 = 0;
+  for (; i0 + NBUF <= nsteps; i0 += NBUF) {  // whole groups of NBUF steps, no conditions
+#pragma unroll
+    for (int b = 0; b < NBUF; ++b) VOX_STEP(i0 + b, b, true)
+  }
+#pragma unroll
+  for (int b = 0; b < NBUF - 1; ++b)  // fewer than NBUF steps remain; their data is in flight
+    if (i0 + b < nsteps) VOX_STEP(i0 + b, b, false)
+#undef VOX_STEP
+#undef VOX_DESC
+}
+
+}  // namespace vox

@@ -1,20 +1,21 @@
-// Paged GQA decode on the vector ALU only (no matrix cores).  Kept as the measured alternative
-// to the MFMA kernel; both consume the same work list and write the same partial records.
+// Paged GQA decode arithmetic on the vector ALU only (no matrix cores).  Kept as the measured
+// alternative to the MFMA arithmetic; both run inside the same split-K kernel skeleton.
 //
-// One wave per (item, kv head).  Per 16-token block:
+// A step's two 16-token blocks are processed one after the other.  Per block:
 //   K granule [D/8][16][8]: lane l reads 16 bytes at (l + 64*kk)*16, i.e. token l%16 and the
 //     8-dim slices l/16 + 4*kk.  Partial dot products (v_dot2_f32_bf16) of the G query heads
-//     are summed over the four lane groups, so every group ends with the 16 scores.
+//     are summed over the four lane groups, so every group ends with the 16 scores.  The G
+//     query rows of the run live in a wave-private LDS tile (they are contiguous in q) and
+//     are read back with broadcast 16-byte reads.
 //   online softmax per head with a 16-lane DPP max; probabilities go through a wave-private
 //     LDS row so each lane can read the 8 it needs for its V slice.
 //   V granule [D][16]: lane l reads 16 bytes at (l + 64*i)*16 = dim l/2 + 32*i, tokens
-//     8*(l%2) .. +8; fp32 FMAs into acc[g][i]; lane pairs are summed at the end.
-#include "vox_common.hpp"
+//     8*(l%2) .. +8; fp32 FMAs into acc[g][i]; lane pairs are summed when a run ends.
+#include "vox_decode_core.hpp"
 
 namespace vox {
 namespace {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 template <int CTRL>
@@ -37,11 +38,6 @@ __device__ inline float row_sum16(float v) {
   return v;
 }
 
-// KV data is read once per step; non-temporal loads keep it out of the way of reused data.
-__device__ inline u32x4 stream_load(const uint16_t* p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-}
-
 __device__ inline float dot2(uint32_t a, uint32_t b, float c) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a),
                                          __builtin_bit_cast(bf16x2, b), c, false);
@@ -50,100 +46,118 @@ __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
 template <int D, int G>
-__global__ __launch_bounds__(256, 2) void decode_valu_kernel(
-    Params p, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_pool,
-    const uint16_t* __restrict__ v_pool, const int32_t* __restrict__ bt,
-    const int32_t* __restrict__ lens, const int32_t* __restrict__ header,
-    const Item* __restrict__ items, float2* __restrict__ pml, float* __restrict__ pacc) {
-  constexpr int NL = D / 32;  // 16-byte loads per lane per granule
-  __shared__ float p_lds[kWavesPerGroup][G][kBlock];
+struct ValuMath {
+  static constexpr int kBuffers = 2;
+  static constexpr int kMinWavesPerSimd = 2;
+  static constexpr int NL = D / 32;  // 16-byte loads per lane per granule
 
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wv = threadIdx.x >> 6;
-  const int wid = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerGroup + wv);
-  if (wid >= header[0] * p.Hkv) return;
-  const int item = wid / p.Hkv, h = wid % p.Hkv;
-  const Item it = items[item];
-  const int s = it.stream;
-  const int tok_end = min(lens[s], (it.first_block + it.nblocks) * kBlock);
-  const int t = lane & 15, grp = lane >> 4, half = lane & 1;
+  static constexpr int QCHUNKS = G * D / 8;             // 16-byte pieces of the G query rows
+  static constexpr int QPL = (QCHUNKS + kWave - 1) / kWave;  // pieces per lane
 
-  uint32_t qr[G][NL][4];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int kk = 0; kk < NL; ++kk) {
-      const u32x4 v = *reinterpret_cast<const u32x4*>(
-          q + ((size_t)s * p.Hq + h * G + g) * D + (grp + 4 * kk) * 8);
-      qr[g][kk][0] = v.x;
-      qr[g][kk][1] = v.y;
-      qr[g][kk][2] = v.z;
-      qr[g][kk][3] = v.w;
-    }
+  struct Q {
+    u32x4 r[QPL];
+  };
+  struct Regs {
+    u32x4 k[2][NL], v[2][NL];
+  };
+  struct State {
+    float m[G], l[G], acc[G][NL];
+  };
 
-  float m[G], l[G], acc[G][NL];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m[g] = -INFINITY;
-    l[g] = 0.f;
-#pragma unroll
-    for (int i = 0; i < NL; ++i) acc[g][i] = 0.f;
+  const Params& p;
+  int lane, t, grp, half;
+  float (*p_lds)[kBlock];  // this wave's [G][16] probabilities
+  u32x4* q_lds;            // this wave's [G][D/8] query slices
+
+  __device__ ValuMath(int lane_, const Params& p_) : p(p_), lane(lane_) {
+    __shared__ float lds_p[kWavesPerGroup][G][kBlock];
+    __shared__ u32x4 lds_q[kWavesPerGroup][QCHUNKS];
+    t = lane & 15;
+    grp = lane >> 4;
+    half = lane & 1;
+    p_lds = lds_p[threadIdx.x >> 6];
+    q_lds = lds_q[threadIdx.x >> 6];
   }
 
-  const int32_t* row = bt + (size_t)s * p.max_nb + it.first_block;
-  u32x4 kb[NL], vb[NL];
-  {
-    const size_t g0 = granule_offset(row[0], h, p.Hkv, D);
+  // rows sigma*G .. sigma*G+G-1 of q are one contiguous run of QCHUNKS 16-byte pieces
+  __device__ void load_q(Q& out, const uint16_t* __restrict__ q, int sigma) const {
+    const u32x4* src = reinterpret_cast<const u32x4*>(q + (size_t)sigma * G * D);
+#pragma unroll
+    for (int j = 0; j < QPL; ++j) {
+      const int c = lane + kWave * j;
+      out.r[j] = src[min(c, QCHUNKS - 1)];
+    }
+  }
+
+  __device__ void install_q(State&, const Q& next) const {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < QPL; ++j) {
+      const int c = lane + kWave * j;
+      if (c < QCHUNKS) q_lds[c] = next.r[j];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+
+  template <bool STREAM>
+  __device__ void issue(Regs& r, const uint16_t* __restrict__ k_pool,
+                        const uint16_t* __restrict__ v_pool, int ga, int gb) const {
+    const size_t oa = (size_t)ga * (kBlock * D), ob = (size_t)gb * (kBlock * D);
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-      kb[i] = stream_load(k_pool + g0 + (lane + 64 * i) * 8);
-      vb[i] = stream_load(v_pool + g0 + (lane + 64 * i) * 8);
+      r.k[0][i] = kv_load<STREAM>(k_pool + oa + (lane + 64 * i) * 8);
+      r.v[0][i] = kv_load<STREAM>(v_pool + oa + (lane + 64 * i) * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      r.k[1][i] = kv_load<STREAM>(k_pool + ob + (lane + 64 * i) * 8);
+      r.v[1][i] = kv_load<STREAM>(v_pool + ob + (lane + 64 * i) * 8);
     }
   }
 
-  for (int b = 0; b < it.nblocks; ++b) {
-    u32x4 kn[NL], vn[NL];
-    if (b + 1 < it.nblocks) {
-      const size_t g1 = granule_offset(row[b + 1], h, p.Hkv, D);
+  __device__ void reset(State& s) const {
 #pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        kn[i] = stream_load(k_pool + g1 + (lane + 64 * i) * 8);
-        vn[i] = stream_load(v_pool + g1 + (lane + 64 * i) * 8);
-      }
-    } else {
+    for (int g = 0; g < G; ++g) {
+      s.m[g] = -INFINITY;
+      s.l[g] = 0.f;
 #pragma unroll
-      for (int i = 0; i < NL; ++i) kn[i] = vn[i] = u32x4{0, 0, 0, 0};
+      for (int i = 0; i < NL; ++i) s.acc[g][i] = 0.f;
     }
+  }
 
-    const int tok0 = (it.first_block + b) * kBlock;
-    const bool valid = tok0 + t < tok_end;
+  __device__ void block(State& s, const u32x4 (&kb)[NL], const u32x4 (&vb)[NL], int ntok) const {
+    const bool valid = t < ntok;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float a = 0.f;
 #pragma unroll
       for (int kk = 0; kk < NL; ++kk) {
-        a = dot2(kb[kk].x, qr[g][kk][0], a);
-        a = dot2(kb[kk].y, qr[g][kk][1], a);
-        a = dot2(kb[kk].z, qr[g][kk][2], a);
-        a = dot2(kb[kk].w, qr[g][kk][3], a);
+        const u32x4 qv = q_lds[g * (D / 8) + grp + 4 * kk];
+        a = dot2(kb[kk].x, qv.x, a);
+        a = dot2(kb[kk].y, qv.y, a);
+        a = dot2(kb[kk].z, qv.z, a);
+        a = dot2(kb[kk].w, qv.w, a);
       }
       a += __shfl_xor(a, 16);
       a += __shfl_xor(a, 32);
       const float sc = valid ? a * p.scale_log2 : -INFINITY;
-      const float m_new = fmaxf(m[g], row_max16(sc));
-      const float alpha = exp2f(m[g] - m_new);  // exp2(-inf) = 0 on the first block
+      const float m_new = fmaxf(s.m[g], row_max16(sc));
+      const float alpha = exp2f(s.m[g] - m_new);  // exp2(-inf) = 0 on the first block
       const float pr = exp2f(sc - m_new);
-      l[g] = l[g] * alpha + pr;
-      m[g] = m_new;
+      s.l[g] = s.l[g] * alpha + pr;
+      s.m[g] = m_new;
 #pragma unroll
-      for (int i = 0; i < NL; ++i) acc[g][i] *= alpha;
-      if (grp == 0) p_lds[wv][g][t] = pr;
+      for (int i = 0; i < NL; ++i) s.acc[g][i] *= alpha;
+      if (grp == 0) p_lds[g][t] = pr;
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    const bool tail = tok0 + kBlock > tok_end;  // wave-uniform
+    const bool tail = ntok < kBlock;  // wave-uniform
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
       float v[8] = {bf16_lo(vb[i].x), bf16_hi(vb[i].x), bf16_lo(vb[i].y), bf16_hi(vb[i].y),
@@ -151,13 +165,13 @@ __global__ __launch_bounds__(256, 2) void decode_valu_kernel(
       if (tail) {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          if (tok0 + half * 8 + e >= tok_end) v[e] = 0.f;  // unread slots may hold NaN
+          if (half * 8 + e >= ntok) v[e] = 0.f;  // unread slots may hold NaN
       }
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float4 pa = *reinterpret_cast<const float4*>(&p_lds[wv][g][half * 8]);
-        const float4 pb = *reinterpret_cast<const float4*>(&p_lds[wv][g][half * 8 + 4]);
-        float a = acc[g][i];
+        const float4 pa = *reinterpret_cast<const float4*>(&p_lds[g][half * 8]);
+        const float4 pb = *reinterpret_cast<const float4*>(&p_lds[g][half * 8 + 4]);
+        float a = s.acc[g][i];
         a = fmaf(pa.x, v[0], a);
         a = fmaf(pa.y, v[1], a);
         a = fmaf(pa.z, v[2], a);
@@ -166,41 +180,44 @@ __global__ __launch_bounds__(256, 2) void decode_valu_kernel(
         a = fmaf(pb.y, v[5], a);
         a = fmaf(pb.z, v[6], a);
         a = fmaf(pb.w, v[7], a);
-        acc[g][i] = a;
+        s.acc[g][i] = a;
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      kb[i] = kn[i];
-      vb[i] = vn[i];
-    }
   }
 
+  __device__ void compute(State& s, Regs& r, int ntok) const {
+    block(s, r.k[0], r.v[0], min(ntok, kBlock));
+    if (ntok > kBlock) block(s, r.k[1], r.v[1], ntok - kBlock);
+  }
+
+  __device__ void finish(State& s, int slot, float2* __restrict__ pml,
+                         float* __restrict__ pacc) const {
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const float lsum = row_sum16(l[g]);
-    const size_t rec = (size_t)item * p.Hq + h * G + g;
-    if (lane == 0) pml[rec] = make_float2(m[g], lsum);
+    for (int g = 0; g < G; ++g) {
+      const float lsum = row_sum16(s.l[g]);
+      const size_t rec = (size_t)slot * G + g;
+      if (lane == 0) pml[rec] = make_float2(s.m[g], lsum);
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const float a = acc[g][i] + __shfl_xor(acc[g][i], 1);
-      if (half == 0) pacc[rec * D + (lane >> 1) + 32 * i] = a;
+      for (int i = 0; i < NL; ++i) {
+        const float a = s.acc[g][i] + __shfl_xor(s.acc[g][i], 1);
+        if (half == 0) pacc[rec * D + (lane >> 1) + 32 * i] = a;
+      }
     }
   }
-}
+};
 
 template <int D>
-hipError_t launch_g(const Params& p, unsigned grid, const void* q, const void* k_pool,
-                    const void* v_pool, const int32_t* bt, const int32_t* lens,
-                    const int32_t* header, const Item* items, float2* pml, float* pacc,
-                    hipStream_t st) {
-#define VOX_VALU_CASE(GG)                                                                     \
-  case GG:                                                                                    \
-    hipLaunchKernelGGL((decode_valu_kernel<D, GG>), dim3(grid), dim3(256), 0, st, p,          \
-                       (const uint16_t*)q, (const uint16_t*)k_pool, (const uint16_t*)v_pool,  \
-                       bt, lens, header, items, pml, pacc);                                   \
+hipError_t launch_g(const Params& p, int waves, const void* q, const void* k_pool,
+                    const void* v_pool, const int32_t* header, const int4* desc, float2* pml,
+                    float* pacc, hipStream_t st) {
+  const unsigned grid = (unsigned)((waves + kWavesPerGroup - 1) / kWavesPerGroup);
+#define VOX_VALU_CASE(GG)                                                                      \
+  case GG:                                                                                     \
+    hipLaunchKernelGGL((decode_kernel<ValuMath<D, GG>>), dim3(grid), dim3(256), 0, st, p,      \
+                       (const uint16_t*)q, (const uint16_t*)k_pool, (const uint16_t*)v_pool,   \
+                       header, desc, pml, pacc);                                               \
     break;
   switch (p.G) {
     VOX_VALU_CASE(1)
@@ -220,15 +237,13 @@ hipError_t launch_g(const Params& p, unsigned grid, const void* q, const void* k
 
 }  // namespace
 
-hipError_t launch_decode_valu(const Params& p, int max_wave_items, const void* q,
-                              const void* k_pool, const void* v_pool, const int32_t* bt,
-                              const int32_t* lens, const int32_t* header, const Item* items,
+hipError_t launch_decode_valu(const Params& p, int waves, const void* q, const void* k_pool,
+                              const void* v_pool, const int32_t* header, const int4* desc,
                               float2* partial_ml, float* partial_acc, hipStream_t st) {
-  const unsigned grid = (unsigned)((max_wave_items + kWavesPerGroup - 1) / kWavesPerGroup);
-  return p.D == 128 ? launch_g<128>(p, grid, q, k_pool, v_pool, bt, lens, header, items,
-                                    partial_ml, partial_acc, st)
-                    : launch_g<64>(p, grid, q, k_pool, v_pool, bt, lens, header, items,
-                                   partial_ml, partial_acc, st);
+  return p.D == 128 ? launch_g<128>(p, waves, q, k_pool, v_pool, header, desc, partial_ml,
+                                    partial_acc, st)
+                    : launch_g<64>(p, waves, q, k_pool, v_pool, header, desc, partial_ml,
+                                   partial_acc, st);
 }
 
 }  // namespace vox

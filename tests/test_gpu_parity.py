@@ -33,9 +33,9 @@ def _host_pools(w, layer=0):
     return bits_of(w.k_pool[layer]), bits_of(w.v_pool[layer])
 
 
-def _decode(w, dev, layer=0, path=binding.PATH_AUTO, chunk=0, host_lens=True, ws_bytes=None,
+def _decode(w, dev, layer=0, path=binding.PATH_AUTO, waves=0, host_lens=True, ws_bytes=None,
             want_lse=True):
-    sh = binding.shape_of(w, decode_path=path, chunk_blocks=chunk)
+    sh = binding.shape_of(w, decode_path=path, split_waves=waves)
     bt, lens = _i32(w.block_tables, dev), _i32(w.context_lens, dev)
     out = torch.full((w.num_streams, w.num_q_heads, w.head_dim), float("nan"), device=dev)
     lse = torch.full((w.num_streams, w.num_q_heads), float("nan"), device=dev) if want_lse else None
@@ -152,25 +152,48 @@ def test_edge_lengths_and_head_groupings(dev, hq, hkv, d, path):
 
 
 @pytest.mark.parametrize("path", PATHS)
-@pytest.mark.parametrize("chunk", [2, 4, 6, 16, 64])
-def test_split_k_chunkings_agree_with_oracle(dev, chunk, path):
-    lens = [1, 31, 32, 33, 63, 64, 65, 95, 96, 97, 1023, 1024, 1025, 2000]
+@pytest.mark.parametrize("waves", [1, 4, 12, 100, 1000, 4096, 100000])
+def test_split_k_range_counts_agree_with_oracle(dev, waves, path):
+    # from one wave walking every segment to more ranges than steps (one step per wave)
+    lens = [1, 31, 32, 33, 63, 64, 65, 95, 96, 97, 1023, 1024, 1025, 2000, 0, 4100]
     w = synth.make_custom(lens, 24, 8, 128, seed=52, device=dev)
     ref, ref_lse = _oracle_decode(w)
     for host_lens in (True, False):
-        out, lse = _decode(w, dev, path=path, chunk=chunk, host_lens=host_lens)
-        _assert_close(out, ref, f"chunk{chunk} host{host_lens} path{path}")
-        _assert_lse(lse, ref_lse, f"chunk{chunk} host{host_lens} path{path}")
+        out, lse = _decode(w, dev, path=path, waves=waves, host_lens=host_lens)
+        _assert_close(out, ref, f"waves{waves} host{host_lens} path{path}")
+        _assert_lse(lse, ref_lse, f"waves{waves} host{host_lens} path{path}")
 
 
 @pytest.mark.parametrize("path", PATHS)
-def test_minimum_workspace_and_no_lse(dev, path):
-    w = synth.make_custom([700, 64, 0, 1500, 33], 24, 8, 128, seed=53, device=dev)
+def test_long_ranges_cross_descriptor_windows(dev, path):
+    # few waves on long contexts: each wave walks several hundred steps (descriptor windows of
+    # 64 are refilled many times) and crosses many segment boundaries
+    lens = [8192, 5000, 3, 8191, 100, 2049]
+    w = synth.make_custom(lens, 8, 2, 64, seed=57, device=dev)
+    ref, ref_lse = _oracle_decode(w)
+    for waves in (4, 8):
+        out, lse = _decode(w, dev, path=path, waves=waves)
+        _assert_close(out, ref, f"waves{waves} path{path}")
+        _assert_lse(lse, ref_lse, f"waves{waves} path{path}")
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_exact_workspace_from_host_lens_and_no_lse(dev, path):
+    # with the host copy of the lengths a workspace sized for the actual steps is enough
+    w = synth.make_custom([700, 64, 0, 1500, 33], 24, 8, 128, seed=53, device=dev,
+                          max_blocks_per_stream=512)
     sh = binding.shape_of(w, decode_path=path)
+    full = binding.paged_decode_workspace_bytes(sh)
+    steps = int(sum(((int(L) + 15) // 16 + 1) // 2 for L in w.context_lens)) * w.num_kv_heads
+    bound = w.num_streams * 256 * w.num_kv_heads
+    small = full - (bound - steps) * 16
+    assert small < full
     ref, _ = _oracle_decode(w)
-    out, _ = _decode(w, dev, path=path, ws_bytes=binding.paged_decode_min_workspace_bytes(sh),
-                     host_lens=False, want_lse=False)
-    _assert_close(out, ref, f"min workspace path{path}")
+    out, _ = _decode(w, dev, path=path, ws_bytes=small, want_lse=False)
+    _assert_close(out, ref, f"exact workspace path{path}")
+    with pytest.raises(binding.VoxError) as e:
+        _decode(w, dev, path=path, ws_bytes=small, host_lens=False)
+    assert e.value.code == -3
 
 
 @pytest.mark.parametrize("path", PATHS)
@@ -203,7 +226,7 @@ def test_unread_slots_may_hold_nan(dev, path):
 @pytest.mark.parametrize("path", PATHS)
 def test_block_permutation_gives_same_bits(dev, path):
     w = synth.make_custom([300, 17, 1024, 50], 24, 8, 128, seed=55, device=dev)
-    out, _ = _decode(w, dev, path=path, chunk=8)
+    out, _ = _decode(w, dev, path=path, waves=64)
     rng = np.random.default_rng(5)
     sigma = rng.permutation(w.num_blocks)
     inv = torch.from_numpy(np.argsort(sigma)).to(dev)
@@ -212,7 +235,7 @@ def test_block_permutation_gives_same_bits(dev, path):
     t = w.block_tables.copy()
     t[t >= 0] = sigma[t[t >= 0]]
     w.block_tables = t.astype(np.int32)
-    out2, _ = _decode(w, dev, path=path, chunk=8)
+    out2, _ = _decode(w, dev, path=path, waves=64)
     assert np.array_equal(out, out2)
 
 
