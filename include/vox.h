@@ -20,11 +20,14 @@
  *
  * KV-cache layout (part of the ABI, bf16 elements, two separate pools):
  *   K pool, element (blk, h, t, d), t in [0,B), d in [0,D):
- *       (((blk*Hkv + h)*(D/8) + d/8)*B + t)*8 + d%8
- *     i.e. [P][Hkv][D/8][B][8]: 8-dim slices of the 16 tokens are contiguous.
+ *       (((blk*Hkv + h)*(D/32) + d/32)*B + t)*32 + d%32
+ *     i.e. [P][Hkv][D/32][B][32]: a token's row is D/32 pieces of 64 bytes.
  *   V pool, element (blk, h, t, d):
- *       ((blk*Hkv + h)*D + d)*B + t
- *     i.e. [P][Hkv][D][B]: each dim holds its 16 tokens contiguously.
+ *       (((blk*Hkv + h)*(B/4) + t/4)*D + d)*4 + t%4
+ *     i.e. [P][Hkv][B/4][D][4]: four consecutive tokens of one dim are adjacent.
+ *   Both serve the matrix-core operand shapes directly (8 consecutive dims of a
+ *   token for QK^T, 4 consecutive tokens of a dim for PV) while an appended
+ *   token touches only D/32 + D/16 cache lines of its block.
  *   Each (blk, h) pair is one contiguous granule of B*D*2 bytes in either pool.
  *   block_tables is int32 [S][max_blocks_per_stream]; logical token t of
  *   stream s lives in physical block block_tables[s][t / B], slot t % B.
@@ -76,7 +79,7 @@ typedef struct {
   int32_t decode_path;           /* VOX_PATH_* */
   int32_t split_waves;           /* split-K: number of equal ranges (one per wave) the context
                                     steps of all streams are cut into; 0 = one per wave the
-                                    chip keeps resident (2048), the balanced single round */
+                                    chip keeps resident (1024), the balanced single round */
 } vox_shape_t;
 
 /*

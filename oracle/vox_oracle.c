@@ -17,8 +17,8 @@
  * passes to the library and is widened exactly too.
  *
  * Cache layout (the library ABI this oracle is the reference for):
- *   K element (blk,h,t,d) at (((blk*Hkv+h)*(D/8) + d/8)*B + t)*8 + d%8
- *   V element (blk,h,t,d) at  ((blk*Hkv+h)*D + d)*B + t
+ *   K element (blk,h,t,d) at (((blk*Hkv+h)*(D/32) + d/32)*B + t)*32 + d%32
+ *   V element (blk,h,t,d) at (((blk*Hkv+h)*(B/4) + t/4)*D + d)*4 + t%4
  *
  * Parity pins (tests/test_oracle_pins.py): brute-force dense attention in
  * numpy and in exact rational arithmetic on tiny inputs, single-key and
@@ -48,15 +48,15 @@ static double bf16_to_f64(uint16_t bits) {
 }
 
 static size_t k_index(int Hkv, int D, int B, int64_t blk, int h, int t, int d) {
-  return ((((size_t)blk * Hkv + h) * (size_t)(D / 8) + (size_t)(d / 8)) * B + t) * 8 + (d % 8);
+  return ((((size_t)blk * Hkv + h) * (size_t)(D / 32) + (size_t)(d / 32)) * B + t) * 32 + (d % 32);
 }
 
 static size_t v_index(int Hkv, int D, int B, int64_t blk, int h, int t, int d) {
-  return (((size_t)blk * Hkv + h) * (size_t)D + d) * B + t;
+  return ((((size_t)blk * Hkv + h) * (size_t)(B / 4) + (size_t)(t / 4)) * D + d) * 4 + (t % 4);
 }
 
 static int shape_ok(int S, int Hq, int Hkv, int D, int B, int P, int max_nb) {
-  return S > 0 && Hq > 0 && Hkv > 0 && Hq % Hkv == 0 && D > 0 && D % 8 == 0 && B > 0 && P > 0 &&
+  return S > 0 && Hq > 0 && Hkv > 0 && Hq % Hkv == 0 && D > 0 && D % 32 == 0 && B > 0 && B % 4 == 0 && P > 0 &&
          max_nb > 0;
 }
 

@@ -5,13 +5,12 @@ namespace vox {
 namespace {
 
 // ---------------------------------------------------------------------------------------
-// KV append: one wave per (stream, kv head).  A token's K row is 16-byte slices 256 bytes
-// apart and its V row is 2-byte slots 32 bytes apart, so storing only those bytes would leave
-// every cache line of the granule partially written, and lines in that state are slow to read
-// back by the attention kernel that follows.  The wave therefore reads the two granules of the
-// token's block, replaces the token's slots in registers and stores both granules back whole,
-// 16 bytes per lane: every line is written in full with bit-identical surroundings.  A block
-// that receives an append belongs to exactly one stream, so nothing else writes it meanwhile.
+// KV append: one wave per (stream, kv head).  The token's K row is D/32 pieces of 64 bytes:
+// lanes [0, D/8) each copy 16 bytes.  Its V row is one 2-byte slot in each 8-byte token quad
+// of a D*8-byte region; lanes [0, D/2) read the 16 bytes holding two dims of that region,
+// replace the token's two slots and store the 16 bytes back, so the region's D/16 cache lines
+// are written whole.  Lines that were just written are slow for the following attention
+// kernel to read, so the layout keeps their number small (D/32 + D/16 per kv head).
 typedef uint32_t au32x4 __attribute__((ext_vector_type(4)));
 
 template <int D>
@@ -21,7 +20,6 @@ __global__ __launch_bounds__(256) void kv_append_kernel(Params p, const uint16_t
                                                         uint16_t* __restrict__ v_pool,
                                                         const int32_t* __restrict__ bt,
                                                         const int32_t* __restrict__ lens) {
-  constexpr int NL = D / 32;  // 16-byte pieces per lane per granule
   const int lane = threadIdx.x & (kWave - 1);
   const int sigma = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
   if (sigma >= p.S * p.Hkv) return;
@@ -34,29 +32,20 @@ __global__ __launch_bounds__(256) void kv_append_kernel(Params p, const uint16_t
   const size_t g = granule_offset(blk, h, p.Hkv, D);
   const uint16_t* krow = k_new + (size_t)sigma * D;
   const uint16_t* vrow = v_new + (size_t)sigma * D;
-  au32x4 kr[NL], vr[NL];
-#pragma unroll
-  for (int j = 0; j < NL; ++j) {
-    kr[j] = *reinterpret_cast<const au32x4*>(k_pool + g + (lane + kWave * j) * 8);
-    vr[j] = *reinterpret_cast<const au32x4*>(v_pool + g + (lane + kWave * j) * 8);
-  }
-#pragma unroll
-  for (int j = 0; j < NL; ++j) {
-    // K piece lane + 64 j holds token lane % 16, dims 8 * (lane / 16 + 4 j) .. + 8
-    if ((lane & 15) == t)
-      kr[j] = *reinterpret_cast<const au32x4*>(krow + ((lane >> 4) + 4 * j) * 8);
-    // V piece lane + 64 j holds dim (lane + 64 j) / 2, tokens 8 * (lane % 2) .. + 8
-    if ((lane & 1) == (t >> 3)) {
-      const uint32_t bits = vrow[(lane + kWave * j) >> 1];
-      const int e = t & 7;
-      const uint32_t old = vr[j][e >> 1];
-      vr[j][e >> 1] = (e & 1) ? ((old & 0x0000FFFFu) | (bits << 16)) : ((old & 0xFFFF0000u) | bits);
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < NL; ++j) {
-    *reinterpret_cast<au32x4*>(k_pool + g + (lane + kWave * j) * 8) = kr[j];
-    *reinterpret_cast<au32x4*>(v_pool + g + (lane + kWave * j) * 8) = vr[j];
+  if (lane < D / 8)
+    *reinterpret_cast<au32x4*>(k_pool + g + k_elem(t, lane * 8)) =
+        *reinterpret_cast<const au32x4*>(krow + lane * 8);
+  if (lane < D / 2) {
+    uint16_t* quad = v_pool + g + v_elem(t & ~3, 2 * lane, D);  // dims 2*lane, 2*lane+1
+    au32x4 r = *reinterpret_cast<const au32x4*>(quad);
+    const uint32_t two = *reinterpret_cast<const uint32_t*>(vrow + 2 * lane);
+    const int e = t & 3;  // slot of the token inside each 4-token quad
+    const uint32_t d0 = two & 0xFFFFu, d1 = two >> 16;
+    const uint32_t keep = (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+    const int sh = (e & 1) * 16;
+    r[e >> 1] = (r[e >> 1] & keep) | (d0 << sh);
+    r[2 + (e >> 1)] = (r[2 + (e >> 1)] & keep) | (d1 << sh);
+    *reinterpret_cast<au32x4*>(quad) = r;
   }
 }
 
@@ -91,8 +80,8 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(Params p, const uint16_t
     uint32_t w[4];
 #pragma unroll
     for (int e = 0; e < 8; e += 2) {
-      const uint32_t lo = v_pool[g + v_elem(t, o * 8 + e)];
-      const uint32_t hi = v_pool[g + v_elem(t, o * 8 + e + 1)];
+      const uint32_t lo = v_pool[g + v_elem(t, o * 8 + e, p.D)];
+      const uint32_t hi = v_pool[g + v_elem(t, o * 8 + e + 1, p.D)];
       w[e >> 1] = lo | (hi << 16);
     }
     v_out[dst] = make_uint4(w[0], w[1], w[2], w[3]);

@@ -25,7 +25,7 @@ constexpr int kWave = 64;          // lanes per wavefront
 constexpr int kWavesPerGroup = 4;  // decode / merge workgroups are 4 independent waves
 constexpr int kStepTokens = 32;    // tokens consumed per step (two blocks)
 constexpr int kMaxStreams = 8192;  // the plan kernel keeps the per-stream prefix in LDS
-constexpr int kDesignWaveSlots = 256 * 2 * kWavesPerGroup;  // 256 CUs x 2 workgroups x 4 waves
+constexpr int kDesignWaveSlots = 256 * kWavesPerGroup;  // 256 CUs x 1 workgroup x 4 waves (1 per SIMD)
 
 // Step descriptor written by the plan kernels, one per global step (16 bytes).
 //   x: granule index (block id * Hkv + h) of the step's first block
@@ -62,12 +62,14 @@ struct Params {
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// K pool [P][Hkv][D/8][B][8], V pool [P][Hkv][D][B]; element offsets of granule (blk, h).
+// K pool [P][Hkv][D/32][B][32], V pool [P][Hkv][B/4][D][4]; element offsets of granule (blk, h).
 __host__ __device__ inline size_t granule_offset(int64_t blk, int h, int Hkv, int D) {
   return ((size_t)blk * Hkv + h) * (size_t)(kBlock * D);
 }
-__host__ __device__ inline int k_elem(int t, int d) { return ((d >> 3) * kBlock + t) * 8 + (d & 7); }
-__host__ __device__ inline int v_elem(int t, int d) { return d * kBlock + t; }
+__host__ __device__ inline int k_elem(int t, int d) {
+  return ((d >> 5) * kBlock + t) * 32 + (d & 31);
+}
+__host__ __device__ inline int v_elem(int t, int d, int D) { return ((t >> 2) * D + d) * 4 + (t & 3); }
 
 // Launchers implemented in the kernel translation units; each returns hipGetLastError().
 hipError_t launch_kv_append(const Params& p, const void* k_new, const void* v_new, void* k_pool,

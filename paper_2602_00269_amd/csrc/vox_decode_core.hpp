@@ -12,7 +12,8 @@
 //   struct Q (query rows in flight), struct Regs (one step of K/V), struct State;
 //   Math(lane, params); load_q(Q&, q, sigma); install_q(State&, Q&);
 //   issue(Regs&, k_pool, v_pool, ga, gb); reset(State&); compute(State&, Regs&, ntok);
-//   finish(State&, slot, pml, pacc);
+//   finish(State&, float* record): writes the run's [G][D] accumulators and [G] (max, sum)
+//   pairs into the LDS record.
 #pragma once
 
 #include "vox_common.hpp"
@@ -28,6 +29,57 @@ __device__ inline u32x4 kv_load(const uint16_t* p) {
   if (STREAM) return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
   return *reinterpret_cast<const u32x4*>(p);
 }
+
+// Wave-private LDS buffer of finished partial records.  A global store issued in the middle of
+// the load pipeline sits in the same in-order vector-memory counter as the K/V loads, and its
+// acknowledgement is slow while the chip streams at full rate: every later load would wait
+// behind it.  Records are therefore kept in LDS ([G][D] accumulators then [G] (max, sum)
+// pairs, the same shape as a global record) and copied out when the wave has finished its
+// range, or earlier if the buffer fills up.
+constexpr int kStashFloats = 4096;  // 16 KB per wave, 64 KB per workgroup
+
+struct PartialStash {
+  float* mem;    // this wave's LDS area
+  int rec;       // floats per record: G * (D + 2)
+  int gd;        // G * D
+  int cap;       // records that fit
+  int count;     // records held
+  int slots;     // lane r holds the slot id of record r
+  int lane;
+
+  __device__ PartialStash(float* mem_, int G, int D, int lane_)
+      : mem(mem_), rec(G * (D + 2)), gd(G * D), cap(kStashFloats / (G * (D + 2))), count(0),
+        slots(0), lane(lane_) {}
+
+  // LDS area of the record being added; the caller fills [g][d] at g*D + d and the (max, sum)
+  // pair of head g at gd + 2*g, then calls commit().
+  __device__ float* next() const { return mem + count * rec; }
+
+  __device__ void commit(int slot, float2* __restrict__ pml, float* __restrict__ pacc) {
+    if (lane == count) slots = slot;
+    ++count;
+    if (count == cap) flush(pml, pacc);
+  }
+
+  __device__ void flush(float2* __restrict__ pml, float* __restrict__ pacc) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int r = 0; r < count; ++r) {
+      const int slot = __builtin_amdgcn_readlane(slots, r);
+      const float* src = mem + r * rec;
+      float* dst = pacc + (size_t)slot * gd;
+      for (int x = lane * 4; x < gd; x += kWave * 4)
+        *reinterpret_cast<float4*>(dst + x) = *reinterpret_cast<const float4*>(src + x);
+      if (2 * lane < rec - gd)
+        pml[(size_t)slot * (rec - gd) / 2 + lane] =
+            *reinterpret_cast<const float2*>(src + gd + 2 * lane);
+    }
+    count = 0;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+};
 
 template <class Math>
 __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
@@ -48,6 +100,8 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
 #define VOX_DESC(I, C) \
   __builtin_amdgcn_readlane((int)((((I) & kWave) ? dw1 : dw0).C), (I) & (kWave - 1))
 
+  __shared__ float stash_mem[kWavesPerGroup][kStashFloats];
+  PartialStash stash(stash_mem[threadIdx.x >> 6], p.G, p.D, lane);
   Math math(lane, p);
   typename Math::State st;
   typename Math::Q qnext;
@@ -84,7 +138,10 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
       const int gb = more ? VOX_DESC(i + NBUF, y) : 0;                                     \
       math.template issue<true>(ring[B], k_pool, v_pool, ga, gb);                          \
     }                                                                                      \
-    if (meta & kMetaLast) math.finish(st, w + sigma, pml, pacc);                           \
+    if (meta & kMetaLast) {                                                                \
+      math.finish(st, stash.next());                                                       \
+      stash.commit(w + sigma, pml, pacc);                                                  \
+    }                                                                                      \
     if ((i & (kWave - 1)) == kWave - 1) { /* window i>>6 is spent: fetch window (i>>6)+2 */ \
       const u32x4 nw = dbase[min(i + 1 + kWave + lane, nsteps - 1)];                       \
       if (i & kWave)                                                                       \
@@ -103,6 +160,7 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
   for (int b = 0; b < NBUF - 1; ++b)  // fewer than NBUF steps remain; their data is in flight
     if (i0 + b < nsteps) VOX_STEP(i0 + b, b, false)
 #undef VOX_STEP
+  stash.flush(pml, pacc);
 #undef VOX_DESC
 }
 

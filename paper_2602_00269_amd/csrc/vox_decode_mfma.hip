@@ -1,26 +1,30 @@
-// Paged GQA decode arithmetic on the bf16 matrix cores (v_mfma_f32_16x16x32_bf16): no LDS and
-// no workgroup barriers, a wave streams KV granules from the block pools straight into MFMA
-// operand registers.
+// Paged GQA decode arithmetic on the bf16 matrix cores: no LDS and no workgroup barriers, a
+// wave streams KV granules from the block pools straight into MFMA operand registers.
 //
 // Step = 32 tokens = blocks A, B.  Lane l = (n = l % 16, c = l / 16).
 //
-//   Scores, two M-tiles T = 0, 1:   S_T[16 x 16] = Ktile_T[16 tokens x D] * Qt[D x 16]
-//     A operand row i (= n when loading) is token 8*((i>>2)&1) + 4*T + (i&3) of block i>>3,
-//     k-slice c + 4*kk of the dims.  With the K granule [D/8][16][8] each lane quad reads 64
-//     contiguous bytes and the two tiles together cover both granules.
+//   Scores per block (v_mfma_f32_16x16x32_bf16, D/32 of them):
+//       S[16 tokens x 16] = Kblk[16 x D] * Qt[D x 16]
+//     A operand row n = token n, k-slice kk = dims 32*kk + 8*c .. +8: with the K granule
+//     [D/32][16][32] that is the 16 bytes at kk*1024 + n*64 + c*16, so one load instruction
+//     covers one contiguous KiB of one block.
 //     B operand column n is a query head: columns [0,G) the G heads, [G,2G) the same heads
 //     again, the rest zero.
-//     Result: lane (n, c) holds, for its column, the scores of tokens 8*c + e (e = 4*T + r)
-//     of the step: eight consecutive tokens, all in block c>>1.
-//   Softmax in log2 units per column; the running max is shared by the four lane groups.
-//     Columns [0,G) keep hi = bf16(p); columns [G,2G) keep lo = bf16(p - hi), so hi + lo
-//     carries p to ~2^-17 relative and the two partial outputs are added once per run.
-//   Output, D/16 tiles:   O_nt[16 dims x 16] += Vt_nt[16 dims x 32 tokens] * Pt[32 x 16]
-//     A operand row i = dim 16*nt + i, k = 8*c + e: with the V granule [D][16] that is one
-//     16-byte read (8 tokens of one dim) from block c>>1.  B operand = the lane's own 8
-//     probabilities.  Nothing moves between lanes inside the loop except the max.
-//     Result layout: lane (n, c), register r = dim 16*nt + 4*c + r of column n, so the
-//     per-column rescale factor is lane-local.
+//     Result: lane (n, c) holds, for its column, the scores of tokens 4*c + r of the block.
+//   Softmax in log2 units per column over the step's 32 scores; the running max is shared by
+//     the four lane groups.  Columns [0,G) keep hi = bf16(p); columns [G,2G) keep
+//     lo = bf16(p - hi), so hi + lo carries p to ~2^-17 relative and the two partial outputs
+//     are added once per run.
+//   Output per block (v_mfma_f32_16x16x16_bf16, D/16 of them):
+//       O_tile[16 dims x 16] += Vt_tile[16 dims x 16 tokens] * Pt[16 tokens x 16]
+//     The V granule [4][D][4] keeps four consecutive tokens of a dim adjacent: lane (n, c)
+//     reads 16 bytes at c*D*8 + j*256 + n*16 = dims 32*j + 2*n and 32*j + 2*n + 1, tokens
+//     4*c .. 4*c+3.  The low 8 bytes are row n of tile 2j, the high 8 bytes row n of tile
+//     2j+1 (tile 2j row i is dim 32j + 2i, tile 2j+1 row i is dim 32j + 2i + 1).  B operand =
+//     the lane's own 4 probabilities of that block.  Nothing moves between lanes inside the
+//     loop except the max.
+//     Result layout: lane (n, c), register r of tile 2j+u = dim 32j + 8c + 2r + u of column n,
+//     so the per-column rescale factor is lane-local and a lane owns 8 consecutive dims.
 #include <stdlib.h>
 
 #include "vox_decode_core.hpp"
@@ -29,11 +33,17 @@ namespace vox {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-__device__ inline f32x4 mfma(u32x4 a, u32x4 b, f32x4 c) {
+__device__ inline f32x4 mfma32(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ inline f32x4 mfma16(u32x2 a, u32x2 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a),
+                                                   __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
 }
 
 __device__ inline uint32_t pack_bf16(float a, float b) {
@@ -46,15 +56,15 @@ __device__ inline float round_bf16(float a) { return (float)(__bf16)a; }
 template <int D, int NBUF>
 struct MfmaMath {
   static constexpr int kBuffers = NBUF;
-  static constexpr int kMinWavesPerSimd = NBUF <= 2 ? 2 : 1;
-  static constexpr int KK = D / 32;  // MFMAs per score tile
+  static constexpr int kMinWavesPerSimd = 1;
+  static constexpr int KK = D / 32;  // score MFMAs per block = V loads per block
   static constexpr int NT = D / 16;  // output dim tiles
 
   struct Q {
     u32x4 b[KK];
   };
   struct Regs {
-    u32x4 k[2 * KK], v[NT];
+    u32x4 k[2][KK], v[2][KK];
   };
   struct State {
     Q q;
@@ -64,7 +74,7 @@ struct MfmaMath {
 
   const Params& p;
   int lane, n, c, G;
-  bool is_lo, k_second, v_second;
+  bool is_lo;
   int k_off, v_off;
 
   __device__ MfmaMath(int lane_, const Params& p_) : p(p_), lane(lane_) {
@@ -72,21 +82,18 @@ struct MfmaMath {
     c = lane >> 4;
     G = p.G;
     is_lo = n >= G;
-    const int k_tok = ((n >> 2) & 1) * 8 + (n & 3);  // + 4*T
-    k_off = (c * kBlock + k_tok) * 8;                 // + kk*4*16*8 + T*4*8
-    v_off = n * kBlock + (c & 1) * 8;                 // + nt*16*16
-    k_second = (n >> 3) != 0;                         // K rows 8..15 come from block B
-    v_second = (c >> 1) != 0;                         // lane groups 2,3 read block B
+    k_off = n * 32 + c * 8;      // + kk * 512
+    v_off = c * D * 4 + n * 8;   // + j * 128
   }
 
   // Query operand of segment sigma: column n -> row sigma*G + (n mod G) for n < 2G, else zero.
   __device__ void load_q(Q& out, const uint16_t* __restrict__ q, int sigma) const {
     const bool has = n < 2 * G;
     const int row = sigma * G + (has ? (n < G ? n : n - G) : 0);
-    const uint16_t* qrow = q + (size_t)row * D;
+    const uint16_t* qrow = q + (size_t)row * D + c * 8;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      out.b[kk] = *reinterpret_cast<const u32x4*>(qrow + (c + 4 * kk) * 8);
+      out.b[kk] = *reinterpret_cast<const u32x4*>(qrow + 32 * kk);
       if (!has) out.b[kk] = u32x4{0, 0, 0, 0};
     }
   }
@@ -96,15 +103,18 @@ struct MfmaMath {
   template <bool STREAM>
   __device__ void issue(Regs& r, const uint16_t* __restrict__ k_pool,
                         const uint16_t* __restrict__ v_pool, int ga, int gb) const {
-    const uint16_t* kp = k_pool + (size_t)(k_second ? gb : ga) * (kBlock * D) + k_off;
-    const uint16_t* vp = v_pool + (size_t)(v_second ? gb : ga) * (kBlock * D) + v_off;
+    const uint16_t* ka = k_pool + (size_t)ga * (kBlock * D) + k_off;
+    const uint16_t* kb = k_pool + (size_t)gb * (kBlock * D) + k_off;
+    const uint16_t* va = v_pool + (size_t)ga * (kBlock * D) + v_off;
+    const uint16_t* vb = v_pool + (size_t)gb * (kBlock * D) + v_off;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      r.k[kk] = kv_load<STREAM>(kp + kk * (4 * kBlock * 8));
-      r.k[KK + kk] = kv_load<STREAM>(kp + kk * (4 * kBlock * 8) + 4 * 8);
-    }
+    for (int kk = 0; kk < KK; ++kk) r.k[0][kk] = kv_load<STREAM>(ka + kk * 512);
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) r.v[nt] = kv_load<STREAM>(vp + nt * (16 * kBlock));
+    for (int kk = 0; kk < KK; ++kk) r.k[1][kk] = kv_load<STREAM>(kb + kk * 512);
+#pragma unroll
+    for (int j = 0; j < KK; ++j) r.v[0][j] = kv_load<STREAM>(va + j * 128);
+#pragma unroll
+    for (int j = 0; j < KK; ++j) r.v[1][j] = kv_load<STREAM>(vb + j * 128);
   }
 
   __device__ void reset(State& s) const {
@@ -115,18 +125,20 @@ struct MfmaMath {
   }
 
   __device__ void compute(State& s, Regs& r, int ntok) const {
-    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      s0 = mfma(r.k[kk], s.q.b[kk], s0);
-      s1 = mfma(r.k[KK + kk], s.q.b[kk], s1);
+      sa = mfma32(r.k[0][kk], s.q.b[kk], sa);
+      sb = mfma32(r.k[1][kk], s.q.b[kk], sb);
     }
-    const int nvalid = ntok - 8 * c;  // valid tokens among this lane's eight; may be <=0 or >=8
-    float t[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+    // valid tokens among this lane's four of block A / block B; may be <= 0 or >= 4
+    const int va = ntok - 4 * c, vb = ntok - kBlock - 4 * c;
+    float t[8] = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
     float mx = -INFINITY;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      t[e] = e < nvalid ? t[e] * p.scale_log2 : -INFINITY;
+      const bool ok = e < 4 ? e < va : e - 4 < vb;
+      t[e] = ok ? t[e] * p.scale_log2 : -INFINITY;
       mx = fmaxf(mx, t[e]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -144,41 +156,63 @@ struct MfmaMath {
       pw[e >> 1] = is_lo ? pack_bf16(p0 - h0, p1 - h1) : pack_bf16(h0, h1);
     }
     s.l = s.l * alpha + psum;
-    const u32x4 pb = {pw[0], pw[1], pw[2], pw[3]};
+    const u32x2 pa = {pw[0], pw[1]}, pb = {pw[2], pw[3]};
     if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) s.acc[nt] *= alpha;
     }
     if (ntok < kStepTokens) {
-      // Unread slots of a tail may hold NaN/Inf bits and 0 * NaN = NaN: clear them.
-      uint32_t msk[4];
+      // Unread slots of a tail may hold NaN/Inf bits and 0 * NaN = NaN: clear them.  A 16-byte
+      // V register is two dims x four tokens: dwords 0,2 hold tokens 0,1 and dwords 1,3 hold 2,3.
+      const auto mask4 = [](int valid) {
+        const uint32_t lo = (0 < valid ? 0x0000FFFFu : 0u) | (1 < valid ? 0xFFFF0000u : 0u);
+        const uint32_t hi = (2 < valid ? 0x0000FFFFu : 0u) | (3 < valid ? 0xFFFF0000u : 0u);
+        return u32x4{lo, hi, lo, hi};
+      };
+      const u32x4 ma = mask4(va), mb = mask4(vb);
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        msk[j] = (2 * j < nvalid ? 0x0000FFFFu : 0u) | (2 * j + 1 < nvalid ? 0xFFFF0000u : 0u);
-      const u32x4 mv = {msk[0], msk[1], msk[2], msk[3]};
+      for (int j = 0; j < KK; ++j) {
+        r.v[0][j] &= ma;
+        r.v[1][j] &= mb;
+      }
+    }
+    // block A into all tiles, then block B: consecutive MFMAs never depend on each other
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) r.v[nt] &= mv;
+    for (int j = 0; j < KK; ++j) {
+      const u32x4 a = r.v[0][j];
+      s.acc[2 * j] = mfma16(u32x2{a.x, a.y}, pa, s.acc[2 * j]);
+      s.acc[2 * j + 1] = mfma16(u32x2{a.z, a.w}, pa, s.acc[2 * j + 1]);
     }
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) s.acc[nt] = mfma(r.v[nt], pb, s.acc[nt]);
+    for (int j = 0; j < KK; ++j) {
+      const u32x4 b = r.v[1][j];
+      s.acc[2 * j] = mfma16(u32x2{b.x, b.y}, pb, s.acc[2 * j]);
+      s.acc[2 * j + 1] = mfma16(u32x2{b.z, b.w}, pb, s.acc[2 * j + 1]);
+    }
   }
 
-  // Partial record of a run: sum over lane groups, add the hi and lo columns, store.
-  __device__ void finish(State& s, int slot, float2* __restrict__ pml,
-                         float* __restrict__ pacc) const {
+  // Partial record of a run: sum over lane groups, add the hi and lo columns, write to the LDS
+  // record.  A lane owns dims 32j + 8c .. +8 of its column: even ones in tile 2j, odd in 2j+1.
+  __device__ void finish(State& s, float* __restrict__ rec) const {
     float l = s.l;
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
     const bool writer = n < G;
-    const size_t rec = (size_t)slot * G + (writer ? n : 0);
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      f32x4 o;
+    for (int j = 0; j < KK; ++j) {
+      float o[8];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) o[r] = s.acc[nt][r] + __shfl(s.acc[nt][r], lane + G);
-      if (writer) *reinterpret_cast<f32x4*>(pacc + rec * D + 16 * nt + 4 * c) = o;
+      for (int r = 0; r < 4; ++r) {
+        o[2 * r] = s.acc[2 * j][r] + __shfl(s.acc[2 * j][r], lane + G);
+        o[2 * r + 1] = s.acc[2 * j + 1][r] + __shfl(s.acc[2 * j + 1][r], lane + G);
+      }
+      if (writer) {
+        float* dst = rec + n * D + 32 * j + 8 * c;
+        *reinterpret_cast<f32x4*>(dst) = f32x4{o[0], o[1], o[2], o[3]};
+        *reinterpret_cast<f32x4*>(dst + 4) = f32x4{o[4], o[5], o[6], o[7]};
+      }
     }
-    if (writer && c == 0) pml[rec] = make_float2(s.m, l);
+    if (writer && c == 0) *reinterpret_cast<float2*>(rec + G * D + 2 * n) = make_float2(s.m, l);
   }
 };
 
@@ -198,10 +232,10 @@ hipError_t launch_one(const Params& p, int waves, const void* q, const void* k_p
 hipError_t launch_decode_mfma(const Params& p, int waves, const void* q, const void* k_pool,
                               const void* v_pool, const int32_t* header, const int4* desc,
                               float2* partial_ml, float* partial_acc, hipStream_t st) {
-  static const int nbuf = getenv("VOX_NBUF") ? atoi(getenv("VOX_NBUF")) : 2;
+  static const int nbuf = getenv("VOX_NBUF") ? atoi(getenv("VOX_NBUF")) : 3;
 #define VOX_GO(DD, NB) launch_one<DD, NB>(p, waves, q, k_pool, v_pool, header, desc, partial_ml, partial_acc, st)
-  if (p.D == 128) return nbuf == 4 ? VOX_GO(128, 4) : nbuf == 3 ? VOX_GO(128, 3) : VOX_GO(128, 2);
-  return nbuf == 4 ? VOX_GO(64, 4) : nbuf == 3 ? VOX_GO(64, 3) : VOX_GO(64, 2);
+  if (p.D == 128) return nbuf == 2 ? VOX_GO(128, 2) : VOX_GO(128, 3);
+  return nbuf == 2 ? VOX_GO(64, 2) : nbuf == 3 ? VOX_GO(64, 3) : nbuf == 4 ? VOX_GO(64, 4) : VOX_GO(64, 6);
 }
 
 }  // namespace vox

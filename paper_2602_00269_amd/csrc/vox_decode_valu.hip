@@ -2,15 +2,16 @@
 // alternative to the MFMA arithmetic; both run inside the same split-K kernel skeleton.
 //
 // A step's two 16-token blocks are processed one after the other.  Per block:
-//   K granule [D/8][16][8]: lane l reads 16 bytes at (l + 64*kk)*16, i.e. token l%16 and the
-//     8-dim slices l/16 + 4*kk.  Partial dot products (v_dot2_f32_bf16) of the G query heads
-//     are summed over the four lane groups, so every group ends with the 16 scores.  The G
-//     query rows of the run live in a wave-private LDS tile (they are contiguous in q) and
-//     are read back with broadcast 16-byte reads.
-//   online softmax per head with a 16-lane DPP max; probabilities go through a wave-private
-//     LDS row so each lane can read the 8 it needs for its V slice.
-//   V granule [D][16]: lane l reads 16 bytes at (l + 64*i)*16 = dim l/2 + 32*i, tokens
-//     8*(l%2) .. +8; fp32 FMAs into acc[g][i]; lane pairs are summed when a run ends.
+//   K granule [D/32][16][32]: lane l reads 16 bytes at (l + 64*i)*16, i.e. token l/4 and dims
+//     32*i + 8*(l%4) .. +8.  Partial dot products (v_dot2_f32_bf16) of the G query heads are
+//     summed over each lane quad (DPP), so all four lanes of a quad hold the token's scores.
+//     The G query rows of the run live in a wave-private LDS tile (they are contiguous in q)
+//     and are read back with 16-byte reads.
+//   online softmax per head with a wave-wide max; probabilities go through a wave-private LDS
+//     row so each lane can read the 4 it needs for its V piece.
+//   V granule [4][D][4]: lane l reads 16 bytes at (l + 64*i)*16 = token quad (l + 64*i)/(D/2),
+//     dims 2*m and 2*m+1 with m = (l + 64*i) % (D/2); fp32 FMAs into acc[g][0..1].  For D = 64
+//     two lanes share a dim pair and are summed when a run ends.
 #include "vox_decode_core.hpp"
 
 namespace vox {
@@ -51,7 +52,7 @@ struct ValuMath {
   static constexpr int kMinWavesPerSimd = 2;
   static constexpr int NL = D / 32;  // 16-byte loads per lane per granule
 
-  static constexpr int QCHUNKS = G * D / 8;             // 16-byte pieces of the G query rows
+  static constexpr int QCHUNKS = G * D / 8;                 // 16-byte pieces of the G query rows
   static constexpr int QPL = (QCHUNKS + kWave - 1) / kWave;  // pieces per lane
 
   struct Q {
@@ -61,20 +62,19 @@ struct ValuMath {
     u32x4 k[2][NL], v[2][NL];
   };
   struct State {
-    float m[G], l[G], acc[G][NL];
+    float m[G], l[G], acc[G][2];
   };
 
   const Params& p;
-  int lane, t, grp, half;
+  int lane, tok, part;
   float (*p_lds)[kBlock];  // this wave's [G][16] probabilities
   u32x4* q_lds;            // this wave's [G][D/8] query slices
 
   __device__ ValuMath(int lane_, const Params& p_) : p(p_), lane(lane_) {
     __shared__ float lds_p[kWavesPerGroup][G][kBlock];
     __shared__ u32x4 lds_q[kWavesPerGroup][QCHUNKS];
-    t = lane & 15;
-    grp = lane >> 4;
-    half = lane & 1;
+    tok = lane >> 2;
+    part = lane & 3;
     p_lds = lds_p[threadIdx.x >> 6];
     q_lds = lds_q[threadIdx.x >> 6];
   }
@@ -123,35 +123,39 @@ struct ValuMath {
     for (int g = 0; g < G; ++g) {
       s.m[g] = -INFINITY;
       s.l[g] = 0.f;
-#pragma unroll
-      for (int i = 0; i < NL; ++i) s.acc[g][i] = 0.f;
+      s.acc[g][0] = s.acc[g][1] = 0.f;
     }
   }
 
   __device__ void block(State& s, const u32x4 (&kb)[NL], const u32x4 (&vb)[NL], int ntok) const {
-    const bool valid = t < ntok;
+    const bool valid = tok < ntok;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float a = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < NL; ++kk) {
-        const u32x4 qv = q_lds[g * (D / 8) + grp + 4 * kk];
-        a = dot2(kb[kk].x, qv.x, a);
-        a = dot2(kb[kk].y, qv.y, a);
-        a = dot2(kb[kk].z, qv.z, a);
-        a = dot2(kb[kk].w, qv.w, a);
+      for (int i = 0; i < NL; ++i) {
+        const u32x4 qv = q_lds[g * (D / 8) + 4 * i + part];
+        a = dot2(kb[i].x, qv.x, a);
+        a = dot2(kb[i].y, qv.y, a);
+        a = dot2(kb[i].z, qv.z, a);
+        a = dot2(kb[i].w, qv.w, a);
       }
-      a += __shfl_xor(a, 16);
-      a += __shfl_xor(a, 32);
+      a += dpp_f<0xB1>(a);  // lane quad: xor 1
+      a += dpp_f<0x4E>(a);  //            xor 2
       const float sc = valid ? a * p.scale_log2 : -INFINITY;
-      const float m_new = fmaxf(s.m[g], row_max16(sc));
+      float mx = sc;  // max over the wave's 16 tokens
+      mx = fmaxf(mx, dpp_f<0x141>(mx));
+      mx = fmaxf(mx, dpp_f<0x140>(mx));
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(s.m[g], mx);
       const float alpha = exp2f(s.m[g] - m_new);  // exp2(-inf) = 0 on the first block
       const float pr = exp2f(sc - m_new);
-      s.l[g] = s.l[g] * alpha + pr;
+      s.l[g] = s.l[g] * alpha + pr;  // every lane of a quad carries its token's term
       s.m[g] = m_new;
-#pragma unroll
-      for (int i = 0; i < NL; ++i) s.acc[g][i] *= alpha;
-      if (grp == 0) p_lds[g][t] = pr;
+      s.acc[g][0] *= alpha;
+      s.acc[g][1] *= alpha;
+      if (part == 0) p_lds[g][tok] = pr;
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -160,27 +164,28 @@ struct ValuMath {
     const bool tail = ntok < kBlock;  // wave-uniform
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
+      const int quad = (lane + kWave * i) / (D / 2);  // token quad of this 16-byte piece
       float v[8] = {bf16_lo(vb[i].x), bf16_hi(vb[i].x), bf16_lo(vb[i].y), bf16_hi(vb[i].y),
                     bf16_lo(vb[i].z), bf16_hi(vb[i].z), bf16_lo(vb[i].w), bf16_hi(vb[i].w)};
       if (tail) {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          if (half * 8 + e >= ntok) v[e] = 0.f;  // unread slots may hold NaN
+          if (4 * quad + (e & 3) >= ntok) v[e] = 0.f;  // unread slots may hold NaN
       }
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float4 pa = *reinterpret_cast<const float4*>(&p_lds[g][half * 8]);
-        const float4 pb = *reinterpret_cast<const float4*>(&p_lds[g][half * 8 + 4]);
-        float a = s.acc[g][i];
-        a = fmaf(pa.x, v[0], a);
-        a = fmaf(pa.y, v[1], a);
-        a = fmaf(pa.z, v[2], a);
-        a = fmaf(pa.w, v[3], a);
-        a = fmaf(pb.x, v[4], a);
-        a = fmaf(pb.y, v[5], a);
-        a = fmaf(pb.z, v[6], a);
-        a = fmaf(pb.w, v[7], a);
-        s.acc[g][i] = a;
+        const float4 pq = *reinterpret_cast<const float4*>(&p_lds[g][4 * quad]);
+        float a0 = s.acc[g][0], a1 = s.acc[g][1];
+        a0 = fmaf(pq.x, v[0], a0);
+        a0 = fmaf(pq.y, v[1], a0);
+        a0 = fmaf(pq.z, v[2], a0);
+        a0 = fmaf(pq.w, v[3], a0);
+        a1 = fmaf(pq.x, v[4], a1);
+        a1 = fmaf(pq.y, v[5], a1);
+        a1 = fmaf(pq.z, v[6], a1);
+        a1 = fmaf(pq.w, v[7], a1);
+        s.acc[g][0] = a0;
+        s.acc[g][1] = a1;
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -192,18 +197,26 @@ struct ValuMath {
     if (ntok > kBlock) block(s, r.k[1], r.v[1], ntok - kBlock);
   }
 
-  __device__ void finish(State& s, int slot, float2* __restrict__ pml,
-                         float* __restrict__ pacc) const {
+  __device__ void finish(State& s, float* __restrict__ rec) const {
+    const int m = lane % (D / 2);  // dim pair owned by this lane
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const float lsum = row_sum16(s.l[g]);
-      const size_t rec = (size_t)slot * G + g;
-      if (lane == 0) pml[rec] = make_float2(s.m[g], lsum);
-#pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        const float a = s.acc[g][i] + __shfl_xor(s.acc[g][i], 1);
-        if (half == 0) pacc[rec * D + (lane >> 1) + 32 * i] = a;
+      // every token's term sits in the four lanes of its quad: sum the wave and divide by 4
+      float lsum = s.l[g];
+      lsum += dpp_f<0xB1>(lsum);
+      lsum += dpp_f<0x4E>(lsum);
+      lsum += dpp_f<0x141>(lsum);
+      lsum += dpp_f<0x140>(lsum);
+      lsum += __shfl_xor(lsum, 16);
+      lsum += __shfl_xor(lsum, 32);
+      lsum *= 0.25f;
+      if (lane == 0) *reinterpret_cast<float2*>(rec + G * D + 2 * g) = make_float2(s.m[g], lsum);
+      float a0 = s.acc[g][0], a1 = s.acc[g][1];
+      if (D == 64) {  // lanes l and l + 32 hold the same dim pair for different token quads
+        a0 += __shfl_xor(a0, 32);
+        a1 += __shfl_xor(a1, 32);
       }
+      if (lane < D / 2) *reinterpret_cast<float2*>(rec + g * D + 2 * m) = make_float2(a0, a1);
     }
   }
 };

@@ -2,7 +2,7 @@
 
 These are written independently of both the oracle's C index arithmetic and the HIP
 kernels: pools are viewed through numpy reshapes that spell the layout the header documents,
-  K granule (blk, h) = [D/8][B][8]   V granule (blk, h) = [D][B]
+  K granule (blk, h) = [D/32][B][32]   V granule (blk, h) = [B/4][D][4]
 """
 
 import math
@@ -31,13 +31,13 @@ def from_bits(b) -> np.ndarray:
 
 
 def k_view(pool: np.ndarray, hkv: int, d: int) -> np.ndarray:
-    """[P, Hkv, B*D] -> view indexed [blk, h, d // 8, t, d % 8]."""
-    return pool.reshape(pool.shape[0], hkv, d // 8, B, 8)
+    """[P, Hkv, B*D] -> view indexed [blk, h, d // 32, t, d % 32]."""
+    return pool.reshape(pool.shape[0], hkv, d // 32, B, 32)
 
 
 def v_view(pool: np.ndarray, hkv: int, d: int) -> np.ndarray:
-    """[P, Hkv, B*D] -> view indexed [blk, h, d, t]."""
-    return pool.reshape(pool.shape[0], hkv, d, B)
+    """[P, Hkv, B*D] -> view indexed [blk, h, t // 4, d, t % 4]."""
+    return pool.reshape(pool.shape[0], hkv, B // 4, d, 4)
 
 
 def pack_pools(k_rows, v_rows, tables, num_blocks, hkv, d, fill=0x7FC0):
@@ -50,8 +50,8 @@ def pack_pools(k_rows, v_rows, tables, num_blocks, hkv, d, fill=0x7FC0):
             blk = int(tables[s, t // B])
             assert 0 <= blk < num_blocks
             for h in range(hkv):
-                kv[blk, h, :, t % B, :] = kr[t, h].reshape(d // 8, 8)
-                vv[blk, h, :, t % B] = vr[t, h]
+                kv[blk, h, :, t % B, :] = kr[t, h].reshape(d // 32, 32)
+                vv[blk, h, (t % B) // 4, :, t % 4] = vr[t, h]
     return kp, vp
 
 
@@ -66,7 +66,7 @@ def unpack_rows(k_pool, v_pool, tables, lens, hkv, d):
             blk = int(tables[s, t // B])
             for h in range(hkv):
                 kr[t, h] = kv[blk, h, :, t % B, :].reshape(d)
-                vr[t, h] = vv[blk, h, :, t % B]
+                vr[t, h] = vv[blk, h, (t % B) // 4, :, t % 4]
         ks.append(kr)
         vs.append(vr)
     return ks, vs

@@ -208,7 +208,7 @@ def test_unread_slots_may_hold_nan(dev, path):
         last = int(tables[s, (L - 1) // 16])
         for t in range(L % 16 or 16, 16):
             kv[last, :, :, t, :] = 0x7FC0 if t % 2 else 0x7F80  # NaN / +inf
-            vv[last, :, :, t] = 0xFFC1 if t % 2 else 0xFF80  # NaN / -inf
+            vv[last, :, t // 4, :, t % 4] = 0xFFC1 if t % 2 else 0xFF80  # NaN / -inf
         nb = (L + 15) // 16
         # entries past the last block point at a poisoned-but-valid block id or a bogus one
         tables[s, nb:] = -1
@@ -255,13 +255,13 @@ def test_single_key_and_equal_scores_closed_forms(dev):
         vv = v_view(vp, 2, 64)
         for s1 in (0, 1, 3):
             blk = int(w.block_tables[s1, 0])
-            row = (vv[blk, :, :, 0].astype(np.uint32) << 16).view(np.float32)  # [Hkv, D]
+            row = (vv[blk, :, 0, :, 0].astype(np.uint32) << 16).view(np.float32)  # [Hkv, D]
             for i in range(8):
                 assert np.array_equal(out[s1, i], row[i // 4]), f"single key path{path}"
         rows = []
         for t in range(L):
             blk = int(w.block_tables[s, t // 16])
-            rows.append((vv[blk, :, :, t % 16].astype(np.uint32) << 16).view(np.float32))
+            rows.append((vv[blk, :, (t % 16) // 4, :, t % 4].astype(np.uint32) << 16).view(np.float32))
         mean = np.mean(np.stack(rows).astype(np.float64), axis=0)
         for i in range(8):
             assert np.abs(out[s, i] - mean[i // 4]).max() <= 1e-5, f"equal scores path{path}"

@@ -137,7 +137,7 @@ def test_unread_slots_may_hold_nan_or_inf():
         last = int(tables[s, (int(L) - 1) // B])
         for t in range(int(L) % B or B, B):  # tail slots of the last block
             kv[last, :, :, t, :] = 0x7F80  # +inf
-            vv[last, :, :, t] = 0xFFC1  # NaN
+            vv[last, :, t // 4, :, t % 4] = 0xFFC1  # NaN
         tables[s, (int(L) + B - 1) // B:] = -7  # entries past the last block
     kp[pr["unused"]] = 0x7FFF
     vp[pr["unused"]] = 0xFF80  # -inf
