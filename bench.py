@@ -24,9 +24,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 
-# HBM bytes per attention-kernel launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
-# the same counters on a plain copy kernel; filled in per workload from profiles/.
-MEASURED_TRAFFIC = {}
+# HBM bytes per attention-kernel launch from rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
+# scaled by what the same counter reads for a plain 1 GiB device copy); the runs are summarised
+# in profiles/decode_kernel_<workload>.txt.  Workloads without a counter run report null.
+MEASURED_TRAFFIC = {"cfg3": 2351725784}
 
 
 def cpu_model() -> str:
@@ -54,13 +55,15 @@ def main() -> int:
     ap.add_argument("--no-device-lens-only", dest="host_lens", action="store_true", default=True)
     ap.add_argument("--device-lens-only", dest="host_lens", action="store_false",
                     help="do not hand the host copy of context_lens to the library")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (known traffic for scaling HBM counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
 
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
-              "(the decode step shards by stream or by kv head with no exchange, see DESIGN.md)",
+              "(the decode step shards by stream or by kv head with no exchange between GPUs)",
               file=sys.stderr)
         return 2
 
@@ -104,6 +107,13 @@ def main() -> int:
 
     def step(i):
         binding.decode_step(sh, step_args[i % copies], bt, lens, ws, context_lens_host=host_lens)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- timed region A: the production entry point, whole step
     for i in range(args.warmup):
@@ -173,15 +183,18 @@ def main() -> int:
         cum = np.cumsum(base.context_lens.astype(np.int64))
         n = int(np.searchsorted(cum, rate * args.cpu_seconds) + 1)
         n = max(probe_n, min(base.num_streams, n))
-        secs = run(n)
         toks = int(cum[n - 1])
+        passes, secs = 0, 0.0
+        while passes == 0 or (secs < args.cpu_seconds and passes < 64):
+            secs += run(n)  # whole sample again: the oracle is fast on many-core hosts
+            passes += 1
         cpu = {
-            "value": round(toks * per_tok / secs / 1e9, 4),
+            "value": round(passes * toks * per_tok / secs / 1e9, 4),
             "unit": "GB/s",
             "cores": oracle.num_threads(),
             "kind": "oracle",
             "sample": f"fp64 oracle decode of streams [0,{n}) of {base.num_streams} "
-                      f"({toks} tokens, layer 0) in {secs:.2f} s",
+                      f"({toks} tokens, layer 0), {passes} passes in {secs:.2f} s",
             "cpu_model": cpu_model(),
             "host_cpus": os.cpu_count(),
         }
