@@ -110,15 +110,24 @@ int enqueue_plan(const Params& p, const Plan& plan, char* ws, const int32_t* bt,
   return e == hipSuccess ? VOX_OK : VOX_ERR_HIP;
 }
 
-int enqueue_decode(const vox_shape_t* s, const Params& p, const Plan& plan, char* ws,
-                   const void* q, const void* k_pool, const void* v_pool, float* out, float* lse,
-                   hipStream_t st, hipEvent_t ev_before = nullptr,
-                   hipEvent_t ev_after = nullptr) {
-  const int32_t* header = (const int32_t*)(ws + plan.ws.header);
-  const int32_t* step_prefix = (const int32_t*)(ws + plan.ws.step_prefix);
-  const int4* desc = (const int4*)(ws + plan.ws.desc);
-  float2* pml = (float2*)(ws + plan.ws.partial_ml);
-  float* pacc = (float*)(ws + plan.ws.partial_acc);
+struct WsPtrs {
+  int32_t* header;
+  int32_t* step_prefix;
+  int4* desc;
+  float2* pml;
+  float* pacc;
+};
+
+WsPtrs ws_ptrs(const Plan& plan, char* ws) {
+  return WsPtrs{(int32_t*)(ws + plan.ws.header), (int32_t*)(ws + plan.ws.step_prefix),
+                (int4*)(ws + plan.ws.desc), (float2*)(ws + plan.ws.partial_ml),
+                (float*)(ws + plan.ws.partial_acc)};
+}
+
+// The split-K attention launch alone (the merge follows separately).
+int enqueue_attention(const vox_shape_t* s, const Params& p, const Plan& plan, const WsPtrs& w,
+                      const void* q, const void* k_pool, const void* v_pool, hipStream_t st,
+                      hipEvent_t ev_before = nullptr, hipEvent_t ev_after = nullptr) {
   // no more waves than steps can exist (each launched wave without a range exits at once)
   int waves = plan.waves;
   if (plan.max_steps < waves)
@@ -126,15 +135,13 @@ int enqueue_decode(const vox_shape_t* s, const Params& p, const Plan& plan, char
   if (ev_before && hipEventRecord(ev_before, st) != hipSuccess) return VOX_ERR_HIP;
   if (waves > 0) {
     hipError_t e = (s->decode_path == VOX_PATH_VALU)
-                       ? launch_decode_valu(p, waves, q, k_pool, v_pool, header, desc, pml, pacc,
-                                            st)
-                       : launch_decode_mfma(p, waves, q, k_pool, v_pool, header, desc, pml, pacc,
-                                            st);
+                       ? launch_decode_valu(p, waves, q, k_pool, v_pool, w.header, w.desc, w.pml,
+                                            w.pacc, st)
+                       : launch_decode_mfma(p, waves, q, k_pool, v_pool, w.header, w.desc, w.pml,
+                                            w.pacc, st);
     if (e != hipSuccess) return VOX_ERR_HIP;
   }
   if (ev_after && hipEventRecord(ev_after, st) != hipSuccess) return VOX_ERR_HIP;
-  if (launch_merge(p, header, step_prefix, pml, pacc, out, lse, st) != hipSuccess)
-    return VOX_ERR_HIP;
   return VOX_OK;
 }
 
@@ -200,8 +207,13 @@ int vox_paged_decode_profiled(const vox_shape_t* shape, const void* q, const voi
   hipStream_t st = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
   if (int rc = enqueue_plan(p, plan, ws, block_tables, context_lens, st)) return rc;
-  return enqueue_decode(shape, p, plan, ws, q, k_pool, v_pool, out, lse, st,
-                        (hipEvent_t)event_before, (hipEvent_t)event_after);
+  const WsPtrs w = ws_ptrs(plan, ws);
+  if (int rc = enqueue_attention(shape, p, plan, w, q, k_pool, v_pool, st,
+                                 (hipEvent_t)event_before, (hipEvent_t)event_after))
+    return rc;
+  return launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out, lse, st) == hipSuccess
+             ? VOX_OK
+             : VOX_ERR_HIP;
 }
 
 int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* const* q,
@@ -223,14 +235,22 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
   const Params p = make_params(shape);
   hipStream_t st = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
-  if (int rc = enqueue_plan(p, plan, ws, block_tables, context_lens, st)) return rc;
+  const WsPtrs w = ws_ptrs(plan, ws);
+  // Launch chain: [plan + append(0)] attention(0) [merge(0) + append(1)] attention(1) ...
+  // merge(L-1).  Each bracket is one launch of two independent roles.
+  if (launch_plan_append(p, block_tables, context_lens, plan.waves, plan.desc_capacity,
+                         plan.max_steps, w.header, w.step_prefix, w.desc, k_new[0], v_new[0],
+                         k_pool[0], v_pool[0], st) != hipSuccess)
+    return VOX_ERR_HIP;
   for (int l = 0; l < num_layers; ++l) {
-    if (launch_kv_append(p, k_new[l], v_new[l], k_pool[l], v_pool[l], block_tables, context_lens,
-                         st) != hipSuccess)
-      return VOX_ERR_HIP;
-    if (int rc = enqueue_decode(shape, p, plan, ws, q[l], k_pool[l], v_pool[l], out[l], nullptr,
-                                st))
-      return rc;
+    if (int rc = enqueue_attention(shape, p, plan, w, q[l], k_pool[l], v_pool[l], st)) return rc;
+    hipError_t e =
+        l + 1 < num_layers
+            ? launch_merge_append(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], block_tables,
+                                  context_lens, k_new[l + 1], v_new[l + 1], k_pool[l + 1],
+                                  v_pool[l + 1], st)
+            : launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], nullptr, st);
+    if (e != hipSuccess) return VOX_ERR_HIP;
   }
   return VOX_OK;
 }

@@ -14,14 +14,13 @@ namespace {
 typedef uint32_t au32x4 __attribute__((ext_vector_type(4)));
 
 template <int D>
-__global__ __launch_bounds__(256) void kv_append_kernel(Params p, const uint16_t* __restrict__ k_new,
-                                                        const uint16_t* __restrict__ v_new,
-                                                        uint16_t* __restrict__ k_pool,
-                                                        uint16_t* __restrict__ v_pool,
-                                                        const int32_t* __restrict__ bt,
-                                                        const int32_t* __restrict__ lens) {
+__device__ inline void append_role(const Params& p, int group, const uint16_t* __restrict__ k_new,
+                                   const uint16_t* __restrict__ v_new,
+                                   uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool,
+                                   const int32_t* __restrict__ bt,
+                                   const int32_t* __restrict__ lens) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int sigma = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
+  const int sigma = group * kWavesPerGroup + (threadIdx.x >> 6);
   if (sigma >= p.S * p.Hkv) return;
   const int s = sigma / p.Hkv, h = sigma % p.Hkv;
   const int L = lens[s];
@@ -47,6 +46,21 @@ __global__ __launch_bounds__(256) void kv_append_kernel(Params p, const uint16_t
     r[2 + (e >> 1)] = (r[2 + (e >> 1)] & keep) | (d1 << sh);
     *reinterpret_cast<au32x4*>(quad) = r;
   }
+}
+
+// The buffers of one layer's append, passed by value to the kernels that carry an append role.
+struct AppendArgs {
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  uint16_t* k_pool;
+  uint16_t* v_pool;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void kv_append_kernel(Params p, AppendArgs a,
+                                                        const int32_t* __restrict__ bt,
+                                                        const int32_t* __restrict__ lens) {
+  append_role<D>(p, blockIdx.x, a.k_new, a.v_new, a.k_pool, a.v_pool, bt, lens);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -91,47 +105,47 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(Params p, const uint16_t
 // ---------------------------------------------------------------------------------------
 // Plan: writes the step prefix, the header (N, Q, W) and one descriptor per global step.
 // Every workgroup rebuilds the exclusive scan of n_s = ceil(ceil(L_s/16)/2) in LDS (S is
-// small), then its threads expand kPlanStepsPerGroup global steps: binary search for the
-// stream, then head and step inside the segment.  Workgroup 0 also publishes the scan.
+// small: a slice per thread, a shuffle scan per wave, one pass over the wave totals), then
+// each thread expands one global step: binary search for the stream, then head and step
+// inside the segment.  Workgroup 0 also publishes the scan.
 constexpr int kPlanThreads = 256;
-constexpr int kPlanStepsPerGroup = 2048;
 constexpr int kPlanMaxStreams = kMaxStreams;  // LDS-resident prefix
 
-__global__ __launch_bounds__(kPlanThreads) void plan_kernel(
-    Params p, const int32_t* __restrict__ bt, const int32_t* __restrict__ lens, int waves,
-    int64_t desc_capacity, int32_t* __restrict__ header, int32_t* __restrict__ step_prefix,
-    int4* __restrict__ desc) {
+__device__ inline void plan_role(const Params& p, int group, const int32_t* __restrict__ bt,
+                                 const int32_t* __restrict__ lens, int waves,
+                                 int64_t desc_capacity, int32_t* __restrict__ header,
+                                 int32_t* __restrict__ step_prefix, int4* __restrict__ desc) {
   __shared__ int prefix[kPlanMaxStreams + 1];
-  __shared__ int wsum[kPlanThreads];
-  const int tid = threadIdx.x;
+  __shared__ int wave_total[kPlanThreads / kWave];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
   const int S = p.S;
-  // each thread scans a contiguous slice of streams, then the slice totals are scanned
   const int per = (S + kPlanThreads - 1) / kPlanThreads;
   const int lo = min(S, tid * per), hi = min(S, lo + per);
   int run = 0;
   for (int s = lo; s < hi; ++s) {
     const int L = lens[s];
     const int nb = L > 0 ? (L + kBlock - 1) / kBlock : 0;
-    prefix[s] = run;
+    prefix[s] = run;  // exclusive inside the slice
     run += (nb + 1) >> 1;
   }
-  wsum[tid] = run;
-  __syncthreads();
-  for (int off = 1; off < kPlanThreads; off <<= 1) {
-    const int v = tid >= off ? wsum[tid - off] : 0;
-    __syncthreads();
-    wsum[tid] += v;
-    __syncthreads();
+  int incl = run;  // inclusive scan of the slice totals inside the wave
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
   }
-  const int before = wsum[tid] - run;
+  if (lane == kWave - 1) wave_total[wv] = incl;
+  __syncthreads();
+  int before = incl - run;
+  for (int k = 0; k < wv; ++k) before += wave_total[k];
   for (int s = lo; s < hi; ++s) prefix[s] += before;
-  if (tid == kPlanThreads - 1) prefix[S] = wsum[tid];
+  if (tid == kPlanThreads - 1) prefix[S] = before + run;
   __syncthreads();
 
   const int64_t n_all = (int64_t)prefix[S] * p.Hkv;
   const int64_t N = min(n_all, desc_capacity);
   const int Q = (int)max((int64_t)1, (N + waves - 1) / waves);
-  if (blockIdx.x == 0) {
+  if (group == 0) {
     for (int s = tid; s <= S; s += kPlanThreads) step_prefix[s] = prefix[s];
     if (tid == 0) {
       header[kHdrSteps] = (int)N;
@@ -141,33 +155,52 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     }
   }
 
-  const int64_t x_begin = (int64_t)blockIdx.x * kPlanStepsPerGroup;
-  for (int64_t x = x_begin + tid; x < min(N, x_begin + kPlanStepsPerGroup); x += kPlanThreads) {
-    // largest s with Hkv * prefix[s] <= x (streams with n_s == 0 share a prefix and are skipped)
-    int a = 0, b = S;
-    while (b - a > 1) {
-      const int mid = (a + b) >> 1;
-      if ((int64_t)prefix[mid] * p.Hkv <= x)
-        a = mid;
-      else
-        b = mid;
-    }
-    const int s = a;
-    const int n = prefix[s + 1] - prefix[s];
-    const int r = (int)(x - (int64_t)prefix[s] * p.Hkv);
-    const int h = r / n, st = r - h * n;
-    const int L = lens[s];
-    const int nb = (L + kBlock - 1) / kBlock;
-    const int32_t* row = bt + (size_t)s * p.max_nb;
-    const int ida = row[2 * st];
-    const int idb = (2 * st + 1 < nb) ? row[2 * st + 1] : ida;
-    const int ntok = min(kStepTokens, L - kStepTokens * st);
-    int meta = ntok;
-    if (st == 0 || x % Q == 0) meta |= kMetaFirst;
-    if (st == n - 1 || x % Q == Q - 1 || x == N - 1) meta |= kMetaLast;
-    if (st == n - 1) meta |= kMetaTail;
-    desc[x] = make_int4(ida * p.Hkv + h, idb * p.Hkv + h, meta, s * p.Hkv + h);
+  const int64_t x = (int64_t)group * kPlanThreads + tid;
+  if (x >= N) return;
+  // largest s with Hkv * prefix[s] <= x (streams with n_s == 0 share a prefix and are skipped)
+  int a = 0, b = S;
+  while (b - a > 1) {
+    const int mid = (a + b) >> 1;
+    if ((int64_t)prefix[mid] * p.Hkv <= x)
+      a = mid;
+    else
+      b = mid;
   }
+  const int s = a;
+  const int n = prefix[s + 1] - prefix[s];
+  const int r = (int)(x - (int64_t)prefix[s] * p.Hkv);
+  const int h = r / n, st = r - h * n;
+  const int L = lens[s];
+  const int nb = (L + kBlock - 1) / kBlock;
+  const int32_t* row = bt + (size_t)s * p.max_nb;
+  const int ida = row[2 * st];
+  const int idb = (2 * st + 1 < nb) ? row[2 * st + 1] : ida;
+  const int ntok = min(kStepTokens, L - kStepTokens * st);
+  int meta = ntok;
+  if (st == 0 || x % Q == 0) meta |= kMetaFirst;
+  if (st == n - 1 || x % Q == Q - 1 || x == N - 1) meta |= kMetaLast;
+  if (st == n - 1) meta |= kMetaTail;
+  desc[x] = make_int4(ida * p.Hkv + h, idb * p.Hkv + h, meta, s * p.Hkv + h);
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(
+    Params p, const int32_t* __restrict__ bt, const int32_t* __restrict__ lens, int waves,
+    int64_t desc_capacity, int32_t* __restrict__ header, int32_t* __restrict__ step_prefix,
+    int4* __restrict__ desc) {
+  plan_role(p, blockIdx.x, bt, lens, waves, desc_capacity, header, step_prefix, desc);
+}
+
+// Plan and the first layer's append in one launch: the two are independent and both are
+// short chains of dependent loads, so running them side by side hides one behind the other.
+template <int D>
+__global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
+    Params p, int plan_groups, AppendArgs a, const int32_t* __restrict__ bt,
+    const int32_t* __restrict__ lens, int waves, int64_t desc_capacity,
+    int32_t* __restrict__ header, int32_t* __restrict__ step_prefix, int4* __restrict__ desc) {
+  if ((int)blockIdx.x < plan_groups)
+    plan_role(p, blockIdx.x, bt, lens, waves, desc_capacity, header, step_prefix, desc);
+  else
+    append_role<D>(p, blockIdx.x - plan_groups, a.k_new, a.v_new, a.k_pool, a.v_pool, bt, lens);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -187,15 +220,13 @@ __device__ inline float wave_sum(float v) {
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void merge_kernel(Params p, const int32_t* __restrict__ header,
-                                                    const int32_t* __restrict__ step_prefix,
-                                                    const float2* __restrict__ pml,
-                                                    const float* __restrict__ pacc,
-                                                    float* __restrict__ out,
-                                                    float* __restrict__ lse) {
+__device__ inline void merge_role(const Params& p, int group, const int32_t* __restrict__ header,
+                                  const int32_t* __restrict__ step_prefix,
+                                  const float2* __restrict__ pml, const float* __restrict__ pacc,
+                                  float* __restrict__ out, float* __restrict__ lse) {
   constexpr int DPL = D / kWave;  // dims per lane
   const int lane = threadIdx.x & (kWave - 1);
-  const int w = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
+  const int w = group * kWavesPerGroup + (threadIdx.x >> 6);
   if (w >= p.S * p.Hq) return;
   const int s = w / p.Hq, i = w % p.Hq;
   const int h = i / p.G, g = i % p.G;
@@ -249,20 +280,55 @@ __global__ __launch_bounds__(256) void merge_kernel(Params p, const int32_t* __r
         (n > 0 && l_run > 0.f) ? (m_run + log2f(l_run)) * 0.69314718055994530942f : -INFINITY;
 }
 
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(Params p, const int32_t* __restrict__ header,
+                                                    const int32_t* __restrict__ step_prefix,
+                                                    const float2* __restrict__ pml,
+                                                    const float* __restrict__ pacc,
+                                                    float* __restrict__ out,
+                                                    float* __restrict__ lse) {
+  merge_role<D>(p, blockIdx.x, header, step_prefix, pml, pacc, out, lse);
+}
+
+// Merge of layer l and the append of layer l + 1 in one launch (independent buffers).
+template <int D>
+__global__ __launch_bounds__(256) void merge_append_kernel(
+    Params p, int merge_grps, const int32_t* __restrict__ header,
+    const int32_t* __restrict__ step_prefix, const float2* __restrict__ pml,
+    const float* __restrict__ pacc, float* __restrict__ out, AppendArgs a,
+    const int32_t* __restrict__ bt, const int32_t* __restrict__ lens) {
+  if ((int)blockIdx.x < merge_grps)
+    merge_role<D>(p, blockIdx.x, header, step_prefix, pml, pacc, out, nullptr);
+  else
+    append_role<D>(p, blockIdx.x - merge_grps, a.k_new, a.v_new, a.k_pool, a.v_pool, bt, lens);
+}
+
 }  // namespace
+
+static AppendArgs append_args(const void* k_new, const void* v_new, void* k_pool, void* v_pool) {
+  return AppendArgs{(const uint16_t*)k_new, (const uint16_t*)v_new, (uint16_t*)k_pool,
+                    (uint16_t*)v_pool};
+}
+static unsigned host_append_groups(const Params& p) {
+  return (unsigned)(((int64_t)p.S * p.Hkv + kWavesPerGroup - 1) / kWavesPerGroup);
+}
+static unsigned host_merge_groups(const Params& p) {
+  return (unsigned)(((int64_t)p.S * p.Hq + kWavesPerGroup - 1) / kWavesPerGroup);
+}
+static unsigned host_plan_groups(int64_t max_steps) {
+  return (unsigned)max((int64_t)1, (max_steps + kPlanThreads - 1) / kPlanThreads);
+}
 
 hipError_t launch_kv_append(const Params& p, const void* k_new, const void* v_new, void* k_pool,
                             void* v_pool, const int32_t* bt, const int32_t* lens,
                             hipStream_t st) {
-  const unsigned grid = (unsigned)(((int64_t)p.S * p.Hkv + kWavesPerGroup - 1) / kWavesPerGroup);
+  const AppendArgs a = append_args(k_new, v_new, k_pool, v_pool);
   if (p.D == 128)
-    hipLaunchKernelGGL(kv_append_kernel<128>, dim3(grid), dim3(256), 0, st, p,
-                       (const uint16_t*)k_new, (const uint16_t*)v_new, (uint16_t*)k_pool,
-                       (uint16_t*)v_pool, bt, lens);
+    hipLaunchKernelGGL(kv_append_kernel<128>, dim3(host_append_groups(p)), dim3(256), 0, st, p, a,
+                       bt, lens);
   else
-    hipLaunchKernelGGL(kv_append_kernel<64>, dim3(grid), dim3(256), 0, st, p,
-                       (const uint16_t*)k_new, (const uint16_t*)v_new, (uint16_t*)k_pool,
-                       (uint16_t*)v_pool, bt, lens);
+    hipLaunchKernelGGL(kv_append_kernel<64>, dim3(host_append_groups(p)), dim3(256), 0, st, p, a,
+                       bt, lens);
   return hipGetLastError();
 }
 
@@ -281,23 +347,55 @@ hipError_t launch_plan(const Params& p, const int32_t* bt, const int32_t* lens, 
                        int64_t desc_capacity, int64_t max_steps, int32_t* header,
                        int32_t* step_prefix, int4* desc, hipStream_t st) {
   if (p.S > kPlanMaxStreams) return hipErrorInvalidValue;
-  const unsigned grid =
-      (unsigned)max((int64_t)1, (max_steps + kPlanStepsPerGroup - 1) / kPlanStepsPerGroup);
-  hipLaunchKernelGGL(plan_kernel, dim3(grid), dim3(kPlanThreads), 0, st, p, bt, lens, waves,
-                     desc_capacity, header, step_prefix, desc);
+  hipLaunchKernelGGL(plan_kernel, dim3(host_plan_groups(max_steps)), dim3(kPlanThreads), 0, st, p,
+                     bt, lens, waves, desc_capacity, header, step_prefix, desc);
+  return hipGetLastError();
+}
+
+hipError_t launch_plan_append(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
+                              int64_t desc_capacity, int64_t max_steps, int32_t* header,
+                              int32_t* step_prefix, int4* desc, const void* k_new,
+                              const void* v_new, void* k_pool, void* v_pool, hipStream_t st) {
+  if (p.S > kPlanMaxStreams) return hipErrorInvalidValue;
+  const unsigned pg = host_plan_groups(max_steps);
+  const AppendArgs a = append_args(k_new, v_new, k_pool, v_pool);
+  if (p.D == 128)
+    hipLaunchKernelGGL(plan_append_kernel<128>, dim3(pg + host_append_groups(p)),
+                       dim3(kPlanThreads), 0, st, p, (int)pg, a, bt, lens, waves, desc_capacity,
+                       header, step_prefix, desc);
+  else
+    hipLaunchKernelGGL(plan_append_kernel<64>, dim3(pg + host_append_groups(p)),
+                       dim3(kPlanThreads), 0, st, p, (int)pg, a, bt, lens, waves, desc_capacity,
+                       header, step_prefix, desc);
   return hipGetLastError();
 }
 
 hipError_t launch_merge(const Params& p, const int32_t* header, const int32_t* step_prefix,
                         const float2* partial_ml, const float* partial_acc, float* out,
                         float* lse, hipStream_t st) {
-  const unsigned grid = (unsigned)(((int64_t)p.S * p.Hq + kWavesPerGroup - 1) / kWavesPerGroup);
   if (p.D == 128)
-    hipLaunchKernelGGL(merge_kernel<128>, dim3(grid), dim3(256), 0, st, p, header, step_prefix,
-                       partial_ml, partial_acc, out, lse);
+    hipLaunchKernelGGL(merge_kernel<128>, dim3(host_merge_groups(p)), dim3(256), 0, st, p, header,
+                       step_prefix, partial_ml, partial_acc, out, lse);
   else
-    hipLaunchKernelGGL(merge_kernel<64>, dim3(grid), dim3(256), 0, st, p, header, step_prefix,
-                       partial_ml, partial_acc, out, lse);
+    hipLaunchKernelGGL(merge_kernel<64>, dim3(host_merge_groups(p)), dim3(256), 0, st, p, header,
+                       step_prefix, partial_ml, partial_acc, out, lse);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_append(const Params& p, const int32_t* header, const int32_t* step_prefix,
+                               const float2* partial_ml, const float* partial_acc, float* out,
+                               const int32_t* bt, const int32_t* lens, const void* k_new,
+                               const void* v_new, void* k_pool, void* v_pool, hipStream_t st) {
+  const unsigned mg = host_merge_groups(p);
+  const AppendArgs a = append_args(k_new, v_new, k_pool, v_pool);
+  if (p.D == 128)
+    hipLaunchKernelGGL(merge_append_kernel<128>, dim3(mg + host_append_groups(p)), dim3(256), 0,
+                       st, p, (int)mg, header, step_prefix, partial_ml, partial_acc, out, a, bt,
+                       lens);
+  else
+    hipLaunchKernelGGL(merge_append_kernel<64>, dim3(mg + host_append_groups(p)), dim3(256), 0,
+                       st, p, (int)mg, header, step_prefix, partial_ml, partial_acc, out, a, bt,
+                       lens);
   return hipGetLastError();
 }
 

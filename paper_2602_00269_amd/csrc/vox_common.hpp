@@ -81,6 +81,14 @@ hipError_t launch_kv_gather(const Params& p, const void* k_pool, const void* v_p
 hipError_t launch_plan(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
                        int64_t desc_capacity, int64_t max_steps, int32_t* header,
                        int32_t* step_prefix, int4* desc, hipStream_t st);
+hipError_t launch_plan_append(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
+                              int64_t desc_capacity, int64_t max_steps, int32_t* header,
+                              int32_t* step_prefix, int4* desc, const void* k_new,
+                              const void* v_new, void* k_pool, void* v_pool, hipStream_t st);
+hipError_t launch_merge_append(const Params& p, const int32_t* header, const int32_t* step_prefix,
+                               const float2* partial_ml, const float* partial_acc, float* out,
+                               const int32_t* bt, const int32_t* lens, const void* k_new,
+                               const void* v_new, void* k_pool, void* v_pool, hipStream_t st);
 hipError_t launch_decode_mfma(const Params& p, int waves, const void* q, const void* k_pool,
                               const void* v_pool, const int32_t* header, const int4* desc,
                               float2* partial_ml, float* partial_acc, hipStream_t st);
