@@ -14,6 +14,9 @@ SOURCES = ["vox_api.hip", "vox_aux_kernels.hip", "vox_decode_mfma.hip", "vox_dec
 # Packed fp32 VALU forms are switched off for device code on purpose.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA operands and results stay in architectural VGPRs where they fit: fewer
+         # v_accvgpr copies between the two register files inside the decode loop
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

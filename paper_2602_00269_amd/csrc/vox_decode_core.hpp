@@ -2,9 +2,8 @@
 //
 // A wave owns the global steps [w*Q, min(N, (w+1)*Q)) and walks them as one flat software
 // pipeline: the K/V loads of step i + NBUF are issued while step i is computed, across segment
-// boundaries, so the load queue never drains inside a wave.  Step descriptors are read 64 at a
-// time into registers (one per lane) and broadcast with v_readlane; two such windows are kept
-// so the load cursor may run ahead of the compute cursor into the next window.  When a run
+// boundaries, so the load queue never drains inside a wave.  Step descriptors are wave-uniform:
+// they come in through scalar loads a few steps ahead and live in scalar registers.  When a run
 // of a segment ends inside the range its partial record is stored and the accumulators are
 // reset; the query rows of the next run are fetched one step ahead.
 //
@@ -87,6 +86,7 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
     const uint16_t* __restrict__ v_pool, const int32_t* __restrict__ header,
     const int4* __restrict__ desc, float2* __restrict__ pml, float* __restrict__ pacc) {
   constexpr int NBUF = Math::kBuffers;
+  constexpr int LA = NBUF + 1;  // descriptor look-ahead in steps
   const int lane = threadIdx.x & (kWave - 1);
   const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6));
   const int N = header[kHdrSteps], Q = header[kHdrPerWave];
@@ -94,11 +94,12 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
   if (x0 >= N) return;
   const int nsteps = (int)min((int64_t)Q, (int64_t)N - x0);
 
-  const u32x4* dbase = reinterpret_cast<const u32x4*>(desc) + x0;
-  u32x4 dw0 = dbase[min(lane, nsteps - 1)];
-  u32x4 dw1 = dbase[min(kWave + lane, nsteps - 1)];
-#define VOX_DESC(I, C) \
-  __builtin_amdgcn_readlane((int)((((I) & kWave) ? dw1 : dw0).C), (I) & (kWave - 1))
+  // Descriptors are wave-uniform: they are fetched with scalar loads LA steps ahead and live in
+  // scalar registers.  dq[k] is the descriptor of step i + k.
+  const int4* dbase = desc + x0;
+  int4 dq[LA + 1];
+#pragma unroll
+  for (int k = 0; k <= LA; ++k) dq[k] = dbase[min(k, nsteps - 1)];
 
   __shared__ float stash_mem[kWavesPerGroup][kStashFloats];
   PartialStash stash(stash_mem[threadIdx.x >> 6], p.G, p.D, lane);
@@ -106,13 +107,12 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
   typename Math::State st;
   typename Math::Q qnext;
   typename Math::Regs ring[NBUF];
-  math.load_q(qnext, q, VOX_DESC(0, w));
+  math.load_q(qnext, q, dq[0].w);
   math.reset(st);
 #pragma unroll
   for (int b = 0; b < NBUF; ++b) {
     const bool more = b < nsteps;
-    math.template issue<true>(ring[b], k_pool, v_pool, more ? VOX_DESC(b, x) : 0,
-                              more ? VOX_DESC(b, y) : 0);
+    math.template issue<true>(ring[b], k_pool, v_pool, more ? dq[b].x : 0, more ? dq[b].y : 0);
   }
 
   // One step of the pipeline.  In the steady-state loop every step refills its ring slot
@@ -123,32 +123,25 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
 #define VOX_STEP(I, B, REFILL)                                                             \
   {                                                                                        \
     const int i = (I);                                                                     \
-    const int meta = VOX_DESC(i, z);                                                       \
-    const int sigma = VOX_DESC(i, w);                                                      \
+    const int meta = dq[0].z;                                                              \
+    const int sigma = dq[0].w;                                                             \
     if (meta & kMetaFirst) {                                                               \
       math.reset(st);                                                                      \
       math.install_q(st, qnext);                                                           \
     }                                                                                      \
     math.compute(st, ring[B], meta & kMetaTokMask);                                        \
-    if (i + 1 < nsteps && (VOX_DESC(i + 1, z) & kMetaFirst))                               \
-      math.load_q(qnext, q, VOX_DESC(i + 1, w));                                           \
+    if (i + 1 < nsteps && (dq[1].z & kMetaFirst)) math.load_q(qnext, q, dq[1].w);          \
     if (REFILL) {                                                                          \
       const bool more = i + NBUF < nsteps;                                                 \
-      const int ga = more ? VOX_DESC(i + NBUF, x) : 0;                                     \
-      const int gb = more ? VOX_DESC(i + NBUF, y) : 0;                                     \
-      math.template issue<true>(ring[B], k_pool, v_pool, ga, gb);                          \
+      math.template issue<true>(ring[B], k_pool, v_pool, more ? dq[NBUF].x : 0,            \
+                                more ? dq[NBUF].y : 0);                                    \
     }                                                                                      \
     if (meta & kMetaLast) {                                                                \
       math.finish(st, stash.next());                                                       \
       stash.commit(w + sigma, pml, pacc);                                                  \
     }                                                                                      \
-    if ((i & (kWave - 1)) == kWave - 1) { /* window i>>6 is spent: fetch window (i>>6)+2 */ \
-      const u32x4 nw = dbase[min(i + 1 + kWave + lane, nsteps - 1)];                       \
-      if (i & kWave)                                                                       \
-        dw1 = nw;                                                                          \
-      else                                                                                 \
-        dw0 = nw;                                                                          \
-    }                                                                                      \
+    _Pragma("unroll") for (int k = 0; k < LA; ++k) dq[k] = dq[k + 1];                      \
+    dq[LA] = dbase[min(i + 1 + LA, nsteps - 1)];                                           \
   }
 
   int i0 = 0;
@@ -161,7 +154,6 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
     if (i0 + b < nsteps) VOX_STEP(i0 + b, b, false)
 #undef VOX_STEP
   stash.flush(pml, pacc);
-#undef VOX_DESC
 }
 
 }  // namespace vox

@@ -25,8 +25,6 @@
 //     loop except the max.
 //     Result layout: lane (n, c), register r of tile 2j+u = dim 32j + 8c + 2r + u of column n,
 //     so the per-column rescale factor is lane-local and a lane owns 8 consecutive dims.
-#include <stdlib.h>
-
 #include "vox_decode_core.hpp"
 
 namespace vox {
@@ -74,14 +72,14 @@ struct MfmaMath {
 
   const Params& p;
   int lane, n, c, G;
-  bool is_lo;
+  float lo_mul;  // 1 for the lo columns [G, 2G), 0 for the hi columns
   int k_off, v_off;
 
   __device__ MfmaMath(int lane_, const Params& p_) : p(p_), lane(lane_) {
     n = lane & 15;
     c = lane >> 4;
     G = p.G;
-    is_lo = n >= G;
+    lo_mul = n >= G ? 1.f : 0.f;
     k_off = n * 32 + c * 8;      // + kk * 512
     v_off = c * D * 4 + n * 8;   // + j * 128
   }
@@ -131,39 +129,20 @@ struct MfmaMath {
       sa = mfma32(r.k[0][kk], s.q.b[kk], sa);
       sb = mfma32(r.k[1][kk], s.q.b[kk], sb);
     }
-    // valid tokens among this lane's four of block A / block B; may be <= 0 or >= 4
-    const int va = ntok - 4 * c, vb = ntok - kBlock - 4 * c;
     float t[8] = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
-    float mx = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const bool ok = e < 4 ? e < va : e - 4 < vb;
-      t[e] = ok ? t[e] * p.scale_log2 : -INFINITY;
-      mx = fmaxf(mx, t[e]);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(s.m, mx);  // finite: lane group 0 always holds a valid token
-    const float alpha = exp2f(s.m - m_new);
-    s.m = m_new;
-    float psum = 0.f;
-    uint32_t pw[4];
-#pragma unroll
-    for (int e = 0; e < 8; e += 2) {
-      const float p0 = exp2f(t[e] - m_new), p1 = exp2f(t[e + 1] - m_new);
-      psum += p0 + p1;
-      const float h0 = round_bf16(p0), h1 = round_bf16(p1);
-      pw[e >> 1] = is_lo ? pack_bf16(p0 - h0, p1 - h1) : pack_bf16(h0, h1);
-    }
-    s.l = s.l * alpha + psum;
-    const u32x2 pa = {pw[0], pw[1]}, pb = {pw[2], pw[3]};
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) s.acc[nt] *= alpha;
-    }
+    for (int e = 0; e < 8; ++e) t[e] *= p.scale_log2;
     if (ntok < kStepTokens) {
-      // Unread slots of a tail may hold NaN/Inf bits and 0 * NaN = NaN: clear them.  A 16-byte
-      // V register is two dims x four tokens: dwords 0,2 hold tokens 0,1 and dwords 1,3 hold 2,3.
+      // Tail of a stream: slots past the last token may hold any bits (NaN/Inf included).
+      // Their scores become -inf by selection, and their V values are cleared because
+      // 0 * NaN = NaN.  A 16-byte V register is two dims x four tokens: dwords 0,2 hold tokens
+      // 0,1 and dwords 1,3 hold tokens 2,3.
+      const int va = ntok - 4 * c, vb = ntok - kBlock - 4 * c;  // valid among the lane's 4 + 4
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (e >= va) t[e] = -INFINITY;
+        if (e >= vb) t[4 + e] = -INFINITY;
+      }
       const auto mask4 = [](int valid) {
         const uint32_t lo = (0 < valid ? 0x0000FFFFu : 0u) | (1 < valid ? 0xFFFF0000u : 0u);
         const uint32_t hi = (2 < valid ? 0x0000FFFFu : 0u) | (3 < valid ? 0xFFFF0000u : 0u);
@@ -175,6 +154,31 @@ struct MfmaMath {
         r.v[0][j] &= ma;
         r.v[1][j] &= mb;
       }
+    }
+    float mx = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])),
+                     fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(s.m, mx);  // finite: lane group 0 always holds a valid token
+    // v_exp_f32 directly: arguments are <= 0 and results below 2^-126 may flush to zero
+    const float alpha = __builtin_amdgcn_exp2f(s.m - m_new);
+    s.m = m_new;
+    float psum = 0.f;
+    uint32_t pw[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(t[e] - m_new);
+      const float p1 = __builtin_amdgcn_exp2f(t[e + 1] - m_new);
+      psum += p0 + p1;
+      // hi columns keep bf16(p); lo columns keep bf16(p - bf16(p)): one fma with lo_mul = 0 / 1
+      const float h0 = round_bf16(p0), h1 = round_bf16(p1);
+      pw[e >> 1] = pack_bf16(fmaf(-lo_mul, h0, p0), fmaf(-lo_mul, h1, p1));
+    }
+    s.l = s.l * alpha + psum;
+    const u32x2 pa = {pw[0], pw[1]}, pb = {pw[2], pw[3]};
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) s.acc[nt] *= alpha;
     }
     // block A into all tiles, then block B: consecutive MFMAs never depend on each other
 #pragma unroll
@@ -191,28 +195,38 @@ struct MfmaMath {
     }
   }
 
-  // Partial record of a run: sum over lane groups, add the hi and lo columns, write to the LDS
-  // record.  A lane owns dims 32j + 8c .. +8 of its column: even ones in tile 2j, odd in 2j+1.
+  // Partial record of a run, written into the wave's LDS record.  The lo columns [G,2G) store
+  // their accumulators first, the hi columns [0,G) then add their own on top (lane (n,c) and
+  // lane (n+G,c) address the same floats), so no register shuffles are needed.  A lane owns
+  // dims 32j + 8c .. +8 of its column: even ones in tile 2j, odd ones in tile 2j+1.
   __device__ void finish(State& s, float* __restrict__ rec) const {
     float l = s.l;
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
-    const bool writer = n < G;
+    const bool hi = n < G, lo = !hi && n < 2 * G;
+    float* mine = rec + (hi ? n : n - G) * D + 8 * c;
+    if (lo) {
 #pragma unroll
-    for (int j = 0; j < KK; ++j) {
-      float o[8];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        o[2 * r] = s.acc[2 * j][r] + __shfl(s.acc[2 * j][r], lane + G);
-        o[2 * r + 1] = s.acc[2 * j + 1][r] + __shfl(s.acc[2 * j + 1][r], lane + G);
-      }
-      if (writer) {
-        float* dst = rec + n * D + 32 * j + 8 * c;
-        *reinterpret_cast<f32x4*>(dst) = f32x4{o[0], o[1], o[2], o[3]};
-        *reinterpret_cast<f32x4*>(dst + 4) = f32x4{o[4], o[5], o[6], o[7]};
+      for (int j = 0; j < KK; ++j) {
+        const f32x4 e = s.acc[2 * j], o = s.acc[2 * j + 1];
+        *reinterpret_cast<f32x4*>(mine + 32 * j) = f32x4{e[0], o[0], e[1], o[1]};
+        *reinterpret_cast<f32x4*>(mine + 32 * j + 4) = f32x4{e[2], o[2], e[3], o[3]};
       }
     }
-    if (writer && c == 0) *reinterpret_cast<float2*>(rec + G * D + 2 * n) = make_float2(s.m, l);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (hi) {
+#pragma unroll
+      for (int j = 0; j < KK; ++j) {
+        const f32x4 e = s.acc[2 * j], o = s.acc[2 * j + 1];
+        f32x4* d0 = reinterpret_cast<f32x4*>(mine + 32 * j);
+        f32x4* d1 = reinterpret_cast<f32x4*>(mine + 32 * j + 4);
+        *d0 = *d0 + f32x4{e[0], o[0], e[1], o[1]};
+        *d1 = *d1 + f32x4{e[2], o[2], e[3], o[3]};
+      }
+      if (c == 0) *reinterpret_cast<float2*>(rec + G * D + 2 * n) = make_float2(s.m, l);
+    }
   }
 };
 
@@ -232,10 +246,12 @@ hipError_t launch_one(const Params& p, int waves, const void* q, const void* k_p
 hipError_t launch_decode_mfma(const Params& p, int waves, const void* q, const void* k_pool,
                               const void* v_pool, const int32_t* header, const int4* desc,
                               float2* partial_ml, float* partial_acc, hipStream_t st) {
-  static const int nbuf = getenv("VOX_NBUF") ? atoi(getenv("VOX_NBUF")) : 3;
-#define VOX_GO(DD, NB) launch_one<DD, NB>(p, waves, q, k_pool, v_pool, header, desc, partial_ml, partial_acc, st)
-  if (p.D == 128) return nbuf == 2 ? VOX_GO(128, 2) : VOX_GO(128, 3);
-  return nbuf == 2 ? VOX_GO(64, 2) : nbuf == 3 ? VOX_GO(64, 3) : nbuf == 4 ? VOX_GO(64, 4) : VOX_GO(64, 6);
+  // Ring depth: three 32-token steps (48 KiB of loads in flight per wave) at head_dim 128, two
+  // at head_dim 64 where deeper rings measured no faster.
+  return p.D == 128 ? launch_one<128, 3>(p, waves, q, k_pool, v_pool, header, desc, partial_ml,
+                                         partial_acc, st)
+                    : launch_one<64, 2>(p, waves, q, k_pool, v_pool, header, desc, partial_ml,
+                                        partial_acc, st);
 }
 
 }  // namespace vox
