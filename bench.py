@@ -156,7 +156,7 @@ def main() -> int:
         "frac": round(achieved / HBM_PEAK_GBPS, 4),
         "kernel_ms": round(kern_ms, 4),
         "bytes_per_launch": kv_bytes_layer,
-        "traffic": MEASURED_TRAFFIC.get(args.workload),
+        "traffic": MEASURED_TRAFFIC.get(args.workload) if path != binding.PATH_VALU else None,
     }
 
     # ---- CPU baseline: the oracle as it stands on a bounded sample of streams
