@@ -27,7 +27,7 @@ METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 # HBM bytes per attention-kernel launch from rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
 # scaled by what the same counter reads for a plain 1 GiB device copy); the runs are summarised
 # in profiles/decode_kernel_<workload>.txt.  Workloads without a counter run report null.
-MEASURED_TRAFFIC = {"cfg3": 2351725784}
+MEASURED_TRAFFIC = {"cfg3": 2353503963, "cfg4": 2726703340, "cfg5": 1100728728}
 
 
 def cpu_model() -> str:
