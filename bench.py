@@ -57,6 +57,8 @@ def main() -> int:
                     help="do not hand the host copy of context_lens to the library")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known traffic for scaling HBM counters)")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="capture one step per pool set into a HIP graph and time the replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -105,8 +107,26 @@ def main() -> int:
     step_args = [binding.StepArgs(w.q, w.k_new, w.v_new, w.k_pool, w.v_pool, o)
                  for w, o in zip(sets, outs)]
 
-    def step(i):
+    def eager_step(i):
         binding.decode_step(sh, step_args[i % copies], bt, lens, ws, context_lens_host=host_lens)
+
+    step = eager_step
+    if args.hip_graph:  # one captured step per pool set, replayed on the current stream
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graphs = []
+        for c in range(copies):
+            with torch.cuda.stream(side):
+                eager_step(c)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                eager_step(c)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+        def step(i):
+            graphs[i % copies].replay()
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -225,6 +245,7 @@ def main() -> int:
             "path": args.path,
             "split_waves": args.split_waves,
             "host_lens": bool(args.host_lens),
+            "hip_graph": bool(args.hip_graph),
         },
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "stream_steps_per_s": round(base.num_streams / (ms_per_step * 1e-3), 1),

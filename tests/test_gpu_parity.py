@@ -310,3 +310,107 @@ def test_multi_layer_step_matches_oracle_on_sampled_streams(dev):
                                          w.context_lens, w.scale, num_kv_heads=w.num_kv_heads,
                                          streams=(s, s + 1))
             _assert_close(got[s:s + 1], ref, f"cfg5 layer{l} stream{s}")
+
+
+def test_decode_step_replays_from_a_hip_graph(dev):
+    # The step only enqueues kernels with length-independent attention grids, so it can be
+    # captured once and replayed with new queries / new tokens in the same buffers.  Each replay
+    # is checked bit for bit against an eager run on the same inputs, with eager work and
+    # synchronisations between the replays.
+    w = synth.make_workload(1, device=dev, layers=1)
+    w2 = synth.make_custom([33, 0, 700, 64, 1, 255], 24, 8, 128, seed=61, device=dev)
+    for wl in (w, w2):
+        sh = binding.shape_of(wl)
+        bt, lens = _i32(wl.block_tables, dev), _i32(wl.context_lens, dev)
+        out = torch.zeros((wl.num_streams, wl.num_q_heads, wl.head_dim), device=dev)
+        ws = binding.alloc_workspace(sh, dev)
+        args = binding.StepArgs(wl.q, wl.k_new, wl.v_new, wl.k_pool, wl.v_pool, [out])
+        k0, v0 = wl.k_pool[0].clone(), wl.v_pool[0].clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):  # warm-up on the capture stream
+            binding.decode_step(sh, args, bt, lens, ws, context_lens_host=wl.context_lens)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            binding.decode_step(sh, args, bt, lens, ws, context_lens_host=wl.context_lens)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(99)
+        for rep in range(3):
+            for t in (wl.q[0], wl.k_new[0], wl.v_new[0]):
+                t.copy_(torch.randn(t.shape, generator=gen, device=dev).to(torch.bfloat16))
+            wl.k_pool[0].copy_(k0)
+            wl.v_pool[0].copy_(v0)
+            out.fill_(float("nan"))
+            binding.decode_step(sh, args, bt, lens, ws, context_lens_host=wl.context_lens)
+            torch.cuda.synchronize()
+            eager = (out.clone(), wl.k_pool[0].clone(), wl.v_pool[0].clone())
+            wl.k_pool[0].copy_(k0)
+            wl.v_pool[0].copy_(v0)
+            out.fill_(float("nan"))
+            ws.fill_(0xFF)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager[0]), f"replay {rep}: output differs from eager"
+            assert torch.equal(wl.k_pool[0].view(torch.int16), eager[1].view(torch.int16))
+            assert torch.equal(wl.v_pool[0].view(torch.int16), eager[2].view(torch.int16))
+        ref, _ = _oracle_decode(wl)
+        _assert_close(out.cpu().numpy(), ref, "graph replay vs oracle")
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("hq,hkv,d,lens", [
+    (8, 1, 128, [20000, 5, 0, 4097]),             # G = 8 at head_dim 128, one very long stream
+    (8, 1, 64, [8192, 31, 1]),                    # G = 8 at head_dim 64
+    (4, 4, 64, [100, 2000, 17, 0, 640]),          # G = 1 (multi-head attention)
+    (12, 2, 128, [3, 3, 3, 3, 3, 3, 3, 3, 3, 3]),  # G = 6, only one-step segments
+])
+def test_extreme_groupings_and_lengths(dev, hq, hkv, d, lens, path):
+    w = synth.make_custom(lens, hq, hkv, d, seed=71, device=dev)
+    out, lse = _decode(w, dev, path=path)
+    ref, ref_lse = _oracle_decode(w)
+    _assert_close(out, ref, f"{hq}q{hkv}kv{d} path{path}")
+    _assert_lse(lse, ref_lse, f"{hq}q{hkv}kv{d} path{path}")
+
+
+def test_many_streams_up_to_the_limit(dev):
+    # 8192 slots (the library's maximum), most of them short or padded: the plan kernel scans 32
+    # streams per thread and almost every wave range crosses dozens of segments
+    rng = np.random.default_rng(72)
+    lens = rng.integers(0, 40, size=8192)
+    lens[rng.integers(0, 8192, size=16)] = rng.integers(500, 3000, size=16)
+    w = synth.make_custom(lens, 14, 2, 64, seed=72, device=dev)
+    out, lse = _decode(w, dev)
+    ref, ref_lse = _oracle_decode(w)
+    _assert_close(out, ref, "8192 streams")
+    _assert_lse(lse, ref_lse, "8192 streams")
+    assert (out[lens == 0] == 0).all()
+    sh = binding.make_shape(8193, 14, 2, 64, w.num_blocks, w.max_blocks_per_stream, w.scale)
+    with pytest.raises(binding.VoxError):
+        binding.paged_decode_workspace_bytes(sh)
+
+
+def test_workspace_reuse_across_calls_with_different_lengths(dev):
+    # the same workspace serves calls whose step counts differ; nothing of the earlier plan or
+    # of its partial records may leak into the later result
+    big = synth.make_custom([900, 1200, 64, 2048], 24, 8, 128, seed=73, device=dev)
+    small = synth.make_custom([5, 0, 33, 17], 24, 8, 128, seed=74, device=dev,
+                              max_blocks_per_stream=big.max_blocks_per_stream)
+    assert small.num_blocks <= big.num_blocks
+    sh_big = binding.shape_of(big)
+    ws = binding.alloc_workspace(sh_big, dev)
+    results = []
+    for wl in (big, small, big):
+        sh = binding.make_shape(wl.num_streams, wl.num_q_heads, wl.num_kv_heads, wl.head_dim,
+                                wl.num_blocks, wl.max_blocks_per_stream, wl.scale)
+        out = torch.full((wl.num_streams, wl.num_q_heads, wl.head_dim), float("nan"), device=dev)
+        binding.paged_decode(sh, wl.q[0], wl.k_pool[0], wl.v_pool[0],
+                             _i32(wl.block_tables, dev), _i32(wl.context_lens, dev), out, ws,
+                             context_lens_host=wl.context_lens)
+        torch.cuda.synchronize()
+        ref, _ = _oracle_decode(wl)
+        _assert_close(out.cpu().numpy(), ref, wl.name)
+        results.append(out.cpu().numpy())
+    assert np.array_equal(results[0], results[2])
