@@ -1,0 +1,70 @@
+/* Small driver that runs every oracle entry point on a seeded problem; built with
+ * -fsanitize=address,undefined by tests/test_oracle_sanitized.py to catch out-of-bounds
+ * indexing and undefined behaviour in the oracle's C. */
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+int vox_oracle_kv_append(int, int, int, int, int, int, const uint16_t*, const uint16_t*, uint16_t*,
+                         uint16_t*, const int32_t*, const int32_t*);
+int vox_oracle_kv_gather(int, int, int, int, int, int, const uint16_t*, const uint16_t*,
+                         const int32_t*, const int32_t*, const int64_t*, uint16_t*, uint16_t*);
+int vox_oracle_paged_decode(int, int, int, int, int, int, int, float, const uint16_t*,
+                            const uint16_t*, const uint16_t*, const int32_t*, const int32_t*, int,
+                            int, double*, double*);
+
+static uint32_t state = 12345u;
+static uint16_t rnd_bf16(void) { /* values in about [-2, 2) with a few mantissa bits */
+  state = state * 1664525u + 1013904223u;
+  int v = (int)((state >> 20) & 255) - 128;
+  float f = (float)v / 64.0f;
+  uint32_t u;
+  __builtin_memcpy(&u, &f, 4);
+  return (uint16_t)(u >> 16);
+}
+
+int main(void) {
+  enum { S = 5, Hq = 6, Hkv = 2, D = 64, B = 16, P = 23, MAXNB = 6 };
+  const int32_t lens[S] = {1, 16, 17, 0, 96};
+  int32_t bt[S * MAXNB];
+  int next = P - 1; /* deal blocks from the top so the highest block ids are used */
+  for (int s = 0; s < S; ++s)
+    for (int j = 0; j < MAXNB; ++j) bt[s * MAXNB + j] = (j < (lens[s] + B - 1) / B) ? next-- : -1;
+  const size_t pool_n = (size_t)P * Hkv * B * D;
+  uint16_t* kp = malloc(pool_n * 2);
+  uint16_t* vp = malloc(pool_n * 2);
+  uint16_t* q = malloc((size_t)S * Hq * D * 2);
+  uint16_t* kn = malloc((size_t)S * Hkv * D * 2);
+  uint16_t* vn = malloc((size_t)S * Hkv * D * 2);
+  for (size_t i = 0; i < pool_n; ++i) { kp[i] = rnd_bf16(); vp[i] = rnd_bf16(); }
+  for (size_t i = 0; i < (size_t)S * Hq * D; ++i) q[i] = rnd_bf16();
+  for (size_t i = 0; i < (size_t)S * Hkv * D; ++i) { kn[i] = rnd_bf16(); vn[i] = rnd_bf16(); }
+  if (vox_oracle_kv_append(S, Hkv, D, B, P, MAXNB, kn, vn, kp, vp, bt, lens)) return 1;
+  int64_t offs[S], total = 0;
+  for (int s = 0; s < S; ++s) { offs[s] = total; total += lens[s]; }
+  uint16_t* ko = malloc((size_t)total * Hkv * D * 2);
+  uint16_t* vo = malloc((size_t)total * Hkv * D * 2);
+  if (vox_oracle_kv_gather(S, Hkv, D, B, P, MAXNB, kp, vp, bt, lens, offs, ko, vo)) return 2;
+  /* the gathered last row of every active stream is the appended row */
+  for (int s = 0; s < S; ++s)
+    if (lens[s] > 0)
+      for (int i = 0; i < Hkv * D; ++i)
+        if (ko[(offs[s] + lens[s] - 1) * Hkv * D + i] != kn[(size_t)s * Hkv * D + i]) return 3;
+  double* out = malloc((size_t)S * Hq * D * sizeof(double));
+  double* lse = malloc((size_t)S * Hq * sizeof(double));
+  if (vox_oracle_paged_decode(S, Hq, Hkv, D, B, P, MAXNB, 0.125f, q, kp, vp, bt, lens, 0, S, out,
+                              lse))
+    return 4;
+  for (int i = 0; i < S * Hq * D; ++i)
+    if (!isfinite(out[i]) || fabs(out[i]) > 2.0) return 5; /* convex combination of |v| <= 2 */
+  for (int i = 0; i < Hq; ++i)
+    if (!(isinf(lse[3 * Hq + i]) && lse[3 * Hq + i] < 0)) return 6; /* stream 3 is inactive */
+  /* subset call writes only its own rows */
+  if (vox_oracle_paged_decode(S, Hq, Hkv, D, B, P, MAXNB, 0.125f, q, kp, vp, bt, lens, 4, 1, out,
+                              NULL))
+    return 7;
+  free(kp); free(vp); free(q); free(kn); free(vn); free(ko); free(vo); free(out); free(lse);
+  puts("oracle sanitizer driver ok");
+  return 0;
+}

@@ -1,0 +1,26 @@
+"""The oracle's C under AddressSanitizer and UBSan (host only)."""
+
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_oracle_runs_clean_under_asan_and_ubsan(tmp_path):
+    exe = tmp_path / "oracle_san"
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-static-libasan", "-fopenmp",
+           os.path.join(ROOT, "oracle", "vox_oracle.c"),
+           os.path.join(ROOT, "tests", "oracle_sanitizer_driver.c"), "-o", str(exe), "-lm"]
+    build = subprocess.run(cmd, capture_output=True, text=True)
+    if build.returncode != 0 and "asan" in build.stderr.lower():
+        pytest.skip("sanitizer runtime not available to gcc here: " + build.stderr[-200:])
+    assert build.returncode == 0, build.stderr
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:verify_asan_link_order=0",
+               OMP_NUM_THREADS="2")
+    run = subprocess.run([str(exe)], capture_output=True, text=True, env=env, timeout=120)
+    assert run.returncode == 0, f"rc={run.returncode}\n{run.stdout}\n{run.stderr[-2000:]}"
+    assert "ok" in run.stdout
