@@ -38,6 +38,7 @@ Params make_params(const vox_shape_t* s) {
   p.P = s->num_blocks;
   p.max_nb = s->max_blocks_per_stream;
   p.scale_log2 = s->scale * 1.44269504088896340736f;
+  p.n_steps = p.per_wave = -1;
   return p;
 }
 
@@ -76,6 +77,7 @@ struct Plan {
   int waves;
   int64_t desc_capacity;  // descriptors the workspace has room for
   int64_t max_steps;      // steps the plan kernel must be able to expand
+  bool exact;             // max_steps is the exact step count (host lengths were given)
   Workspace ws;
 };
 
@@ -98,8 +100,18 @@ int make_plan(const vox_shape_t* s, const int32_t* lens_host, size_t workspace_b
   out->waves = split_waves(s);
   out->desc_capacity = cap < INT32_MAX ? cap : INT32_MAX;
   out->max_steps = need;
+  out->exact = lens_host != nullptr;
   out->ws = map_workspace(s, 0);
   return VOX_OK;
+}
+
+// With exact host-side knowledge of the step count, N and Q travel as kernel arguments (the
+// plan kernel derives the same two numbers from the device lengths).
+void set_step_hints(Params* p, const Plan& plan) {
+  if (!plan.exact) return;
+  p->n_steps = (int32_t)plan.max_steps;
+  const int64_t q = (plan.max_steps + plan.waves - 1) / plan.waves;
+  p->per_wave = (int32_t)(q > 1 ? q : 1);
 }
 
 int enqueue_plan(const Params& p, const Plan& plan, char* ws, const int32_t* bt,
@@ -203,7 +215,8 @@ int vox_paged_decode_profiled(const vox_shape_t* shape, const void* q, const voi
   if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
   Plan plan;
   if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
-  const Params p = make_params(shape);
+  Params p = make_params(shape);
+  set_step_hints(&p, plan);
   hipStream_t st = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
   if (int rc = enqueue_plan(p, plan, ws, block_tables, context_lens, st)) return rc;
@@ -232,7 +245,8 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
   if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
   Plan plan;
   if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
-  const Params p = make_params(shape);
+  Params p = make_params(shape);
+  set_step_hints(&p, plan);
   hipStream_t st = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
   const WsPtrs w = ws_ptrs(plan, ws);

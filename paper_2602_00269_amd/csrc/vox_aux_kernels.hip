@@ -231,8 +231,8 @@ __device__ inline void merge_role(const Params& p, int group, const int32_t* __r
   const int s = w / p.Hq, i = w % p.Hq;
   const int h = i / p.G, g = i % p.G;
   const int sigma = s * p.Hkv + h;
-  const int Q = header[kHdrPerWave];
-  const int64_t N = header[kHdrSteps];
+  const int Q = p.n_steps >= 0 ? p.per_wave : header[kHdrPerWave];
+  const int64_t N = p.n_steps >= 0 ? p.n_steps : header[kHdrSteps];
   const int nseg = step_prefix[s + 1] - step_prefix[s];
   const int64_t first = (int64_t)step_prefix[s] * p.Hkv + (int64_t)h * nseg;
   int n = 0;         // number of runs

@@ -58,6 +58,9 @@ struct Workspace {
 struct Params {
   int32_t S, Hq, Hkv, G, D, P, max_nb;
   float scale_log2;  // scale * log2(e): scores are kept in log2 units
+  // N and Q when the host knows the lengths (else -1 and the kernels read the plan's header):
+  // saves every wave one dependent round trip to memory before its first descriptor load
+  int32_t n_steps, per_wave;
 };
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

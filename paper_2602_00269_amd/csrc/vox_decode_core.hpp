@@ -89,7 +89,8 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
   constexpr int LA = NBUF + 1;  // descriptor look-ahead in steps
   const int lane = threadIdx.x & (kWave - 1);
   const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6));
-  const int N = header[kHdrSteps], Q = header[kHdrPerWave];
+  const int N = p.n_steps >= 0 ? p.n_steps : header[kHdrSteps];
+  const int Q = p.n_steps >= 0 ? p.per_wave : header[kHdrPerWave];
   const int64_t x0 = (int64_t)w * Q;
   if (x0 >= N) return;
   const int nsteps = (int)min((int64_t)Q, (int64_t)N - x0);
