@@ -24,6 +24,10 @@ def _load():
         lib.vox_oracle_kv_gather.restype = i
         lib.vox_oracle_paged_decode.argtypes = [i] * 7 + [f] + [p] * 5 + [i, i, p, p]
         lib.vox_oracle_paged_decode.restype = i
+        lib.vox_oracle_kv_append_multi.argtypes = [i] * 6 + [p] * 7
+        lib.vox_oracle_kv_append_multi.restype = i
+        lib.vox_oracle_paged_prefill.argtypes = [i] * 7 + [f] + [p] * 8
+        lib.vox_oracle_paged_prefill.restype = i
         lib.vox_oracle_num_threads.restype = i
         _lib = lib
     return _lib
@@ -97,4 +101,37 @@ def paged_decode(q, k_pool, v_pool, block_tables, context_lens, scale, *, num_kv
                                          _ptr(v_pool), _ptr(bt), _ptr(lens), s0, s1 - s0,
                                          _ptr(out), _ptr(lse))
     _check(rc, "paged_decode")
+    return out, lse
+
+
+def kv_append_multi(k_new, v_new, k_pool, v_pool, block_tables, context_lens, q_offsets, *,
+                    head_dim, block_size=16):
+    """In-place append of packed rows [Tq, Hkv, D]; stream s owns rows q_offsets[s]:q_offsets[s+1]."""
+    k_new, v_new = _u16(k_new), _u16(v_new)
+    bt, lens, qo = _i32(block_tables), _i32(context_lens), _i32(q_offsets)
+    for pool in (k_pool, v_pool):
+        if pool.dtype != np.uint16 or not pool.flags.c_contiguous or not pool.flags.writeable:
+            raise TypeError("pools must be writable C-contiguous uint16 arrays")
+    rc = _load().vox_oracle_kv_append_multi(lens.size, k_new.shape[1], head_dim, block_size,
+                                            k_pool.shape[0], bt.shape[1], _ptr(k_new),
+                                            _ptr(v_new), _ptr(k_pool), _ptr(v_pool), _ptr(bt),
+                                            _ptr(lens), _ptr(qo))
+    _check(rc, "kv_append_multi")
+
+
+def paged_prefill(q, k_pool, v_pool, block_tables, context_lens, q_offsets, scale, *,
+                  num_kv_heads, block_size=16):
+    """Causal multi-token attention: fp64 (out [Tq, Hq, D], lse [Tq, Hq])."""
+    q, k_pool, v_pool = _u16(q), _u16(k_pool), _u16(v_pool)
+    bt, lens, qo = _i32(block_tables), _i32(context_lens), _i32(q_offsets)
+    tq, hq, d = q.shape
+    if int(qo[-1]) != tq:
+        raise ValueError("q_offsets[-1] must equal the number of query rows")
+    out = np.zeros((tq, hq, d), dtype=np.float64)
+    lse = np.zeros((tq, hq), dtype=np.float64)
+    rc = _load().vox_oracle_paged_prefill(lens.size, hq, num_kv_heads, d, block_size,
+                                          k_pool.shape[0], bt.shape[1], np.float32(scale),
+                                          _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(bt),
+                                          _ptr(lens), _ptr(qo), _ptr(out), _ptr(lse))
+    _check(rc, "paged_prefill")
     return out, lse

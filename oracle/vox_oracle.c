@@ -112,6 +112,49 @@ int vox_oracle_kv_gather(int S, int Hkv, int D, int B, int P, int max_nb, const 
 }
 
 /*
+ * Attention of one query row over tokens [0, ctx) of stream s, kv head h: the definition above,
+ * nothing else.  o receives D doubles; returns ORACLE_OK, ORACLE_ERR_BLOCK or ORACLE_ERR_MEM.
+ */
+static int attend(int Hkv, int D, int B, int P, int max_nb, float scale, const uint16_t* qrow,
+                  const uint16_t* k_pool, const uint16_t* v_pool, const int32_t* bt, int s, int h,
+                  int ctx, double* o, double* lse_out) {
+  for (int d = 0; d < D; ++d) o[d] = 0.0;
+  if (ctx <= 0) {
+    if (lse_out) *lse_out = -INFINITY;
+    return ORACLE_OK;
+  }
+  double* z = (double*)malloc((size_t)ctx * sizeof(double));
+  if (!z) return ORACLE_ERR_MEM;
+  double zmax = -INFINITY;
+  for (int t = 0; t < ctx; ++t) {
+    int64_t blk = block_of(bt, max_nb, P, B, s, t);
+    if (blk < 0) {
+      free(z);
+      return ORACLE_ERR_BLOCK;
+    }
+    double dot = 0.0;
+    for (int d = 0; d < D; ++d)
+      dot += bf16_to_f64(qrow[d]) * bf16_to_f64(k_pool[k_index(Hkv, D, B, blk, h, t % B, d)]);
+    z[t] = (double)scale * dot;
+    if (z[t] > zmax) zmax = z[t];
+  }
+  double denom = 0.0;
+  for (int t = 0; t < ctx; ++t) {
+    z[t] = exp(z[t] - zmax);
+    denom += z[t];
+  }
+  for (int t = 0; t < ctx; ++t) {
+    int64_t blk = block_of(bt, max_nb, P, B, s, t);
+    double p = z[t] / denom;
+    for (int d = 0; d < D; ++d)
+      o[d] += p * bf16_to_f64(v_pool[v_index(Hkv, D, B, blk, h, t % B, d)]);
+  }
+  if (lse_out) *lse_out = zmax + log(denom);
+  free(z);
+  return ORACLE_OK;
+}
+
+/*
  * Decode for streams [s0, s0+ns): out is fp64 [ns][Hq][D], lse fp64 [ns][Hq] (may be NULL).
  * Inactive streams (L == 0) give out = 0, lse = -inf.
  */
@@ -125,55 +168,77 @@ int vox_oracle_paged_decode(int S, int Hq, int Hkv, int D, int B, int P, int max
   int status = ORACLE_OK;
 #pragma omp parallel for schedule(dynamic, 1)
   for (int item = 0; item < ns * Hq; ++item) {
-    const int s = s0 + item / Hq, i = item % Hq, h = i / G;
-    const int L = lens[s];
-    double* o = out + (size_t)item * D;
-    for (int d = 0; d < D; ++d) o[d] = 0.0;
-    if (L <= 0) {
-      if (lse) lse[item] = -INFINITY;
-      continue;
-    }
-    double* z = (double*)malloc((size_t)L * sizeof(double));
-    if (!z) {
+    const int s = s0 + item / Hq, i = item % Hq;
+    const int rc = attend(Hkv, D, B, P, max_nb, scale, q + ((size_t)s * Hq + i) * D, k_pool,
+                          v_pool, bt, s, i / G, lens[s], out + (size_t)item * D,
+                          lse ? lse + item : NULL);
+    if (rc != ORACLE_OK) {
 #pragma omp atomic write
-      status = ORACLE_ERR_MEM;
-      continue;
+      status = rc;
     }
-    const uint16_t* qrow = q + ((size_t)s * Hq + i) * D;
-    int bad = 0;
-    double zmax = -INFINITY;
-    for (int t = 0; t < L; ++t) {
-      int64_t blk = block_of(bt, max_nb, P, B, s, t);
-      if (blk < 0) {
-        bad = 1;
-        break;
-      }
-      double dot = 0.0;
-      for (int d = 0; d < D; ++d)
-        dot += bf16_to_f64(qrow[d]) * bf16_to_f64(k_pool[k_index(Hkv, D, B, blk, h, t % B, d)]);
-      z[t] = (double)scale * dot;
-      if (z[t] > zmax) zmax = z[t];
-    }
-    if (bad) {
-#pragma omp atomic write
-      status = ORACLE_ERR_BLOCK;
-      free(z);
-      continue;
-    }
-    double denom = 0.0;
-    for (int t = 0; t < L; ++t) {
-      z[t] = exp(z[t] - zmax);
-      denom += z[t];
-    }
-    for (int t = 0; t < L; ++t) {
-      int64_t blk = block_of(bt, max_nb, P, B, s, t);
-      double p = z[t] / denom;
-      for (int d = 0; d < D; ++d)
-        o[d] += p * bf16_to_f64(v_pool[v_index(Hkv, D, B, blk, h, t % B, d)]);
-    }
-    if (lse) lse[item] = zmax + log(denom);
-    free(z);
   }
+  return status;
+}
+
+/*
+ * Multi-token step (prompt prefill, chunked admission, detokenizer chunks): stream s brings
+ * n_s = q_offsets[s+1] - q_offsets[s] new tokens, rows q_offsets[s] .. of the packed arrays,
+ * occupying positions L_s - n_s .. L_s - 1 (L_s counts them).  Query j of the stream attends
+ * causally: to tokens [0, L_s - n_s + j].
+ */
+int vox_oracle_kv_append_multi(int S, int Hkv, int D, int B, int P, int max_nb,
+                               const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
+                               uint16_t* v_pool, const int32_t* bt, const int32_t* lens,
+                               const int32_t* q_offsets) {
+  if (!shape_ok(S, Hkv, Hkv, D, B, P, max_nb)) return ORACLE_ERR_ARG;
+  for (int s = 0; s < S; ++s) {
+    const int n = q_offsets[s + 1] - q_offsets[s];
+    if (n < 0 || n > lens[s]) return ORACLE_ERR_ARG;
+    for (int j = 0; j < n; ++j) {
+      const int pos = lens[s] - n + j;
+      int64_t blk = block_of(bt, max_nb, P, B, s, pos);
+      if (blk < 0) return ORACLE_ERR_BLOCK;
+      for (int h = 0; h < Hkv; ++h)
+        for (int d = 0; d < D; ++d) {
+          size_t src = (((size_t)q_offsets[s] + j) * Hkv + h) * D + d;
+          k_pool[k_index(Hkv, D, B, blk, h, pos % B, d)] = k_new[src];
+          v_pool[v_index(Hkv, D, B, blk, h, pos % B, d)] = v_new[src];
+        }
+    }
+  }
+  return ORACLE_OK;
+}
+
+/* out fp64 [Tq][Hq][D], lse fp64 [Tq][Hq] (may be NULL), Tq = q_offsets[S]. */
+int vox_oracle_paged_prefill(int S, int Hq, int Hkv, int D, int B, int P, int max_nb, float scale,
+                             const uint16_t* q, const uint16_t* k_pool, const uint16_t* v_pool,
+                             const int32_t* bt, const int32_t* lens, const int32_t* q_offsets,
+                             double* out, double* lse) {
+  if (!shape_ok(S, Hq, Hkv, D, B, P, max_nb)) return ORACLE_ERR_ARG;
+  const int G = Hq / Hkv;
+  for (int s = 0; s < S; ++s) {
+    const int n = q_offsets[s + 1] - q_offsets[s];
+    if (n < 0 || n > lens[s]) return ORACLE_ERR_ARG;
+  }
+  const int Tq = q_offsets[S];
+  int* row_stream = (int*)malloc(((size_t)Tq + 1) * sizeof(int));
+  if (!row_stream) return ORACLE_ERR_MEM;
+  for (int s = 0; s < S; ++s)
+    for (int r = q_offsets[s]; r < q_offsets[s + 1]; ++r) row_stream[r] = s;
+  int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int item = 0; item < Tq * Hq; ++item) {
+    const int row = item / Hq, i = item % Hq, s = row_stream[row];
+    const int n = q_offsets[s + 1] - q_offsets[s];
+    const int ctx = lens[s] - n + (row - q_offsets[s]) + 1;
+    const int rc = attend(Hkv, D, B, P, max_nb, scale, q + (size_t)item * D, k_pool, v_pool, bt,
+                          s, i / G, ctx, out + (size_t)item * D, lse ? lse + item : NULL);
+    if (rc != ORACLE_OK) {
+#pragma omp atomic write
+      status = rc;
+    }
+  }
+  free(row_stream);
   return status;
 }
 
