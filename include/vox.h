@@ -168,6 +168,37 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
                     const int32_t* context_lens_host, float* const* out, void* workspace,
                     size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Multi-token step: the prefill operation of the Worker (paper Section 3) and every other case
+ * where a stream brings several new tokens at once: chunked admission of a prompt during the
+ * startup phase (Section 3.2.1), or a detokenizer that keeps attention caches per request and
+ * runs on chunks of tokens (Section 3.1, Postprocess).  Stream s brings
+ * n_s = q_offsets[s+1] - q_offsets[s] tokens, rows q_offsets[s].. of the packed arrays, at
+ * positions L_s - n_s .. L_s - 1 (L_s = context_lens[s] counts them; 0 <= n_s <= L_s).
+ *
+ * vox_kv_append_multi copies k_new / v_new ([total_q][Hkv][D] bf16) into those positions.
+ * vox_paged_prefill computes, for query row r = q_offsets[s] + j and q head i,
+ *     out[r][i][:] = softmax(scale * q[r][i] . K(s, i/G, 0 .. L_s - n_s + j)) V(...)
+ * i.e. causal attention over the paged context (row j sees itself and everything before).
+ *   q                 : [total_q][Hq][D] bf16;  out: [total_q][Hq][D] fp32;  lse: [total_q][Hq] or NULL
+ *   q_offsets         : int32 [S+1] device, q_offsets[0] == 0
+ *   context_lens_host, q_offsets_host : HOST copies, both required (the scheduler that admits
+ *                       a prompt knows its length); sizes of the launches come from them
+ * vox_paged_prefill_workspace_bytes(shape, total_q) is enough for any lengths the shape
+ * admits; a smaller workspace is accepted when the actual step count fits.
+ */
+size_t vox_paged_prefill_workspace_bytes(const vox_shape_t* shape, int32_t total_q);
+int vox_kv_append_multi(const vox_shape_t* shape, const void* k_new, const void* v_new,
+                        void* k_pool, void* v_pool, const int32_t* block_tables,
+                        const int32_t* context_lens, const int32_t* q_offsets, int32_t total_q,
+                        void* hip_stream);
+int vox_paged_prefill(const vox_shape_t* shape, const void* q, const void* k_pool,
+                      const void* v_pool, const int32_t* block_tables,
+                      const int32_t* context_lens, const int32_t* q_offsets,
+                      const int32_t* context_lens_host, const int32_t* q_offsets_host,
+                      float* out, float* lse, void* workspace, size_t workspace_bytes,
+                      void* hip_stream);
+
 /* Static, never-NULL description of a return code. */
 const char* vox_strerror(int code);
 

@@ -68,6 +68,12 @@ def load() -> ctypes.CDLL:
     lib.vox_paged_decode_profiled.restype = ctypes.c_int
     lib.vox_decode_step.argtypes = [sp, i32] + [vp] * 10 + [ctypes.c_size_t, vp]
     lib.vox_decode_step.restype = ctypes.c_int
+    lib.vox_paged_prefill_workspace_bytes.argtypes = [sp, i32]
+    lib.vox_paged_prefill_workspace_bytes.restype = ctypes.c_size_t
+    lib.vox_kv_append_multi.argtypes = [sp] + [vp] * 7 + [i32, vp]
+    lib.vox_kv_append_multi.restype = ctypes.c_int
+    lib.vox_paged_prefill.argtypes = [sp] + [vp] * 11 + [ctypes.c_size_t, vp]
+    lib.vox_paged_prefill.restype = ctypes.c_int
     lib.vox_strerror.argtypes = [ctypes.c_int]
     lib.vox_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -207,3 +213,40 @@ def decode_step(shape, args: StepArgs, block_tables, context_lens, workspace,
                                 _stream(stream))
     del keep
     _check(rc, "vox_decode_step")
+
+
+def paged_prefill_workspace_bytes(shape, total_q: int) -> int:
+    n = load().vox_paged_prefill_workspace_bytes(ctypes.byref(shape), int(total_q))
+    if n == 0:
+        raise VoxError(-2, "vox_paged_prefill_workspace_bytes")
+    return int(n)
+
+
+def kv_append_multi(shape, k_new, v_new, k_pool, v_pool, block_tables, context_lens, q_offsets,
+                    stream=None):
+    bf, i32 = torch.bfloat16, torch.int32
+    rc = load().vox_kv_append_multi(ctypes.byref(shape), _dev(k_new, bf, "k_new"),
+                                    _dev(v_new, bf, "v_new"), _dev(k_pool, bf, "k_pool"),
+                                    _dev(v_pool, bf, "v_pool"),
+                                    _dev(block_tables, i32, "block_tables"),
+                                    _dev(context_lens, i32, "context_lens"),
+                                    _dev(q_offsets, i32, "q_offsets"), int(k_new.shape[0]),
+                                    _stream(stream))
+    _check(rc, "vox_kv_append_multi")
+
+
+def paged_prefill(shape, q, k_pool, v_pool, block_tables, context_lens, q_offsets,
+                  context_lens_host, q_offsets_host, out, workspace, lse=None, stream=None):
+    bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+    keep1, lens_h = _host_lens(context_lens_host)
+    keep2, qo_h = _host_lens(q_offsets_host)
+    rc = load().vox_paged_prefill(ctypes.byref(shape), _dev(q, bf, "q"),
+                                  _dev(k_pool, bf, "k_pool"), _dev(v_pool, bf, "v_pool"),
+                                  _dev(block_tables, i32, "block_tables"),
+                                  _dev(context_lens, i32, "context_lens"),
+                                  _dev(q_offsets, i32, "q_offsets"), lens_h, qo_h,
+                                  _dev(out, f32, "out"), _dev(lse, f32, "lse", optional=True),
+                                  _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                  _stream(stream))
+    del keep1, keep2
+    _check(rc, "vox_paged_prefill")

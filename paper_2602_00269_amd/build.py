@@ -9,7 +9,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvox.so")
-SOURCES = ["vox_api.hip", "vox_aux_kernels.hip", "vox_decode_mfma.hip", "vox_decode_valu.hip"]
+SOURCES = ["vox_api.hip", "vox_aux_kernels.hip", "vox_decode_mfma.hip", "vox_decode_valu.hip",
+           "vox_prefill.hip"]
 
 # Packed fp32 VALU forms are switched off for device code on purpose.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -43,7 +44,7 @@ def _compile(src: str) -> str:
 def build(verbose: bool = True) -> str:
     """Compile every source and link libvox.so; always recompiles."""
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
     r = subprocess.run(cmd, capture_output=True, text=True)

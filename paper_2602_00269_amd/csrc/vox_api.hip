@@ -269,6 +269,72 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
   return VOX_OK;
 }
 
+size_t vox_paged_prefill_workspace_bytes(const vox_shape_t* shape, int32_t total_q) {
+  if (validate(shape) != VOX_OK || total_q < 0) return 0;
+  const Params p = make_params(shape);
+  const int64_t tiles = (int64_t)total_q + shape->num_streams;  // every tile holds >= 1 row
+  const int64_t steps = tiles * ((shape->max_blocks_per_stream + 1) / 2) * shape->num_kv_heads;
+  const int64_t slots = split_waves(shape) + tiles * shape->num_kv_heads;
+  return map_prefill_workspace(p, tiles, total_q, slots, steps).total;
+}
+
+int vox_kv_append_multi(const vox_shape_t* shape, const void* k_new, const void* v_new,
+                        void* k_pool, void* v_pool, const int32_t* block_tables,
+                        const int32_t* context_lens, const int32_t* q_offsets, int32_t total_q,
+                        void* hip_stream) {
+  if (int rc = validate(shape)) return rc;
+  if (total_q < 0) return VOX_ERR_ARG;
+  if (!k_new || !v_new || !k_pool || !v_pool || !block_tables || !context_lens || !q_offsets)
+    return VOX_ERR_NULL;
+  const Params p = make_params(shape);
+  return launch_kv_append_multi(p, total_q, k_new, v_new, k_pool, v_pool, block_tables,
+                                context_lens, q_offsets, (hipStream_t)hip_stream) == hipSuccess
+             ? VOX_OK
+             : VOX_ERR_HIP;
+}
+
+int vox_paged_prefill(const vox_shape_t* shape, const void* q, const void* k_pool,
+                      const void* v_pool, const int32_t* block_tables,
+                      const int32_t* context_lens, const int32_t* q_offsets,
+                      const int32_t* context_lens_host, const int32_t* q_offsets_host,
+                      float* out, float* lse, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+  if (int rc = validate(shape)) return rc;
+  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !q_offsets ||
+      !context_lens_host || !q_offsets_host || !out || !workspace)
+    return VOX_ERR_NULL;
+  if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
+  const Params p = make_params(shape);
+  const int tq = 16 / p.G;
+  // exact tile and step counts from the host copies (the scheduler that admits a prompt
+  // knows its length)
+  if (q_offsets_host[0] != 0) return VOX_ERR_ARG;
+  int64_t tiles = 0, steps = 0;
+  for (int s = 0; s < p.S; ++s) {
+    const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
+    const int64_t L = context_lens_host[s];
+    if (n < 0 || n > L || L > (int64_t)shape->max_blocks_per_stream * kBlock) return VOX_ERR_ARG;
+    const int64_t nt = (n + tq - 1) / tq;
+    for (int64_t tau = 0; tau < nt; ++tau) {
+      const int64_t ctx = L - n + (n < (tau + 1) * tq ? n : (tau + 1) * tq);
+      steps += (ctx + kStepTokens - 1) / kStepTokens;
+    }
+    tiles += nt;
+  }
+  steps *= p.Hkv;
+  const int64_t total_q = q_offsets_host[p.S];
+  if (steps > INT32_MAX || tiles * p.Hkv > INT32_MAX / 2) return VOX_ERR_SHAPE;
+  const int waves = split_waves(shape);
+  const int64_t slots = waves + tiles * p.Hkv;
+  const PrefillWorkspace m = map_prefill_workspace(p, tiles, total_q, slots, steps);
+  if (m.total > workspace_bytes) return VOX_ERR_WORKSPACE;
+  return launch_prefill(p, m, (char*)workspace, tq, tiles, steps, steps, waves, (int)total_q, q,
+                        k_pool, v_pool, block_tables, context_lens, q_offsets, out, lse,
+                        (hipStream_t)hip_stream) == hipSuccess
+             ? VOX_OK
+             : VOX_ERR_HIP;
+}
+
 const char* vox_strerror(int code) {
   switch (code) {
     case VOX_OK: return "ok";

@@ -1,5 +1,5 @@
 // KV append, block gather, split-K planning and the partial-softmax merge.
-#include "vox_common.hpp"
+#include "vox_merge.hpp"
 
 namespace vox {
 namespace {
@@ -208,23 +208,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
 // w0 = P/Q .. w1 = (P+n-1)/Q (P = first global step of the segment); run j is slot w0+j+sigma.
 // Lanes hold the runs' (max, sum) records; the global max and the rescaled sum are wave
 // reductions; the accumulators are then combined with each lane owning D/64 output dims.
-__device__ inline float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-  return v;
-}
-__device__ inline float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
-
 template <int D>
 __device__ inline void merge_role(const Params& p, int group, const int32_t* __restrict__ header,
                                   const int32_t* __restrict__ step_prefix,
                                   const float2* __restrict__ pml, const float* __restrict__ pacc,
                                   float* __restrict__ out, float* __restrict__ lse) {
-  constexpr int DPL = D / kWave;  // dims per lane
   const int lane = threadIdx.x & (kWave - 1);
   const int w = group * kWavesPerGroup + (threadIdx.x >> 6);
   if (w >= p.S * p.Hq) return;
@@ -235,7 +223,7 @@ __device__ inline void merge_role(const Params& p, int group, const int32_t* __r
   const int64_t N = p.n_steps >= 0 ? p.n_steps : header[kHdrSteps];
   const int nseg = step_prefix[s + 1] - step_prefix[s];
   const int64_t first = (int64_t)step_prefix[s] * p.Hkv + (int64_t)h * nseg;
-  int n = 0;         // number of runs
+  int n = 0;          // number of runs
   int64_t slot0 = 0;  // slot of run 0
   if (nseg > 0 && first < N) {
     const int64_t last = min(N, first + nseg) - 1;
@@ -243,41 +231,8 @@ __device__ inline void merge_role(const Params& p, int group, const int32_t* __r
     n = (int)(w1 - w0 + 1);
     slot0 = w0 + sigma;
   }
-  float m_run = -INFINITY, l_run = 0.f;
-  float acc[DPL];
-#pragma unroll
-  for (int k = 0; k < DPL; ++k) acc[k] = 0.f;
-  for (int c0 = 0; c0 < n; c0 += kWave) {
-    const int c = c0 + lane;
-    float2 ml = make_float2(-INFINITY, 0.f);
-    if (c < n) ml = pml[(size_t)(slot0 + c) * p.G + g];
-    const float m_new = fmaxf(m_run, wave_max(ml.x));
-    const float wgt = (ml.x == -INFINITY) ? 0.f : exp2f(ml.x - m_new);
-    const float alpha = (m_run == -INFINITY) ? 0.f : exp2f(m_run - m_new);
-    l_run = l_run * alpha + wave_sum(wgt * ml.y);
-#pragma unroll
-    for (int k = 0; k < DPL; ++k) acc[k] *= alpha;
-    const int cnt = min(kWave, n - c0);
-    for (int j = 0; j < cnt; ++j) {
-      const float wj = __shfl(wgt, j);
-      const float* src = pacc + ((size_t)(slot0 + c0 + j) * p.G + g) * D + lane * DPL;
-      if (DPL == 2) {
-        const float2 a = *reinterpret_cast<const float2*>(src);
-        acc[0] += wj * a.x;
-        acc[DPL - 1] += wj * a.y;
-      } else {
-        acc[0] += wj * src[0];
-      }
-    }
-    m_run = m_new;
-  }
-  float* dst = out + ((size_t)s * p.Hq + i) * D + lane * DPL;
-  const float inv = (n > 0 && l_run > 0.f) ? 1.f / l_run : 0.f;
-#pragma unroll
-  for (int k = 0; k < DPL; ++k) dst[k] = acc[k] * inv;
-  if (lse && lane == 0)
-    lse[(size_t)s * p.Hq + i] =
-        (n > 0 && l_run > 0.f) ? (m_run + log2f(l_run)) * 0.69314718055994530942f : -INFINITY;
+  merge_runs<D>(pml, pacc, slot0, n, p.G, g, lane, out + ((size_t)s * p.Hq + i) * D,
+                lse ? lse + (size_t)s * p.Hq + i : nullptr);
 }
 
 template <int D>

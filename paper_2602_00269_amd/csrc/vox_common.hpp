@@ -54,6 +54,12 @@ struct Workspace {
   size_t total;
 };
 
+// Workspace map of the multi-token (prefill / chunk) step.
+struct PrefillWorkspace {
+  size_t header, pt, ps, tile_first, tile_steps, tile_info, row_tile, partial_ml, partial_acc,
+      desc, total;
+};
+
 // Everything a kernel needs besides its buffers.
 struct Params {
   int32_t S, Hq, Hkv, G, D, P, max_nb;
@@ -92,6 +98,18 @@ hipError_t launch_merge_append(const Params& p, const int32_t* header, const int
                                const float2* partial_ml, const float* partial_acc, float* out,
                                const int32_t* bt, const int32_t* lens, const void* k_new,
                                const void* v_new, void* k_pool, void* v_pool, hipStream_t st);
+PrefillWorkspace map_prefill_workspace(const Params& p, int64_t tiles, int64_t total_q,
+                                       int64_t slots, int64_t desc_capacity);
+size_t prefill_desc_bytes();
+hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_new,
+                                  const void* v_new, void* k_pool, void* v_pool,
+                                  const int32_t* bt, const int32_t* lens, const int32_t* qo,
+                                  hipStream_t st);
+hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, int tq,
+                          int64_t tiles, int64_t steps, int64_t desc_capacity, int waves,
+                          int total_q, const void* q, const void* k_pool, const void* v_pool,
+                          const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
+                          float* lse, hipStream_t st);
 hipError_t launch_decode_mfma(const Params& p, int waves, const void* q, const void* k_pool,
                               const void* v_pool, const int32_t* header, const int4* desc,
                               float2* partial_ml, float* partial_acc, hipStream_t st);

@@ -9,8 +9,9 @@
 //
 // `Math` supplies the registers and arithmetic of one step:
 //   struct Q (query rows in flight), struct Regs (one step of K/V), struct State;
-//   Math(lane, params); load_q(Q&, q, sigma); install_q(State&, Q&);
-//   issue(Regs&, k_pool, v_pool, ga, gb); reset(State&); compute(State&, Regs&, ntok);
+//   struct Desc (step descriptor) with static accessors ga/gb/meta/sigma; columns(params);
+//   Math(lane, params); load_q(Q&, q, desc); install_q(State&, Q&);
+//   issue(Regs&, k_pool, v_pool, ga, gb); reset(State&); compute(State&, Regs&, desc);
 //   finish(State&, float* record): writes the run's [G][D] accumulators and [G] (max, sum)
 //   pairs into the LDS record.
 #pragma once
@@ -34,24 +35,25 @@ __device__ inline u32x4 kv_load(const uint16_t* p) {
 // acknowledgement is slow while the chip streams at full rate: every later load would wait
 // behind it.  Records are therefore kept in LDS ([G][D] accumulators then [G] (max, sum)
 // pairs, the same shape as a global record) and copied out when the wave has finished its
-// range, or earlier if the buffer fills up.
+// range, or earlier if the buffer fills up.  `cols` is the number of (query row, head) columns
+// a record holds: G for the decode step, 16 for the multi-token step.
 constexpr int kStashFloats = 4096;  // 16 KB per wave, 64 KB per workgroup
 
 struct PartialStash {
   float* mem;    // this wave's LDS area
-  int rec;       // floats per record: G * (D + 2)
-  int gd;        // G * D
+  int rec;       // floats per record: cols * (D + 2)
+  int gd;        // cols * D
   int cap;       // records that fit
   int count;     // records held
   int slots;     // lane r holds the slot id of record r
   int lane;
 
-  __device__ PartialStash(float* mem_, int G, int D, int lane_)
-      : mem(mem_), rec(G * (D + 2)), gd(G * D), cap(kStashFloats / (G * (D + 2))), count(0),
-        slots(0), lane(lane_) {}
+  __device__ PartialStash(float* mem_, int cols, int D, int lane_)
+      : mem(mem_), rec(cols * (D + 2)), gd(cols * D), cap(kStashFloats / (cols * (D + 2))),
+        count(0), slots(0), lane(lane_) {}
 
-  // LDS area of the record being added; the caller fills [g][d] at g*D + d and the (max, sum)
-  // pair of head g at gd + 2*g, then calls commit().
+  // LDS area of the record being added; the caller fills [col][d] at col*D + d and the
+  // (max, sum) pair of column col at gd + 2*col, then calls commit().
   __device__ float* next() const { return mem + count * rec; }
 
   __device__ void commit(int slot, float2* __restrict__ pml, float* __restrict__ pacc) {
@@ -84,7 +86,9 @@ template <class Math>
 __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
     Params p, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_pool,
     const uint16_t* __restrict__ v_pool, const int32_t* __restrict__ header,
-    const int4* __restrict__ desc, float2* __restrict__ pml, float* __restrict__ pacc) {
+    const typename Math::Desc* __restrict__ desc, float2* __restrict__ pml,
+    float* __restrict__ pacc) {
+  typedef typename Math::Desc Desc;
   constexpr int NBUF = Math::kBuffers;
   constexpr int LA = NBUF + 1;  // descriptor look-ahead in steps
   const int lane = threadIdx.x & (kWave - 1);
@@ -97,23 +101,24 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
 
   // Descriptors are wave-uniform: they are fetched with scalar loads LA steps ahead and live in
   // scalar registers.  dq[k] is the descriptor of step i + k.
-  const int4* dbase = desc + x0;
-  int4 dq[LA + 1];
+  const Desc* dbase = desc + x0;
+  Desc dq[LA + 1];
 #pragma unroll
   for (int k = 0; k <= LA; ++k) dq[k] = dbase[min(k, nsteps - 1)];
 
   __shared__ float stash_mem[kWavesPerGroup][kStashFloats];
-  PartialStash stash(stash_mem[threadIdx.x >> 6], p.G, p.D, lane);
+  PartialStash stash(stash_mem[threadIdx.x >> 6], Math::columns(p), p.D, lane);
   Math math(lane, p);
   typename Math::State st;
   typename Math::Q qnext;
   typename Math::Regs ring[NBUF];
-  math.load_q(qnext, q, dq[0].w);
+  math.load_q(qnext, q, dq[0]);
   math.reset(st);
 #pragma unroll
   for (int b = 0; b < NBUF; ++b) {
     const bool more = b < nsteps;
-    math.template issue<true>(ring[b], k_pool, v_pool, more ? dq[b].x : 0, more ? dq[b].y : 0);
+    math.template issue<true>(ring[b], k_pool, v_pool, more ? Math::ga(dq[b]) : 0,
+                              more ? Math::gb(dq[b]) : 0);
   }
 
   // One step of the pipeline.  In the steady-state loop every step refills its ring slot
@@ -124,18 +129,19 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
 #define VOX_STEP(I, B, REFILL)                                                             \
   {                                                                                        \
     const int i = (I);                                                                     \
-    const int meta = dq[0].z;                                                              \
-    const int sigma = dq[0].w;                                                             \
+    const Desc dcur = dq[0];                                                               \
+    const int meta = Math::meta(dcur);                                                     \
+    const int sigma = Math::sigma(dcur);                                                   \
     if (meta & kMetaFirst) {                                                               \
       math.reset(st);                                                                      \
       math.install_q(st, qnext);                                                           \
     }                                                                                      \
-    math.compute(st, ring[B], meta & kMetaTokMask);                                        \
-    if (i + 1 < nsteps && (dq[1].z & kMetaFirst)) math.load_q(qnext, q, dq[1].w);          \
+    math.compute(st, ring[B], dcur);                                                       \
+    if (i + 1 < nsteps && (Math::meta(dq[1]) & kMetaFirst)) math.load_q(qnext, q, dq[1]);  \
     if (REFILL) {                                                                          \
       const bool more = i + NBUF < nsteps;                                                 \
-      math.template issue<true>(ring[B], k_pool, v_pool, more ? dq[NBUF].x : 0,            \
-                                more ? dq[NBUF].y : 0);                                    \
+      math.template issue<true>(ring[B], k_pool, v_pool, more ? Math::ga(dq[NBUF]) : 0,    \
+                                more ? Math::gb(dq[NBUF]) : 0);                            \
     }                                                                                      \
     if (meta & kMetaLast) {                                                                \
       math.finish(st, stash.next());                                                       \

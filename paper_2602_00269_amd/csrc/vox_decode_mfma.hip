@@ -53,6 +53,13 @@ __device__ inline float round_bf16(float a) { return (float)(__bf16)a; }
 
 template <int D, int NBUF>
 struct MfmaMath {
+  typedef int4 Desc;  // decode step descriptor, see the plan kernel
+  __device__ static int ga(const Desc& d) { return d.x; }
+  __device__ static int gb(const Desc& d) { return d.y; }
+  __device__ static int meta(const Desc& d) { return d.z; }
+  __device__ static int sigma(const Desc& d) { return d.w; }
+  __device__ static int columns(const Params& p) { return p.G; }
+
   static constexpr int kBuffers = NBUF;
   static constexpr int kMinWavesPerSimd = 1;
   static constexpr int KK = D / 32;  // score MFMAs per block = V loads per block
@@ -85,7 +92,8 @@ struct MfmaMath {
   }
 
   // Query operand of segment sigma: column n -> row sigma*G + (n mod G) for n < 2G, else zero.
-  __device__ void load_q(Q& out, const uint16_t* __restrict__ q, int sigma) const {
+  __device__ void load_q(Q& out, const uint16_t* __restrict__ q, const Desc& dsc) const {
+    const int sigma = dsc.w;
     const bool has = n < 2 * G;
     const int row = sigma * G + (has ? (n < G ? n : n - G) : 0);
     const uint16_t* qrow = q + (size_t)row * D + c * 8;
@@ -122,7 +130,8 @@ struct MfmaMath {
     s.l = 0.f;
   }
 
-  __device__ void compute(State& s, Regs& r, int ntok) const {
+  __device__ void compute(State& s, Regs& r, const Desc& dsc) const {
+    const int ntok = dsc.z & kMetaTokMask;
     f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {

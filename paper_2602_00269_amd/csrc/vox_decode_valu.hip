@@ -48,6 +48,13 @@ __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0
 
 template <int D, int G>
 struct ValuMath {
+  typedef int4 Desc;  // decode step descriptor, see the plan kernel
+  __device__ static int ga(const Desc& d) { return d.x; }
+  __device__ static int gb(const Desc& d) { return d.y; }
+  __device__ static int meta(const Desc& d) { return d.z; }
+  __device__ static int sigma(const Desc& d) { return d.w; }
+  __device__ static int columns(const Params& p) { return p.G; }
+
   static constexpr int kBuffers = 2;
   static constexpr int kMinWavesPerSimd = 2;
   static constexpr int NL = D / 32;  // 16-byte loads per lane per granule
@@ -80,7 +87,8 @@ struct ValuMath {
   }
 
   // rows sigma*G .. sigma*G+G-1 of q are one contiguous run of QCHUNKS 16-byte pieces
-  __device__ void load_q(Q& out, const uint16_t* __restrict__ q, int sigma) const {
+  __device__ void load_q(Q& out, const uint16_t* __restrict__ q, const Desc& dsc) const {
+    const int sigma = dsc.w;
     const u32x4* src = reinterpret_cast<const u32x4*>(q + (size_t)sigma * G * D);
 #pragma unroll
     for (int j = 0; j < QPL; ++j) {
@@ -192,7 +200,8 @@ struct ValuMath {
     __builtin_amdgcn_wave_barrier();
   }
 
-  __device__ void compute(State& s, Regs& r, int ntok) const {
+  __device__ void compute(State& s, Regs& r, const Desc& dsc) const {
+    const int ntok = dsc.z & kMetaTokMask;
     block(s, r.k[0], r.v[0], min(ntok, kBlock));
     if (ntok > kBlock) block(s, r.k[1], r.v[1], ntok - kBlock);
   }

@@ -1,0 +1,540 @@
+// Multi-token step: stream s brings n_s new tokens (a prompt, an admission chunk, a detokenizer
+// chunk) that attend causally over its paged context.  The same split-K kernel skeleton as the
+// decode step is used; what changes is the meaning of the 16 MFMA columns and the plan.
+//
+// A tile is TQ = 16 / G consecutive new tokens of one stream; segment (tile, kv head) puts the
+// tile's TQ x G (token, head) pairs in the columns of the score MFMAs, column n = j * G + g, and
+// walks the context [0, position of the tile's last token] in 32-token steps.  Column j may
+// only see tokens up to its own position, which matters in the last steps of a segment only.
+// Probabilities are split hi + lo as in the decode step, but as two output MFMAs per tile
+// instead of duplicated columns.
+#include "vox_decode_core.hpp"
+#include "vox_merge.hpp"
+
+namespace vox {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kCols = 16;  // MFMA columns = record columns of the multi-token step
+
+// Step descriptor of the multi-token step (32 bytes, wave-uniform).
+//   a: granule of block A, granule of block B, meta (valid tokens | first | last), segment
+//   b: first query row of the tile, tokens in the tile, cm0, kv head
+//      cm0 = tokens of this step visible to column 0 (column j sees cm0 + j); >= 32: all
+struct MqDesc {
+  int4 a, b;
+};
+
+struct TileInfo {
+  int32_t stream, q_row0, nq, pos0;
+};
+
+__device__ inline f32x4 mfma32(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ inline f32x4 mfma16(u32x2 a, u32x2 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a),
+                                                   __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
+}
+__device__ inline uint32_t pack_bf16(float a, float b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v = {(__bf16)a, (__bf16)b};
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ inline float round_bf16(float a) { return (float)(__bf16)a; }
+
+template <int D, int NBUF>
+struct MqMath {
+  typedef MqDesc Desc;
+  __device__ static int ga(const Desc& d) { return d.a.x; }
+  __device__ static int gb(const Desc& d) { return d.a.y; }
+  __device__ static int meta(const Desc& d) { return d.a.z; }
+  __device__ static int sigma(const Desc& d) { return d.a.w; }
+  __device__ static int columns(const Params&) { return kCols; }
+
+  static constexpr int kBuffers = NBUF;
+  static constexpr int kMinWavesPerSimd = 1;
+  static constexpr int KK = D / 32;
+  static constexpr int NT = D / 16;
+
+  struct Q {
+    u32x4 b[KK];
+  };
+  struct Regs {
+    u32x4 k[2][KK], v[2][KK];
+  };
+  struct State {
+    Q q;
+    f32x4 acc[NT];
+    float m, l;
+  };
+
+  const Params& p;
+  int lane, n, c, jcol, gcol;
+  int k_off, v_off;
+
+  __device__ MqMath(int lane_, const Params& p_) : p(p_), lane(lane_) {
+    n = lane & 15;
+    c = lane >> 4;
+    jcol = n / p.G;  // query token of this column inside the tile
+    gcol = n - jcol * p.G;
+    k_off = n * 32 + c * 8;
+    v_off = c * D * 4 + n * 8;
+  }
+
+  __device__ void load_q(Q& out, const uint16_t* __restrict__ q, const Desc& d) const {
+    const bool has = jcol < d.b.y;
+    const int row = (d.b.x + (has ? jcol : 0)) * p.Hq + d.b.w * p.G + gcol;
+    const uint16_t* qrow = q + (size_t)row * D + c * 8;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      out.b[kk] = *reinterpret_cast<const u32x4*>(qrow + 32 * kk);
+      if (!has) out.b[kk] = u32x4{0, 0, 0, 0};
+    }
+  }
+
+  __device__ void install_q(State& s, const Q& next) const { s.q = next; }
+
+  template <bool STREAM>
+  __device__ void issue(Regs& r, const uint16_t* __restrict__ k_pool,
+                        const uint16_t* __restrict__ v_pool, int ga_, int gb_) const {
+    const uint16_t* ka = k_pool + (size_t)ga_ * (kBlock * D) + k_off;
+    const uint16_t* kb = k_pool + (size_t)gb_ * (kBlock * D) + k_off;
+    const uint16_t* va = v_pool + (size_t)ga_ * (kBlock * D) + v_off;
+    const uint16_t* vb = v_pool + (size_t)gb_ * (kBlock * D) + v_off;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) r.k[0][kk] = kv_load<STREAM>(ka + kk * 512);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) r.k[1][kk] = kv_load<STREAM>(kb + kk * 512);
+#pragma unroll
+    for (int j = 0; j < KK; ++j) r.v[0][j] = kv_load<STREAM>(va + j * 128);
+#pragma unroll
+    for (int j = 0; j < KK; ++j) r.v[1][j] = kv_load<STREAM>(vb + j * 128);
+  }
+
+  __device__ void reset(State& s) const {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) s.acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    s.m = -INFINITY;
+    s.l = 0.f;
+  }
+
+  __device__ void compute(State& s, Regs& r, const Desc& d) const {
+    const int ntok = d.a.z & kMetaTokMask;
+    const int cm0 = d.b.z;
+    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      sa = mfma32(r.k[0][kk], s.q.b[kk], sa);
+      sb = mfma32(r.k[1][kk], s.q.b[kk], sb);
+    }
+    float t[8] = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) t[e] *= p.scale_log2;
+    if (cm0 < kStepTokens) {
+      // causal edge: column j sees the first cm0 + j tokens of this step
+      const int lim = cm0 + jcol;
+      const int va = lim - 4 * c, vb = lim - kBlock - 4 * c;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (e >= va) t[e] = -INFINITY;
+        if (e >= vb) t[4 + e] = -INFINITY;
+      }
+    }
+    if (ntok < kStepTokens) {
+      // slots past the tile's last token may hold any bits: clear their V values (every
+      // column's probability there is zero, and 0 * NaN = NaN)
+      const int va = ntok - 4 * c, vb = ntok - kBlock - 4 * c;
+      const auto mask4 = [](int valid) {
+        const uint32_t lo = (0 < valid ? 0x0000FFFFu : 0u) | (1 < valid ? 0xFFFF0000u : 0u);
+        const uint32_t hi = (2 < valid ? 0x0000FFFFu : 0u) | (3 < valid ? 0xFFFF0000u : 0u);
+        return u32x4{lo, hi, lo, hi};
+      };
+      const u32x4 ma = mask4(va), mb = mask4(vb);
+#pragma unroll
+      for (int j = 0; j < KK; ++j) {
+        r.v[0][j] &= ma;
+        r.v[1][j] &= mb;
+      }
+    }
+    float mx = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])),
+                     fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(s.m, mx);
+    // a column may have seen no token yet (its run starts past its causal limit): keep the
+    // exponent arguments finite, everything it contributes is zero
+    const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(s.m - m_ref);
+    s.m = m_new;
+    float psum = 0.f;
+    uint32_t ph[4], pl[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(t[e] - m_ref);
+      const float p1 = __builtin_amdgcn_exp2f(t[e + 1] - m_ref);
+      psum += p0 + p1;
+      const float h0 = round_bf16(p0), h1 = round_bf16(p1);
+      ph[e >> 1] = pack_bf16(h0, h1);
+      pl[e >> 1] = pack_bf16(p0 - h0, p1 - h1);
+    }
+    s.l = s.l * alpha + psum;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) s.acc[nt] *= alpha;
+    }
+    const u32x2 pah = {ph[0], ph[1]}, pbh = {ph[2], ph[3]};
+    const u32x2 pal = {pl[0], pl[1]}, pbl = {pl[2], pl[3]};
+#pragma unroll
+    for (int j = 0; j < KK; ++j) {
+      const u32x4 a = r.v[0][j];
+      s.acc[2 * j] = mfma16(u32x2{a.x, a.y}, pah, s.acc[2 * j]);
+      s.acc[2 * j + 1] = mfma16(u32x2{a.z, a.w}, pah, s.acc[2 * j + 1]);
+    }
+#pragma unroll
+    for (int j = 0; j < KK; ++j) {
+      const u32x4 b = r.v[1][j];
+      s.acc[2 * j] = mfma16(u32x2{b.x, b.y}, pbh, s.acc[2 * j]);
+      s.acc[2 * j + 1] = mfma16(u32x2{b.z, b.w}, pbh, s.acc[2 * j + 1]);
+    }
+#pragma unroll
+    for (int j = 0; j < KK; ++j) {
+      const u32x4 a = r.v[0][j];
+      s.acc[2 * j] = mfma16(u32x2{a.x, a.y}, pal, s.acc[2 * j]);
+      s.acc[2 * j + 1] = mfma16(u32x2{a.z, a.w}, pal, s.acc[2 * j + 1]);
+    }
+#pragma unroll
+    for (int j = 0; j < KK; ++j) {
+      const u32x4 b = r.v[1][j];
+      s.acc[2 * j] = mfma16(u32x2{b.x, b.y}, pbl, s.acc[2 * j]);
+      s.acc[2 * j + 1] = mfma16(u32x2{b.z, b.w}, pbl, s.acc[2 * j + 1]);
+    }
+  }
+
+  // Record: [16 columns][D] accumulators, then 16 (max, sum) pairs.  A lane owns dims
+  // 32j + 8c .. +8 of its column: even ones in tile 2j, odd ones in tile 2j+1.
+  __device__ void finish(State& s, float* __restrict__ rec) const {
+    float l = s.l;
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    float* mine = rec + n * D + 8 * c;
+#pragma unroll
+    for (int j = 0; j < KK; ++j) {
+      const f32x4 e = s.acc[2 * j], o = s.acc[2 * j + 1];
+      *reinterpret_cast<f32x4*>(mine + 32 * j) = f32x4{e[0], o[0], e[1], o[1]};
+      *reinterpret_cast<f32x4*>(mine + 32 * j + 4) = f32x4{e[2], o[2], e[3], o[3]};
+    }
+    if (c == 0) *reinterpret_cast<float2*>(rec + kCols * D + 2 * n) = make_float2(s.m, l);
+  }
+};
+
+// ---------------------------------------------------------------------------------------
+// Plan, three small kernels.
+//   scan:   per stream tiles_s = ceil(n_s / TQ) and steps_s = sum over its tiles of
+//           ceil(ctx_tile / 32); exclusive scans PT (tiles) and PS (steps, per kv head).
+//   tiles:  per tile its first global step, step count, TileInfo and the row -> tile map.
+//   expand: per global step its descriptor (binary search over the tiles' first steps).
+__device__ inline int tile_ctx(int L, int n, int tq, int tau) {
+  return L - n + min(n, (tau + 1) * tq);  // tokens visible to the tile's last query
+}
+__device__ inline int steps_of(int ctx) { return (ctx + kStepTokens - 1) / kStepTokens; }
+
+constexpr int kScanThreads = 256;
+
+__global__ __launch_bounds__(kScanThreads) void mq_scan_kernel(
+    Params p, int tq, const int32_t* __restrict__ lens, const int32_t* __restrict__ qo, int waves,
+    int64_t desc_capacity, int32_t* __restrict__ header, int32_t* __restrict__ pt,
+    int32_t* __restrict__ ps) {
+  __shared__ int wave_tiles[kScanThreads / kWave], wave_steps[kScanThreads / kWave];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+  const int S = p.S;
+  const int per = (S + kScanThreads - 1) / kScanThreads;
+  const int lo = min(S, tid * per), hi = min(S, lo + per);
+  int tiles = 0, steps = 0;
+  for (int s = lo; s < hi; ++s) {
+    const int L = lens[s], n = qo[s + 1] - qo[s];
+    const int nt = (n + tq - 1) / tq;
+    for (int tau = 0; tau < nt; ++tau) steps += steps_of(tile_ctx(L, n, tq, tau));
+    tiles += nt;
+  }
+  int it = tiles, is = steps;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int a = __shfl_up(it, o), b = __shfl_up(is, o);
+    if (lane >= o) {
+      it += a;
+      is += b;
+    }
+  }
+  if (lane == kWave - 1) {
+    wave_tiles[wv] = it;
+    wave_steps[wv] = is;
+  }
+  __syncthreads();
+  int bt_ = it - tiles, bs_ = is - steps;
+  for (int k = 0; k < wv; ++k) {
+    bt_ += wave_tiles[k];
+    bs_ += wave_steps[k];
+  }
+  for (int s = lo; s < hi; ++s) {  // second walk writes the exclusive prefixes
+    pt[s] = bt_;
+    ps[s] = bs_;
+    const int L = lens[s], n = qo[s + 1] - qo[s];
+    const int nt = (n + tq - 1) / tq;
+    for (int tau = 0; tau < nt; ++tau) bs_ += steps_of(tile_ctx(L, n, tq, tau));
+    bt_ += nt;
+  }
+  if (tid == kScanThreads - 1) {
+    pt[S] = bt_;
+    ps[S] = bs_;
+    const int64_t n_all = (int64_t)bs_ * p.Hkv;
+    const int64_t N = min(n_all, desc_capacity);
+    header[kHdrSteps] = (int)N;
+    header[kHdrPerWave] = (int)max((int64_t)1, (N + waves - 1) / waves);
+    header[kHdrWaves] = waves;
+    header[kHdrOverflow] = n_all > desc_capacity;
+  }
+}
+
+__global__ __launch_bounds__(256) void mq_tiles_kernel(
+    Params p, int tq, const int32_t* __restrict__ lens, const int32_t* __restrict__ qo,
+    const int32_t* __restrict__ header, const int32_t* __restrict__ pt,
+    const int32_t* __restrict__ ps, int32_t* __restrict__ tile_first,
+    int32_t* __restrict__ tile_steps, TileInfo* __restrict__ tile_info,
+    int32_t* __restrict__ row_tile) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  const int total = pt[p.S];
+  if (t >= total) return;
+  int a = 0, b = p.S;  // largest s with pt[s] <= t
+  while (b - a > 1) {
+    const int mid = (a + b) >> 1;
+    if (pt[mid] <= t)
+      a = mid;
+    else
+      b = mid;
+  }
+  const int s = a, tau = t - pt[s];
+  const int L = lens[s], n = qo[s + 1] - qo[s];
+  int cum = 0;
+  for (int k = 0; k < tau; ++k) cum += steps_of(tile_ctx(L, n, tq, k));
+  tile_first[t] = (ps[s] + cum) * p.Hkv;
+  tile_steps[t] = steps_of(tile_ctx(L, n, tq, tau));
+  TileInfo info;
+  info.stream = s;
+  info.q_row0 = qo[s] + tau * tq;
+  info.nq = min(tq, n - tau * tq);
+  info.pos0 = L - n + tau * tq;
+  tile_info[t] = info;
+  for (int j = 0; j < info.nq; ++j) row_tile[info.q_row0 + j] = t;
+  if (t == total - 1) tile_first[total] = ps[p.S] * p.Hkv;
+}
+
+__global__ __launch_bounds__(256) void mq_expand_kernel(
+    Params p, const int32_t* __restrict__ bt, const int32_t* __restrict__ header,
+    const int32_t* __restrict__ pt, const int32_t* __restrict__ tile_first,
+    const int32_t* __restrict__ tile_steps, const TileInfo* __restrict__ tile_info,
+    MqDesc* __restrict__ desc) {
+  const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int N = header[kHdrSteps], Q = header[kHdrPerWave];
+  if (x >= N) return;
+  int a = 0, b = pt[p.S];  // largest t with tile_first[t] <= x
+  while (b - a > 1) {
+    const int mid = (a + b) >> 1;
+    if (tile_first[mid] <= x)
+      a = mid;
+    else
+      b = mid;
+  }
+  const int t = a, f = tile_steps[t];
+  const int r = (int)(x - tile_first[t]);
+  const int h = r / f, st = r - h * f;
+  const TileInfo info = tile_info[t];
+  const int ctx = info.pos0 + info.nq;
+  const int nb = (ctx + kBlock - 1) / kBlock;
+  const int32_t* row = bt + (size_t)info.stream * p.max_nb;
+  const int ida = row[2 * st];
+  const int idb = (2 * st + 1 < nb) ? row[2 * st + 1] : ida;
+  int meta = min(kStepTokens, ctx - kStepTokens * st);
+  if (st == 0 || x % Q == 0) meta |= kMetaFirst;
+  if (st == f - 1 || x % Q == Q - 1 || x == N - 1) meta |= kMetaLast;
+  MqDesc d;
+  d.a = make_int4(ida * p.Hkv + h, idb * p.Hkv + h, meta, t * p.Hkv + h);
+  d.b = make_int4(info.q_row0, info.nq, info.pos0 + 1 - kStepTokens * st, h);
+  desc[x] = d;
+}
+
+// ---------------------------------------------------------------------------------------
+// Merge: one wave per (query row, q head).
+template <int D>
+__global__ __launch_bounds__(256) void mq_merge_kernel(
+    Params p, int total_q, const int32_t* __restrict__ header,
+    const int32_t* __restrict__ tile_first, const int32_t* __restrict__ tile_steps,
+    const TileInfo* __restrict__ tile_info, const int32_t* __restrict__ row_tile,
+    const float2* __restrict__ pml, const float* __restrict__ pacc, float* __restrict__ out,
+    float* __restrict__ lse) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int w = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
+  if (w >= total_q * p.Hq) return;
+  const int row = w / p.Hq, i = w % p.Hq;
+  const int h = i / p.G, g = i % p.G;
+  const int t = row_tile[row];
+  const TileInfo info = tile_info[t];
+  const int Q = header[kHdrPerWave];
+  const int64_t N = header[kHdrSteps];
+  const int f = tile_steps[t];
+  const int64_t first = (int64_t)tile_first[t] + (int64_t)h * f;
+  int n = 0;
+  int64_t slot0 = 0;
+  if (first < N) {
+    const int64_t last = min(N, first + f) - 1;
+    const int64_t w0 = first / Q, w1 = last / Q;
+    n = (int)(w1 - w0 + 1);
+    slot0 = w0 + (int64_t)t * p.Hkv + h;
+  }
+  const int col = (row - info.q_row0) * p.G + g;
+  merge_runs<D>(pml, pacc, slot0, n, kCols, col, lane, out + (size_t)w * D,
+                lse ? lse + w : nullptr);
+}
+
+// ---------------------------------------------------------------------------------------
+// Multi-token append: one wave per (new row, kv head).  Rows of one stream may share a 4-token
+// V quad, so the V slots are stored as 2-byte writes (no read-modify-write of shared bytes).
+template <int D>
+__global__ __launch_bounds__(256) void kv_append_multi_kernel(
+    Params p, int total_q, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
+    uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool, const int32_t* __restrict__ bt,
+    const int32_t* __restrict__ lens, const int32_t* __restrict__ qo) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int w = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
+  if (w >= total_q * p.Hkv) return;
+  const int row = w / p.Hkv, h = w % p.Hkv;
+  int a = 0, b = p.S;  // largest s with qo[s] <= row
+  while (b - a > 1) {
+    const int mid = (a + b) >> 1;
+    if (qo[mid] <= row)
+      a = mid;
+    else
+      b = mid;
+  }
+  const int s = a;
+  const int n = qo[s + 1] - qo[s];
+  const int pos = lens[s] - n + (row - qo[s]);
+  if (pos < 0) return;
+  const int64_t blk = bt[(int64_t)s * p.max_nb + (pos >> 4)];
+  const int t = pos & (kBlock - 1);
+  const size_t g = granule_offset(blk, h, p.Hkv, D);
+  const uint16_t* krow = k_new + (size_t)w * D;
+  const uint16_t* vrow = v_new + (size_t)w * D;
+  if (lane < D / 8)
+    *reinterpret_cast<u32x4*>(k_pool + g + k_elem(t, lane * 8)) =
+        *reinterpret_cast<const u32x4*>(krow + lane * 8);
+  if (lane < D / 2) {
+    const uint32_t two = *reinterpret_cast<const uint32_t*>(vrow + 2 * lane);
+    v_pool[g + v_elem(t, 2 * lane, D)] = (uint16_t)(two & 0xFFFFu);
+    v_pool[g + v_elem(t, 2 * lane + 1, D)] = (uint16_t)(two >> 16);
+  }
+}
+
+}  // namespace
+
+// Workspace map of the multi-token step (byte offsets), for `tiles` tiles at most, `total_q`
+// query rows, `slots` partial records and `desc_capacity` step descriptors.
+PrefillWorkspace map_prefill_workspace(const Params& p, int64_t tiles, int64_t total_q,
+                                       int64_t slots, int64_t desc_capacity) {
+  PrefillWorkspace w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off = align_up(off + bytes, 256);
+    return at;
+  };
+  w.header = take(64 * sizeof(int32_t));
+  w.pt = take(((size_t)p.S + 1) * sizeof(int32_t));
+  w.ps = take(((size_t)p.S + 1) * sizeof(int32_t));
+  w.tile_first = take(((size_t)tiles + 1) * sizeof(int32_t));
+  w.tile_steps = take((size_t)tiles * sizeof(int32_t));
+  w.tile_info = take((size_t)tiles * sizeof(TileInfo));
+  w.row_tile = take((size_t)total_q * sizeof(int32_t));
+  w.partial_ml = take((size_t)slots * kCols * sizeof(float2));
+  w.partial_acc = take((size_t)slots * kCols * p.D * sizeof(float));
+  w.desc = take((size_t)desc_capacity * sizeof(MqDesc));
+  w.total = off;
+  return w;
+}
+
+size_t prefill_desc_bytes() { return sizeof(MqDesc); }
+
+hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_new,
+                                  const void* v_new, void* k_pool, void* v_pool,
+                                  const int32_t* bt, const int32_t* lens, const int32_t* qo,
+                                  hipStream_t st) {
+  if (total_q <= 0) return hipSuccess;
+  const unsigned grid =
+      (unsigned)(((int64_t)total_q * p.Hkv + kWavesPerGroup - 1) / kWavesPerGroup);
+  if (p.D == 128)
+    hipLaunchKernelGGL(kv_append_multi_kernel<128>, dim3(grid), dim3(256), 0, st, p, total_q,
+                       (const uint16_t*)k_new, (const uint16_t*)v_new, (uint16_t*)k_pool,
+                       (uint16_t*)v_pool, bt, lens, qo);
+  else
+    hipLaunchKernelGGL(kv_append_multi_kernel<64>, dim3(grid), dim3(256), 0, st, p, total_q,
+                       (const uint16_t*)k_new, (const uint16_t*)v_new, (uint16_t*)k_pool,
+                       (uint16_t*)v_pool, bt, lens, qo);
+  return hipGetLastError();
+}
+
+hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, int tq,
+                          int64_t tiles, int64_t steps, int64_t desc_capacity, int waves,
+                          int total_q, const void* q, const void* k_pool, const void* v_pool,
+                          const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
+                          float* lse, hipStream_t st) {
+  int32_t* header = (int32_t*)(ws + m.header);
+  int32_t* pt = (int32_t*)(ws + m.pt);
+  int32_t* ps = (int32_t*)(ws + m.ps);
+  int32_t* tile_first = (int32_t*)(ws + m.tile_first);
+  int32_t* tile_steps = (int32_t*)(ws + m.tile_steps);
+  TileInfo* tile_info = (TileInfo*)(ws + m.tile_info);
+  int32_t* row_tile = (int32_t*)(ws + m.row_tile);
+  float2* pml = (float2*)(ws + m.partial_ml);
+  float* pacc = (float*)(ws + m.partial_acc);
+  MqDesc* desc = (MqDesc*)(ws + m.desc);
+
+  hipLaunchKernelGGL(mq_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, p, tq, lens, qo, waves,
+                     desc_capacity, header, pt, ps);
+  if (tiles > 0) {
+    hipLaunchKernelGGL(mq_tiles_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, st,
+                       p, tq, lens, qo, header, pt, ps, tile_first, tile_steps, tile_info,
+                       row_tile);
+    hipLaunchKernelGGL(mq_expand_kernel, dim3((unsigned)((steps + 255) / 256)), dim3(256), 0, st,
+                       p, bt, header, pt, tile_first, tile_steps, tile_info, desc);
+    int launch_waves = waves;
+    if (steps < launch_waves)
+      launch_waves = (int)((steps + kWavesPerGroup - 1) / kWavesPerGroup * kWavesPerGroup);
+    const unsigned grid = (unsigned)(launch_waves / kWavesPerGroup);
+    Params pk = p;  // the kernels read N and Q from the header the scan kernel wrote
+    pk.n_steps = pk.per_wave = -1;
+    if (p.D == 128)
+      hipLaunchKernelGGL((decode_kernel<MqMath<128, 3>>), dim3(grid), dim3(256), 0, st, pk,
+                         (const uint16_t*)q, (const uint16_t*)k_pool, (const uint16_t*)v_pool,
+                         header, desc, pml, pacc);
+    else
+      hipLaunchKernelGGL((decode_kernel<MqMath<64, 2>>), dim3(grid), dim3(256), 0, st, pk,
+                         (const uint16_t*)q, (const uint16_t*)k_pool, (const uint16_t*)v_pool,
+                         header, desc, pml, pacc);
+    const unsigned mg =
+        (unsigned)(((int64_t)total_q * p.Hq + kWavesPerGroup - 1) / kWavesPerGroup);
+    if (p.D == 128)
+      hipLaunchKernelGGL(mq_merge_kernel<128>, dim3(mg), dim3(256), 0, st, p, total_q, header,
+                         tile_first, tile_steps, tile_info, row_tile, pml, pacc, out, lse);
+    else
+      hipLaunchKernelGGL(mq_merge_kernel<64>, dim3(mg), dim3(256), 0, st, p, total_q, header,
+                         tile_first, tile_steps, tile_info, row_tile, pml, pacc, out, lse);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace vox

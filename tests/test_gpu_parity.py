@@ -414,3 +414,79 @@ def test_workspace_reuse_across_calls_with_different_lengths(dev):
         _assert_close(out.cpu().numpy(), ref, wl.name)
         results.append(out.cpu().numpy())
     assert np.array_equal(results[0], results[2])
+
+
+# ------------------------------------------------------------------ multi-token step
+
+
+def _prefill_case(dev, lens, nq, hq, hkv, d, seed):
+    lens = np.asarray(lens, dtype=np.int32)
+    nq = np.asarray(nq, dtype=np.int32)
+    w = synth.make_custom(lens, hq, hkv, d, seed=seed, device=dev)
+    qo = np.zeros(lens.size + 1, dtype=np.int32)
+    qo[1:] = np.cumsum(nq)
+    tq = int(qo[-1])
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed + 1)
+
+    def rnd(shape):
+        return torch.randn(shape, generator=gen, device=dev).to(torch.bfloat16)
+
+    return w, qo, rnd((tq, hq, d)), rnd((tq, hkv, d)), rnd((tq, hkv, d))
+
+
+PREFILL_CASES = [
+    # lens, new tokens per stream, Hq, Hkv, D
+    ([37, 16, 5, 64, 9, 300], [37, 3, 0, 17, 9, 1], 24, 8, 128),   # whole prompts, chunks, decode
+    ([1, 2, 31, 32, 33, 65], [1, 2, 31, 32, 33, 65], 8, 2, 64),    # prompts from scratch
+    ([700, 1500, 90], [28, 25, 15], 14, 2, 64),                    # detokenizer-style chunks, G = 7
+    ([2000, 40], [500, 40], 8, 8, 128),                            # long prompt, G = 1
+    ([129, 4097], [129, 2], 8, 1, 128),                            # G = 8
+]
+
+
+@pytest.mark.parametrize("case", range(len(PREFILL_CASES)))
+def test_multi_token_append_and_prefill_match_oracle(dev, case):
+    lens, nq, hq, hkv, d = PREFILL_CASES[case]
+    w, qo, q, k_new, v_new = _prefill_case(dev, lens, nq, hq, hkv, d, seed=80 + case)
+    sh = binding.shape_of(w)
+    bt, lens_d, qo_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev), _i32(qo, dev)
+    kp_ref, vp_ref = _host_pools(w)
+    oracle.kv_append_multi(bits_of(k_new), bits_of(v_new), kp_ref, vp_ref, w.block_tables,
+                           w.context_lens, qo, head_dim=d)
+    binding.kv_append_multi(sh, k_new, v_new, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d)
+    torch.cuda.synchronize()
+    kp, vp = _host_pools(w)
+    assert np.array_equal(kp, kp_ref) and np.array_equal(vp, vp_ref)  # bit-exact, whole pools
+    ref, ref_lse = oracle.paged_prefill(bits_of(q), kp_ref, vp_ref, w.block_tables,
+                                        w.context_lens, qo, w.scale, num_kv_heads=hkv)
+    tq = int(qo[-1])
+    for waves in (0, 8, 4096):
+        sh.split_waves = waves
+        out = torch.full((tq, hq, d), float("nan"), device=dev)
+        lse = torch.full((tq, hq), float("nan"), device=dev)
+        ws = torch.empty(binding.paged_prefill_workspace_bytes(sh, tq), dtype=torch.uint8,
+                         device=dev)
+        ws.fill_(0xFF)
+        binding.paged_prefill(sh, q, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d, w.context_lens,
+                              qo, out, ws, lse=lse)
+        torch.cuda.synchronize()
+        _assert_close(out.cpu().numpy(), ref, f"prefill case {case} waves {waves}")
+        _assert_lse(lse.cpu().numpy(), ref_lse, f"prefill case {case} waves {waves}")
+
+
+def test_prefill_with_one_token_per_stream_equals_decode(dev):
+    lens = [33, 700, 64, 1, 255]
+    w, qo, q, _, _ = _prefill_case(dev, lens, [1] * 5, 24, 8, 128, seed=90)
+    sh = binding.shape_of(w)
+    bt, lens_d, qo_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev), _i32(qo, dev)
+    out = torch.zeros((5, 24, 128), device=dev)
+    ws = torch.empty(binding.paged_prefill_workspace_bytes(sh, 5), dtype=torch.uint8, device=dev)
+    binding.paged_prefill(sh, q, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d, w.context_lens, qo,
+                          out, ws)
+    out_d = torch.zeros_like(out)
+    ws_d = binding.alloc_workspace(sh, dev)
+    binding.paged_decode(sh, q, w.k_pool[0], w.v_pool[0], bt, lens_d, out_d, ws_d,
+                         context_lens_host=w.context_lens)
+    torch.cuda.synchronize()
+    assert (out - out_d).abs().max().item() <= 1e-5
