@@ -275,7 +275,8 @@ size_t vox_paged_prefill_workspace_bytes(const vox_shape_t* shape, int32_t total
   const int64_t tiles = (int64_t)total_q + shape->num_streams;  // every tile holds >= 1 row
   const int64_t steps = tiles * ((shape->max_blocks_per_stream + 1) / 2) * shape->num_kv_heads;
   const int64_t slots = split_waves(shape) + tiles * shape->num_kv_heads;
-  return map_prefill_workspace(p, tiles, total_q, slots, steps).total;
+  const int ncg = prefill_column_groups(p, total_q);  // the widest records any call may use
+  return map_prefill_workspace(p, ncg, tiles, total_q, slots, steps).total;
 }
 
 int vox_kv_append_multi(const vox_shape_t* shape, const void* k_new, const void* v_new,
@@ -305,10 +306,16 @@ int vox_paged_prefill(const vox_shape_t* shape, const void* q, const void* k_poo
     return VOX_ERR_NULL;
   if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
   const Params p = make_params(shape);
-  const int tq = 16 / p.G;
   // exact tile and step counts from the host copies (the scheduler that admits a prompt
   // knows its length)
   if (q_offsets_host[0] != 0) return VOX_ERR_ARG;
+  int64_t max_new = 0;
+  for (int s = 0; s < p.S; ++s) {
+    const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
+    if (n > max_new) max_new = n;
+  }
+  const int ncg = prefill_column_groups(p, (int)(max_new < INT32_MAX ? max_new : INT32_MAX));
+  const int tq = (16 / p.G) * ncg;
   int64_t tiles = 0, steps = 0;
   for (int s = 0; s < p.S; ++s) {
     const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
@@ -326,9 +333,9 @@ int vox_paged_prefill(const vox_shape_t* shape, const void* q, const void* k_poo
   if (steps > INT32_MAX || tiles * p.Hkv > INT32_MAX / 2) return VOX_ERR_SHAPE;
   const int waves = split_waves(shape);
   const int64_t slots = waves + tiles * p.Hkv;
-  const PrefillWorkspace m = map_prefill_workspace(p, tiles, total_q, slots, steps);
+  const PrefillWorkspace m = map_prefill_workspace(p, ncg, tiles, total_q, slots, steps);
   if (m.total > workspace_bytes) return VOX_ERR_WORKSPACE;
-  return launch_prefill(p, m, (char*)workspace, tq, tiles, steps, steps, waves, (int)total_q, q,
+  return launch_prefill(p, m, (char*)workspace, ncg, tiles, steps, steps, waves, (int)total_q, q,
                         k_pool, v_pool, block_tables, context_lens, q_offsets, out, lse,
                         (hipStream_t)hip_stream) == hipSuccess
              ? VOX_OK

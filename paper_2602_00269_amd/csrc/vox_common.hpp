@@ -98,14 +98,15 @@ hipError_t launch_merge_append(const Params& p, const int32_t* header, const int
                                const float2* partial_ml, const float* partial_acc, float* out,
                                const int32_t* bt, const int32_t* lens, const void* k_new,
                                const void* v_new, void* k_pool, void* v_pool, hipStream_t st);
-PrefillWorkspace map_prefill_workspace(const Params& p, int64_t tiles, int64_t total_q,
+PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, int64_t total_q,
                                        int64_t slots, int64_t desc_capacity);
+int prefill_column_groups(const Params& p, int max_new_tokens);
 size_t prefill_desc_bytes();
 hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_new,
                                   const void* v_new, void* k_pool, void* v_pool,
                                   const int32_t* bt, const int32_t* lens, const int32_t* qo,
                                   hipStream_t st);
-hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, int tq,
+hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, int ncg,
                           int64_t tiles, int64_t steps, int64_t desc_capacity, int waves,
                           int total_q, const void* q, const void* k_pool, const void* v_pool,
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,

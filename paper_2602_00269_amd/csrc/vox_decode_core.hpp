@@ -10,10 +10,11 @@
 // `Math` supplies the registers and arithmetic of one step:
 //   struct Q (query rows in flight), struct Regs (one step of K/V), struct State;
 //   struct Desc (step descriptor) with static accessors ga/gb/meta/sigma; columns(params);
-//   Math(lane, params); load_q(Q&, q, desc); install_q(State&, Q&);
+//   Math(lane, params); load_q(Q&, q, desc) one step ahead; install_q(State&, Q&, q, desc);
 //   issue(Regs&, k_pool, v_pool, ga, gb); reset(State&); compute(State&, Regs&, desc);
-//   finish(State&, float* record): writes the run's [G][D] accumulators and [G] (max, sum)
-//   pairs into the LDS record.
+//   finish(State&, float* acc, float* ml): writes the run's [columns][D] accumulators to acc
+//   and its [columns] (max, sum) pairs to ml (an LDS record, or global memory when a record
+//   does not fit the LDS buffer).
 #pragma once
 
 #include "vox_common.hpp"
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
     const int sigma = Math::sigma(dcur);                                                   \
     if (meta & kMetaFirst) {                                                               \
       math.reset(st);                                                                      \
-      math.install_q(st, qnext);                                                           \
+      math.install_q(st, qnext, q, dcur);                                                  \
     }                                                                                      \
     math.compute(st, ring[B], dcur);                                                       \
     if (i + 1 < nsteps && (Math::meta(dq[1]) & kMetaFirst)) math.load_q(qnext, q, dq[1]);  \
@@ -144,8 +145,15 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
                                 more ? Math::gb(dq[NBUF]) : 0);                            \
     }                                                                                      \
     if (meta & kMetaLast) {                                                                \
-      math.finish(st, stash.next());                                                       \
-      stash.commit(w + sigma, pml, pacc);                                                  \
+      if (stash.cap > 0) {                                                                 \
+        float* rec = stash.next();                                                         \
+        math.finish(st, rec, rec + stash.gd);                                              \
+        stash.commit(w + sigma, pml, pacc);                                                \
+      } else { /* record larger than the LDS buffer: straight to global memory */          \
+        const size_t slot = (size_t)(w + sigma);                                           \
+        math.finish(st, pacc + slot * stash.gd,                                            \
+                    reinterpret_cast<float*>(pml + slot * Math::columns(p)));              \
+      }                                                                                    \
     }                                                                                      \
     _Pragma("unroll") for (int k = 0; k < LA; ++k) dq[k] = dq[k + 1];                      \
     dq[LA] = dbase[min(i + 1 + LA, nsteps - 1)];                                           \

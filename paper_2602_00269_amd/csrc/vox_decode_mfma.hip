@@ -104,7 +104,9 @@ struct MfmaMath {
     }
   }
 
-  __device__ void install_q(State& s, const Q& next) const { s.q = next; }
+  __device__ void install_q(State& s, const Q& next, const uint16_t*, const Desc&) const {
+    s.q = next;
+  }
 
   template <bool STREAM>
   __device__ void issue(Regs& r, const uint16_t* __restrict__ k_pool,
@@ -208,7 +210,7 @@ struct MfmaMath {
   // their accumulators first, the hi columns [0,G) then add their own on top (lane (n,c) and
   // lane (n+G,c) address the same floats), so no register shuffles are needed.  A lane owns
   // dims 32j + 8c .. +8 of its column: even ones in tile 2j, odd ones in tile 2j+1.
-  __device__ void finish(State& s, float* __restrict__ rec) const {
+  __device__ void finish(State& s, float* __restrict__ rec, float* __restrict__ ml) const {
     float l = s.l;
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
@@ -234,7 +236,7 @@ struct MfmaMath {
         *d0 = *d0 + f32x4{e[0], o[0], e[1], o[1]};
         *d1 = *d1 + f32x4{e[2], o[2], e[3], o[3]};
       }
-      if (c == 0) *reinterpret_cast<float2*>(rec + G * D + 2 * n) = make_float2(s.m, l);
+      if (c == 0) *reinterpret_cast<float2*>(ml + 2 * n) = make_float2(s.m, l);
     }
   }
 };

@@ -97,7 +97,7 @@ struct ValuMath {
     }
   }
 
-  __device__ void install_q(State&, const Q& next) const {
+  __device__ void install_q(State&, const Q& next, const uint16_t*, const Desc&) const {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -206,7 +206,7 @@ struct ValuMath {
     if (ntok > kBlock) block(s, r.k[1], r.v[1], ntok - kBlock);
   }
 
-  __device__ void finish(State& s, float* __restrict__ rec) const {
+  __device__ void finish(State& s, float* __restrict__ rec, float* __restrict__ ml) const {
     const int m = lane % (D / 2);  // dim pair owned by this lane
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -219,7 +219,7 @@ struct ValuMath {
       lsum += __shfl_xor(lsum, 16);
       lsum += __shfl_xor(lsum, 32);
       lsum *= 0.25f;
-      if (lane == 0) *reinterpret_cast<float2*>(rec + G * D + 2 * g) = make_float2(s.m[g], lsum);
+      if (lane == 0) *reinterpret_cast<float2*>(ml + 2 * g) = make_float2(s.m[g], lsum);
       float a0 = s.acc[g][0], a1 = s.acc[g][1];
       if (D == 64) {  // lanes l and l + 32 hold the same dim pair for different token quads
         a0 += __shfl_xor(a0, 32);

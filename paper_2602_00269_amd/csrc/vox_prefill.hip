@@ -2,9 +2,10 @@
 // chunk) that attend causally over its paged context.  The same split-K kernel skeleton as the
 // decode step is used; what changes is the meaning of the 16 MFMA columns and the plan.
 //
-// A tile is TQ = 16 / G consecutive new tokens of one stream; segment (tile, kv head) puts the
-// tile's TQ x G (token, head) pairs in the columns of the score MFMAs, column n = j * G + g, and
-// walks the context [0, position of the tile's last token] in 32-token steps.  Column j may
+// A column group is TQ = 16 / G consecutive new tokens of one stream: their TQ x G (token, head)
+// pairs fill the 16 columns of the score MFMAs, column n = j * G + g.  A tile is 1, 2 or 4
+// column groups (chosen from the largest n_s) that share every loaded K/V step; segment (tile,
+// kv head) walks the context [0, position of the tile's last token] in 32-token steps.  Column j may
 // only see tokens up to its own position, which matters in the last steps of a segment only.
 // Probabilities are split hi + lo as in the decode step, but as two output MFMAs per tile
 // instead of duplicated columns.
@@ -48,57 +49,76 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
 }
 __device__ inline float round_bf16(float a) { return (float)(__bf16)a; }
 
-template <int D, int NBUF>
+template <int D, int NBUF, int NCG>
 struct MqMath {
   typedef MqDesc Desc;
   __device__ static int ga(const Desc& d) { return d.a.x; }
   __device__ static int gb(const Desc& d) { return d.a.y; }
   __device__ static int meta(const Desc& d) { return d.a.z; }
   __device__ static int sigma(const Desc& d) { return d.a.w; }
-  __device__ static int columns(const Params&) { return kCols; }
+  __device__ static int columns(const Params&) { return kCols * NCG; }
 
   static constexpr int kBuffers = NBUF;
   static constexpr int kMinWavesPerSimd = 1;
   static constexpr int KK = D / 32;
   static constexpr int NT = D / 16;
 
+  // With one column group the query rows of the next run are fetched a step ahead like in the
+  // decode step; with more groups they would cost too many registers and are loaded when the
+  // run starts (runs are long in that regime: a whole context per tile).
   struct Q {
-    u32x4 b[KK];
+    u32x4 b[NCG == 1 ? KK : 1];
   };
   struct Regs {
     u32x4 k[2][KK], v[2][KK];
   };
   struct State {
-    Q q;
-    f32x4 acc[NT];
-    float m, l;
+    u32x4 q[NCG][KK];
+    f32x4 acc[NCG][NT];
+    float m[NCG], l[NCG];
   };
 
   const Params& p;
-  int lane, n, c, jcol, gcol;
+  int lane, n, c, jcol, gcol, tq;
   int k_off, v_off;
 
   __device__ MqMath(int lane_, const Params& p_) : p(p_), lane(lane_) {
     n = lane & 15;
     c = lane >> 4;
-    jcol = n / p.G;  // query token of this column inside the tile
+    tq = kCols / p.G;  // query tokens per column group
+    jcol = n / p.G;    // token of this column inside its group (valid when < tq)
     gcol = n - jcol * p.G;
     k_off = n * 32 + c * 8;
     v_off = c * D * 4 + n * 8;
   }
 
-  __device__ void load_q(Q& out, const uint16_t* __restrict__ q, const Desc& d) const {
-    const bool has = jcol < d.b.y;
-    const int row = (d.b.x + (has ? jcol : 0)) * p.Hq + d.b.w * p.G + gcol;
+  __device__ void load_group(u32x4 (&dst)[KK], const uint16_t* __restrict__ q, const Desc& d,
+                             int cg) const {
+    const int tok = cg * tq + jcol;
+    const bool has = jcol < tq && tok < d.b.y;
+    const int row = (d.b.x + (has ? tok : 0)) * p.Hq + d.b.w * p.G + gcol;
     const uint16_t* qrow = q + (size_t)row * D + c * 8;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      out.b[kk] = *reinterpret_cast<const u32x4*>(qrow + 32 * kk);
-      if (!has) out.b[kk] = u32x4{0, 0, 0, 0};
+      dst[kk] = *reinterpret_cast<const u32x4*>(qrow + 32 * kk);
+      if (!has) dst[kk] = u32x4{0, 0, 0, 0};
     }
   }
 
-  __device__ void install_q(State& s, const Q& next) const { s.q = next; }
+  __device__ void load_q(Q& out, const uint16_t* __restrict__ q, const Desc& d) const {
+    if (NCG == 1) load_group(reinterpret_cast<u32x4(&)[KK]>(out.b), q, d, 0);
+  }
+
+  __device__ void install_q(State& s, const Q& next, const uint16_t* __restrict__ q,
+                            const Desc& d) const {
+    if (NCG == 1) {
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) s.q[0][kk] = next.b[NCG == 1 ? kk : 0];
+    } else {
+#pragma unroll
+      for (int cg = 0; cg < NCG; ++cg) load_group(s.q[cg], q, d, cg);
+    }
+  }
 
   template <bool STREAM>
   __device__ void issue(Regs& r, const uint16_t* __restrict__ k_pool,
@@ -119,33 +139,17 @@ struct MqMath {
 
   __device__ void reset(State& s) const {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) s.acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    s.m = -INFINITY;
-    s.l = 0.f;
+    for (int cg = 0; cg < NCG; ++cg) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) s.acc[cg][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      s.m[cg] = -INFINITY;
+      s.l[cg] = 0.f;
+    }
   }
 
   __device__ void compute(State& s, Regs& r, const Desc& d) const {
     const int ntok = d.a.z & kMetaTokMask;
     const int cm0 = d.b.z;
-    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      sa = mfma32(r.k[0][kk], s.q.b[kk], sa);
-      sb = mfma32(r.k[1][kk], s.q.b[kk], sb);
-    }
-    float t[8] = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) t[e] *= p.scale_log2;
-    if (cm0 < kStepTokens) {
-      // causal edge: column j sees the first cm0 + j tokens of this step
-      const int lim = cm0 + jcol;
-      const int va = lim - 4 * c, vb = lim - kBlock - 4 * c;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if (e >= va) t[e] = -INFINITY;
-        if (e >= vb) t[4 + e] = -INFINITY;
-      }
-    }
     if (ntok < kStepTokens) {
       // slots past the tile's last token may hold any bits: clear their V values (every
       // column's probability there is zero, and 0 * NaN = NaN)
@@ -162,74 +166,100 @@ struct MqMath {
         r.v[1][j] &= mb;
       }
     }
-    float mx = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])),
-                     fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(s.m, mx);
-    // a column may have seen no token yet (its run starts past its causal limit): keep the
-    // exponent arguments finite, everything it contributes is zero
-    const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(s.m - m_ref);
-    s.m = m_new;
-    float psum = 0.f;
-    uint32_t ph[4], pl[4];
 #pragma unroll
-    for (int e = 0; e < 8; e += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(t[e] - m_ref);
-      const float p1 = __builtin_amdgcn_exp2f(t[e + 1] - m_ref);
-      psum += p0 + p1;
-      const float h0 = round_bf16(p0), h1 = round_bf16(p1);
-      ph[e >> 1] = pack_bf16(h0, h1);
-      pl[e >> 1] = pack_bf16(p0 - h0, p1 - h1);
-    }
-    s.l = s.l * alpha + psum;
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
+    for (int cg = 0; cg < NCG; ++cg) {
+      f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) s.acc[nt] *= alpha;
-    }
-    const u32x2 pah = {ph[0], ph[1]}, pbh = {ph[2], ph[3]};
-    const u32x2 pal = {pl[0], pl[1]}, pbl = {pl[2], pl[3]};
+      for (int kk = 0; kk < KK; ++kk) {
+        sa = mfma32(r.k[0][kk], s.q[cg][kk], sa);
+        sb = mfma32(r.k[1][kk], s.q[cg][kk], sb);
+      }
+      float t[8] = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
 #pragma unroll
-    for (int j = 0; j < KK; ++j) {
-      const u32x4 a = r.v[0][j];
-      s.acc[2 * j] = mfma16(u32x2{a.x, a.y}, pah, s.acc[2 * j]);
-      s.acc[2 * j + 1] = mfma16(u32x2{a.z, a.w}, pah, s.acc[2 * j + 1]);
-    }
+      for (int e = 0; e < 8; ++e) t[e] *= p.scale_log2;
+      if (cm0 + cg * tq < kStepTokens) {
+        // causal edge: the column of token j sees the first cm0 + j tokens of this step
+        const int lim = cm0 + cg * tq + jcol;
+        const int va = lim - 4 * c, vb = lim - kBlock - 4 * c;
 #pragma unroll
-    for (int j = 0; j < KK; ++j) {
-      const u32x4 b = r.v[1][j];
-      s.acc[2 * j] = mfma16(u32x2{b.x, b.y}, pbh, s.acc[2 * j]);
-      s.acc[2 * j + 1] = mfma16(u32x2{b.z, b.w}, pbh, s.acc[2 * j + 1]);
-    }
+        for (int e = 0; e < 4; ++e) {
+          if (e >= va) t[e] = -INFINITY;
+          if (e >= vb) t[4 + e] = -INFINITY;
+        }
+      }
+      float mx = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])),
+                       fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(s.m[cg], mx);
+      // a column may have seen no token yet (its run starts past its causal limit): keep the
+      // exponent arguments finite, everything it contributes is zero
+      const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(s.m[cg] - m_ref);
+      s.m[cg] = m_new;
+      float psum = 0.f;
+      uint32_t ph[4], pl[4];
 #pragma unroll
-    for (int j = 0; j < KK; ++j) {
-      const u32x4 a = r.v[0][j];
-      s.acc[2 * j] = mfma16(u32x2{a.x, a.y}, pal, s.acc[2 * j]);
-      s.acc[2 * j + 1] = mfma16(u32x2{a.z, a.w}, pal, s.acc[2 * j + 1]);
-    }
+      for (int e = 0; e < 8; e += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(t[e] - m_ref);
+        const float p1 = __builtin_amdgcn_exp2f(t[e + 1] - m_ref);
+        psum += p0 + p1;
+        const float h0 = round_bf16(p0), h1 = round_bf16(p1);
+        ph[e >> 1] = pack_bf16(h0, h1);
+        pl[e >> 1] = pack_bf16(p0 - h0, p1 - h1);
+      }
+      s.l[cg] = s.l[cg] * alpha + psum;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
 #pragma unroll
-    for (int j = 0; j < KK; ++j) {
-      const u32x4 b = r.v[1][j];
-      s.acc[2 * j] = mfma16(u32x2{b.x, b.y}, pbl, s.acc[2 * j]);
-      s.acc[2 * j + 1] = mfma16(u32x2{b.z, b.w}, pbl, s.acc[2 * j + 1]);
+        for (int nt = 0; nt < NT; ++nt) s.acc[cg][nt] *= alpha;
+      }
+      const u32x2 pah = {ph[0], ph[1]}, pbh = {ph[2], ph[3]};
+      const u32x2 pal = {pl[0], pl[1]}, pbl = {pl[2], pl[3]};
+#pragma unroll
+      for (int j = 0; j < KK; ++j) {
+        const u32x4 a = r.v[0][j];
+        s.acc[cg][2 * j] = mfma16(u32x2{a.x, a.y}, pah, s.acc[cg][2 * j]);
+        s.acc[cg][2 * j + 1] = mfma16(u32x2{a.z, a.w}, pah, s.acc[cg][2 * j + 1]);
+      }
+#pragma unroll
+      for (int j = 0; j < KK; ++j) {
+        const u32x4 b = r.v[1][j];
+        s.acc[cg][2 * j] = mfma16(u32x2{b.x, b.y}, pbh, s.acc[cg][2 * j]);
+        s.acc[cg][2 * j + 1] = mfma16(u32x2{b.z, b.w}, pbh, s.acc[cg][2 * j + 1]);
+      }
+#pragma unroll
+      for (int j = 0; j < KK; ++j) {
+        const u32x4 a = r.v[0][j];
+        s.acc[cg][2 * j] = mfma16(u32x2{a.x, a.y}, pal, s.acc[cg][2 * j]);
+        s.acc[cg][2 * j + 1] = mfma16(u32x2{a.z, a.w}, pal, s.acc[cg][2 * j + 1]);
+      }
+#pragma unroll
+      for (int j = 0; j < KK; ++j) {
+        const u32x4 b = r.v[1][j];
+        s.acc[cg][2 * j] = mfma16(u32x2{b.x, b.y}, pbl, s.acc[cg][2 * j]);
+        s.acc[cg][2 * j + 1] = mfma16(u32x2{b.z, b.w}, pbl, s.acc[cg][2 * j + 1]);
+      }
     }
   }
 
-  // Record: [16 columns][D] accumulators, then 16 (max, sum) pairs.  A lane owns dims
-  // 32j + 8c .. +8 of its column: even ones in tile 2j, odd ones in tile 2j+1.
-  __device__ void finish(State& s, float* __restrict__ rec) const {
-    float l = s.l;
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-    float* mine = rec + n * D + 8 * c;
+  // Record: [16 * NCG columns][D] accumulators and as many (max, sum) pairs; column cg*16 + n.
+  // A lane owns dims 32j + 8c .. +8 of its columns: even ones in tile 2j, odd ones in 2j+1.
+  __device__ void finish(State& s, float* __restrict__ rec, float* __restrict__ ml) const {
 #pragma unroll
-    for (int j = 0; j < KK; ++j) {
-      const f32x4 e = s.acc[2 * j], o = s.acc[2 * j + 1];
-      *reinterpret_cast<f32x4*>(mine + 32 * j) = f32x4{e[0], o[0], e[1], o[1]};
-      *reinterpret_cast<f32x4*>(mine + 32 * j + 4) = f32x4{e[2], o[2], e[3], o[3]};
+    for (int cg = 0; cg < NCG; ++cg) {
+      float l = s.l[cg];
+      l += __shfl_xor(l, 16);
+      l += __shfl_xor(l, 32);
+      float* mine = rec + (cg * kCols + n) * D + 8 * c;
+#pragma unroll
+      for (int j = 0; j < KK; ++j) {
+        const f32x4 e = s.acc[cg][2 * j], o = s.acc[cg][2 * j + 1];
+        *reinterpret_cast<f32x4*>(mine + 32 * j) = f32x4{e[0], o[0], e[1], o[1]};
+        *reinterpret_cast<f32x4*>(mine + 32 * j + 4) = f32x4{e[2], o[2], e[3], o[3]};
+      }
+      if (c == 0)
+        *reinterpret_cast<float2*>(ml + 2 * (cg * kCols + n)) = make_float2(s.m[cg], l);
     }
-    if (c == 0) *reinterpret_cast<float2*>(rec + kCols * D + 2 * n) = make_float2(s.m, l);
   }
 };
 
@@ -372,7 +402,7 @@ __global__ __launch_bounds__(256) void mq_expand_kernel(
 // Merge: one wave per (query row, q head).
 template <int D>
 __global__ __launch_bounds__(256) void mq_merge_kernel(
-    Params p, int total_q, const int32_t* __restrict__ header,
+    Params p, int total_q, int ncg, const int32_t* __restrict__ header,
     const int32_t* __restrict__ tile_first, const int32_t* __restrict__ tile_steps,
     const TileInfo* __restrict__ tile_info, const int32_t* __restrict__ row_tile,
     const float2* __restrict__ pml, const float* __restrict__ pacc, float* __restrict__ out,
@@ -396,8 +426,9 @@ __global__ __launch_bounds__(256) void mq_merge_kernel(
     n = (int)(w1 - w0 + 1);
     slot0 = w0 + (int64_t)t * p.Hkv + h;
   }
-  const int col = (row - info.q_row0) * p.G + g;
-  merge_runs<D>(pml, pacc, slot0, n, kCols, col, lane, out + (size_t)w * D,
+  const int tqg = kCols / p.G, j = row - info.q_row0;  // column group j / tqg, column inside it
+  const int col = (j / tqg) * kCols + (j % tqg) * p.G + g;
+  merge_runs<D>(pml, pacc, slot0, n, kCols * ncg, col, lane, out + (size_t)w * D,
                 lse ? lse + w : nullptr);
 }
 
@@ -444,7 +475,7 @@ __global__ __launch_bounds__(256) void kv_append_multi_kernel(
 
 // Workspace map of the multi-token step (byte offsets), for `tiles` tiles at most, `total_q`
 // query rows, `slots` partial records and `desc_capacity` step descriptors.
-PrefillWorkspace map_prefill_workspace(const Params& p, int64_t tiles, int64_t total_q,
+PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, int64_t total_q,
                                        int64_t slots, int64_t desc_capacity) {
   PrefillWorkspace w;
   size_t off = 0;
@@ -460,8 +491,8 @@ PrefillWorkspace map_prefill_workspace(const Params& p, int64_t tiles, int64_t t
   w.tile_steps = take((size_t)tiles * sizeof(int32_t));
   w.tile_info = take((size_t)tiles * sizeof(TileInfo));
   w.row_tile = take((size_t)total_q * sizeof(int32_t));
-  w.partial_ml = take((size_t)slots * kCols * sizeof(float2));
-  w.partial_acc = take((size_t)slots * kCols * p.D * sizeof(float));
+  w.partial_ml = take((size_t)slots * kCols * ncg * sizeof(float2));
+  w.partial_acc = take((size_t)slots * kCols * ncg * p.D * sizeof(float));
   w.desc = take((size_t)desc_capacity * sizeof(MqDesc));
   w.total = off;
   return w;
@@ -487,11 +518,29 @@ hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_ne
   return hipGetLastError();
 }
 
-hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, int tq,
+int prefill_column_groups(const Params& p, int max_new_tokens) {
+  const int tq = kCols / p.G;
+  const int want = (max_new_tokens + tq - 1) / tq;
+  // register budget: four groups at head_dim 64, two at head_dim 128
+  const int most = p.D == 64 ? 4 : 2;
+  return want >= 4 && most >= 4 ? 4 : want >= 2 ? 2 : 1;
+}
+
+template <int D, int NBUF, int NCG>
+static void launch_mq(const Params& pk, unsigned grid, const void* q, const void* k_pool,
+                      const void* v_pool, const int32_t* header, const MqDesc* desc, float2* pml,
+                      float* pacc, hipStream_t st) {
+  hipLaunchKernelGGL((decode_kernel<MqMath<D, NBUF, NCG>>), dim3(grid), dim3(256), 0, st, pk,
+                     (const uint16_t*)q, (const uint16_t*)k_pool, (const uint16_t*)v_pool, header,
+                     desc, pml, pacc);
+}
+
+hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, int ncg,
                           int64_t tiles, int64_t steps, int64_t desc_capacity, int waves,
                           int total_q, const void* q, const void* k_pool, const void* v_pool,
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
                           float* lse, hipStream_t st) {
+  const int tq = (kCols / p.G) * ncg;  // query tokens per tile
   int32_t* header = (int32_t*)(ws + m.header);
   int32_t* pt = (int32_t*)(ws + m.pt);
   int32_t* ps = (int32_t*)(ws + m.ps);
@@ -517,21 +566,27 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
     const unsigned grid = (unsigned)(launch_waves / kWavesPerGroup);
     Params pk = p;  // the kernels read N and Q from the header the scan kernel wrote
     pk.n_steps = pk.per_wave = -1;
-    if (p.D == 128)
-      hipLaunchKernelGGL((decode_kernel<MqMath<128, 3>>), dim3(grid), dim3(256), 0, st, pk,
-                         (const uint16_t*)q, (const uint16_t*)k_pool, (const uint16_t*)v_pool,
-                         header, desc, pml, pacc);
-    else
-      hipLaunchKernelGGL((decode_kernel<MqMath<64, 2>>), dim3(grid), dim3(256), 0, st, pk,
-                         (const uint16_t*)q, (const uint16_t*)k_pool, (const uint16_t*)v_pool,
-                         header, desc, pml, pacc);
+    if (p.D == 128) {
+      if (ncg == 2)
+        launch_mq<128, 2, 2>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
+      else
+        launch_mq<128, 3, 1>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
+    } else {
+      if (ncg == 4)
+        launch_mq<64, 2, 4>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
+      else if (ncg == 2)
+        launch_mq<64, 2, 2>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
+      else
+        launch_mq<64, 2, 1>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
+    }
     const unsigned mg =
         (unsigned)(((int64_t)total_q * p.Hq + kWavesPerGroup - 1) / kWavesPerGroup);
     if (p.D == 128)
-      hipLaunchKernelGGL(mq_merge_kernel<128>, dim3(mg), dim3(256), 0, st, p, total_q, header,
-                         tile_first, tile_steps, tile_info, row_tile, pml, pacc, out, lse);
+      hipLaunchKernelGGL(mq_merge_kernel<128>, dim3(mg), dim3(256), 0, st, p, total_q, ncg,
+                         header, tile_first, tile_steps, tile_info, row_tile, pml, pacc, out,
+                         lse);
     else
-      hipLaunchKernelGGL(mq_merge_kernel<64>, dim3(mg), dim3(256), 0, st, p, total_q, header,
+      hipLaunchKernelGGL(mq_merge_kernel<64>, dim3(mg), dim3(256), 0, st, p, total_q, ncg, header,
                          tile_first, tile_steps, tile_info, row_tile, pml, pacc, out, lse);
   }
   return hipGetLastError();
