@@ -22,6 +22,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core rate
+MULTI_WORKLOADS = ("chunk15", "chunk25", "chunk28", "prefill", "admit")
 METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 
 # HBM bytes per attention-kernel launch from rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
@@ -41,12 +43,160 @@ def cpu_model() -> str:
     return "unknown"
 
 
+def bench_multi(args, dev) -> int:
+    """Multi-token step (append of n_s new tokens per stream + causal paged attention).
+
+    Algorithmic work per step: every context token's K and V read once per kv head
+    (sum L_s * kappa bytes) and 4*Hq*D flops per (query row, visible token) pair; the roofline
+    entry names whichever bound takes longer at the chip's peaks.
+    """
+    import copy
+
+    import numpy as np
+    import torch
+
+    from paper_2602_00269_amd import binding, synth
+
+    m = synth.make_multi_workload(args.workload, device=dev)
+    base = m.base
+    kv_bytes = base.kv_bytes_per_layer
+    lens64, n64 = base.context_lens.astype(np.int64), m.new_tokens.astype(np.int64)
+    pairs = int((n64 * (lens64 - n64) + n64 * (n64 + 1) // 2).sum())  # (row, visible token)
+    flops = 4 * base.num_q_heads * base.head_dim * pairs
+    copies = args.pool_copies
+    if copies is None:
+        copies = 1 if kv_bytes >= (1 << 30) else int(min(16, -(-(1 << 30) // max(1, kv_bytes))))
+    pools = [(base.k_pool[0], base.v_pool[0])]
+    for _ in range(1, copies):
+        pools.append((base.k_pool[0].clone(), base.v_pool[0].clone()))
+    sh = binding.shape_of(base, split_waves=args.split_waves)
+    bt = torch.from_numpy(base.block_tables).to(dev)
+    lens = torch.from_numpy(base.context_lens).to(dev)
+    qo = torch.from_numpy(m.q_offsets).to(dev)
+    tq = m.total_q
+    ws = torch.empty(binding.paged_prefill_workspace_bytes(sh, tq), dtype=torch.uint8, device=dev)
+    out = torch.zeros((tq, base.num_q_heads, base.head_dim), device=dev)
+
+    def step(i, events=None):
+        kp, vp = pools[i % copies]
+        binding.kv_append_multi(sh, m.k_new, m.v_new, kp, vp, bt, lens, qo)
+        binding.paged_prefill(sh, m.q, kp, vp, bt, lens, qo, base.context_lens, m.q_offsets, out,
+                              ws, events=events)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    value = kv_bytes / (ms_per_step * 1e-3) / 1e9
+
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    for a, b in evs:
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        step(i, events=evs[i])
+    torch.cuda.synchronize()
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    t_hbm, t_mfma = kv_bytes / (HBM_PEAK_GBPS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if t_mfma > t_hbm:
+        ach = flops / (kern_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4)}
+    else:
+        ach = kv_bytes / (kern_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4)}
+    roofline.update({"kernel": "decode_kernel<MqMath>", "kernel_ms": round(kern_ms, 4),
+                     "bytes_per_launch": kv_bytes, "flops_per_launch": flops, "traffic": None})
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        def bits(t):
+            return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+        qb, kp, vp = bits(m.q), bits(base.k_pool[0]), bits(base.v_pool[0])
+
+        def run(n):  # the first n streams: their tables, lengths and packed query rows
+            t = time.perf_counter()
+            oracle.paged_prefill(qb[: m.q_offsets[n]], kp, vp, base.block_tables[:n],
+                                 base.context_lens[:n], m.q_offsets[: n + 1], base.scale,
+                                 num_kv_heads=base.num_kv_heads)
+            return time.perf_counter() - t
+
+        probe_n = min(base.num_streams, 2)
+        probe_t = run(probe_n)
+        # the oracle's cost follows the (row, token) pairs, not the context bytes
+        ppairs = (n64 * (lens64 - n64) + n64 * (n64 + 1) // 2)
+        cum = np.cumsum(ppairs)
+        rate = cum[probe_n - 1] / max(probe_t, 1e-6)
+        n = int(np.searchsorted(cum, rate * args.cpu_seconds) + 1)
+        n = max(probe_n, min(base.num_streams, n))
+        secs = run(n)
+        toks = int(lens64[:n].sum())
+        cpu = {
+            "value": round(toks * base.kv_bytes_per_token / secs / 1e9, 4),
+            "unit": "GB/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"fp64 oracle multi-token attention of streams [0,{n}) of "
+                      f"{base.num_streams} ({toks} context tokens, {int(m.q_offsets[n])} query "
+                      f"rows), 1 pass in {secs:.2f} s",
+            "cpu_model": cpu_model(),
+            "host_cpus": os.cpu_count(),
+        }
+
+    print(json.dumps({
+        "metric": "multi-token step context KV GB/s (each context byte counted once)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": m.name,
+            "streams": base.num_streams,
+            "q_heads": base.num_q_heads,
+            "kv_heads": base.num_kv_heads,
+            "head_dim": base.head_dim,
+            "layers": 1,
+            "total_tokens": base.total_tokens,
+            "query_rows": tq,
+            "kv_bytes_per_step": kv_bytes,
+            "flops_per_step": flops,
+            "pool_copies": copies,
+            "split_waves": args.split_waves,
+        },
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 2),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg3",
+                    choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", *MULTI_WORKLOADS],
+                    help="cfg1..cfg5: decode step (cfg3 is the headline); the others are "
+                         "multi-token steps (detokenizer chunks, prompts, admission mix)")
     ap.add_argument("--path", default="auto", choices=["auto", "mfma", "valu"])
     ap.add_argument("--split-waves", type=int, default=0)
     ap.add_argument("--layers", type=int, default=None, help="override the preset's layer count")
@@ -79,6 +229,8 @@ def main() -> int:
         return 3
     binding.load()
     dev = torch.device("cuda:0")
+    if args.workload in MULTI_WORKLOADS:
+        return bench_multi(args, dev)
     cfg = int(args.workload[3:])
     path = {"auto": binding.PATH_AUTO, "mfma": binding.PATH_MFMA, "valu": binding.PATH_VALU}[args.path]
 

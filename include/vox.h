@@ -199,6 +199,18 @@ int vox_paged_prefill(const vox_shape_t* shape, const void* q, const void* k_poo
                       float* out, float* lse, void* workspace, size_t workspace_bytes,
                       void* hip_stream);
 
+/*
+ * Measurement aid: vox_paged_prefill that also records two caller-created hipEvent_t on
+ * hip_stream around the multi-token attention kernel (the launch that reads the KV cache).
+ * Either event may be NULL; with no query rows at all nothing is launched or recorded.
+ */
+int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const void* k_pool,
+                               const void* v_pool, const int32_t* block_tables,
+                               const int32_t* context_lens, const int32_t* q_offsets,
+                               const int32_t* context_lens_host, const int32_t* q_offsets_host,
+                               float* out, float* lse, void* workspace, size_t workspace_bytes,
+                               void* hip_stream, void* event_before, void* event_after);
+
 /* Static, never-NULL description of a return code. */
 const char* vox_strerror(int code);
 

@@ -74,6 +74,8 @@ def load() -> ctypes.CDLL:
     lib.vox_kv_append_multi.restype = ctypes.c_int
     lib.vox_paged_prefill.argtypes = [sp] + [vp] * 11 + [ctypes.c_size_t, vp]
     lib.vox_paged_prefill.restype = ctypes.c_int
+    lib.vox_paged_prefill_profiled.argtypes = [sp] + [vp] * 11 + [ctypes.c_size_t, vp, vp, vp]
+    lib.vox_paged_prefill_profiled.restype = ctypes.c_int
     lib.vox_strerror.argtypes = [ctypes.c_int]
     lib.vox_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -236,17 +238,22 @@ def kv_append_multi(shape, k_new, v_new, k_pool, v_pool, block_tables, context_l
 
 
 def paged_prefill(shape, q, k_pool, v_pool, block_tables, context_lens, q_offsets,
-                  context_lens_host, q_offsets_host, out, workspace, lse=None, stream=None):
+                  context_lens_host, q_offsets_host, out, workspace, lse=None, stream=None,
+                  events=None):
+    """``events``: optional pair of events as in ``paged_decode``."""
     bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
     keep1, lens_h = _host_lens(context_lens_host)
     keep2, qo_h = _host_lens(q_offsets_host)
-    rc = load().vox_paged_prefill(ctypes.byref(shape), _dev(q, bf, "q"),
+    ev0 = ev1 = None
+    if events is not None:
+        ev0, ev1 = (ctypes.c_void_p(e.cuda_event) for e in events)
+    rc = load().vox_paged_prefill_profiled(ctypes.byref(shape), _dev(q, bf, "q"),
                                   _dev(k_pool, bf, "k_pool"), _dev(v_pool, bf, "v_pool"),
                                   _dev(block_tables, i32, "block_tables"),
                                   _dev(context_lens, i32, "context_lens"),
                                   _dev(q_offsets, i32, "q_offsets"), lens_h, qo_h,
                                   _dev(out, f32, "out"), _dev(lse, f32, "lse", optional=True),
                                   _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
-                                  _stream(stream))
+                                  _stream(stream), ev0, ev1)
     del keep1, keep2
     _check(rc, "vox_paged_prefill")

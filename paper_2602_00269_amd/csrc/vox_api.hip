@@ -39,6 +39,7 @@ Params make_params(const vox_shape_t* s) {
   p.max_nb = s->max_blocks_per_stream;
   p.scale_log2 = s->scale * 1.44269504088896340736f;
   p.n_steps = p.per_wave = -1;
+  p.ranges_off = 0;
   return p;
 }
 
@@ -276,7 +277,7 @@ size_t vox_paged_prefill_workspace_bytes(const vox_shape_t* shape, int32_t total
   const int64_t steps = tiles * ((shape->max_blocks_per_stream + 1) / 2) * shape->num_kv_heads;
   const int64_t slots = split_waves(shape) + tiles * shape->num_kv_heads;
   const int ncg = prefill_column_groups(p, total_q);  // the widest records any call may use
-  return map_prefill_workspace(p, ncg, tiles, total_q, slots, steps).total;
+  return map_prefill_workspace(p, ncg, tiles, total_q, slots, steps, split_waves(shape)).total;
 }
 
 int vox_kv_append_multi(const vox_shape_t* shape, const void* k_new, const void* v_new,
@@ -300,6 +301,17 @@ int vox_paged_prefill(const vox_shape_t* shape, const void* q, const void* k_poo
                       const int32_t* context_lens_host, const int32_t* q_offsets_host,
                       float* out, float* lse, void* workspace, size_t workspace_bytes,
                       void* hip_stream) {
+  return vox_paged_prefill_profiled(shape, q, k_pool, v_pool, block_tables, context_lens,
+                                    q_offsets, context_lens_host, q_offsets_host, out, lse,
+                                    workspace, workspace_bytes, hip_stream, nullptr, nullptr);
+}
+
+int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const void* k_pool,
+                               const void* v_pool, const int32_t* block_tables,
+                               const int32_t* context_lens, const int32_t* q_offsets,
+                               const int32_t* context_lens_host, const int32_t* q_offsets_host,
+                               float* out, float* lse, void* workspace, size_t workspace_bytes,
+                               void* hip_stream, void* event_before, void* event_after) {
   if (int rc = validate(shape)) return rc;
   if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !q_offsets ||
       !context_lens_host || !q_offsets_host || !out || !workspace)
@@ -333,11 +345,12 @@ int vox_paged_prefill(const vox_shape_t* shape, const void* q, const void* k_poo
   if (steps > INT32_MAX || tiles * p.Hkv > INT32_MAX / 2) return VOX_ERR_SHAPE;
   const int waves = split_waves(shape);
   const int64_t slots = waves + tiles * p.Hkv;
-  const PrefillWorkspace m = map_prefill_workspace(p, ncg, tiles, total_q, slots, steps);
+  const PrefillWorkspace m = map_prefill_workspace(p, ncg, tiles, total_q, slots, steps, waves);
   if (m.total > workspace_bytes) return VOX_ERR_WORKSPACE;
   return launch_prefill(p, m, (char*)workspace, ncg, tiles, steps, steps, waves, (int)total_q, q,
                         k_pool, v_pool, block_tables, context_lens, q_offsets, out, lse,
-                        (hipStream_t)hip_stream) == hipSuccess
+                        (hipStream_t)hip_stream, (hipEvent_t)event_before,
+                        (hipEvent_t)event_after) == hipSuccess
              ? VOX_OK
              : VOX_ERR_HIP;
 }

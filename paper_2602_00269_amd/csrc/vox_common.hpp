@@ -56,8 +56,8 @@ struct Workspace {
 
 // Workspace map of the multi-token (prefill / chunk) step.
 struct PrefillWorkspace {
-  size_t header, pt, ps, tile_first, tile_steps, tile_info, row_tile, partial_ml, partial_acc,
-      desc, total;
+  size_t header, ranges, pt, ps, tile_first, tile_steps, tile_info, row_tile, partial_ml,
+      partial_acc, desc, total;
 };
 
 // Everything a kernel needs besides its buffers.
@@ -67,6 +67,9 @@ struct Params {
   // N and Q when the host knows the lengths (else -1 and the kernels read the plan's header):
   // saves every wave one dependent round trip to memory before its first descriptor load
   int32_t n_steps, per_wave;
+  // When > 0: wave w owns steps [r[w], r[w+1]) with r = header + ranges_off (int32 words), a
+  // table the plan wrote, instead of the equal ranges [w*Q, (w+1)*Q)
+  int32_t ranges_off;
 };
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -99,7 +102,7 @@ hipError_t launch_merge_append(const Params& p, const int32_t* header, const int
                                const int32_t* bt, const int32_t* lens, const void* k_new,
                                const void* v_new, void* k_pool, void* v_pool, hipStream_t st);
 PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, int64_t total_q,
-                                       int64_t slots, int64_t desc_capacity);
+                                       int64_t slots, int64_t desc_capacity, int waves);
 int prefill_column_groups(const Params& p, int max_new_tokens);
 size_t prefill_desc_bytes();
 hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_new,
@@ -110,7 +113,8 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
                           int64_t tiles, int64_t steps, int64_t desc_capacity, int waves,
                           int total_q, const void* q, const void* k_pool, const void* v_pool,
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
-                          float* lse, hipStream_t st);
+                          float* lse, hipStream_t st, hipEvent_t ev_before,
+                          hipEvent_t ev_after);
 hipError_t launch_decode_mfma(const Params& p, int waves, const void* q, const void* k_pool,
                               const void* v_pool, const int32_t* header, const int4* desc,
                               float2* partial_ml, float* partial_acc, hipStream_t st);

@@ -1,6 +1,7 @@
 // The split-K decode kernel skeleton shared by the MFMA and VALU arithmetic.
 //
-// A wave owns the global steps [w*Q, min(N, (w+1)*Q)) and walks them as one flat software
+// A wave owns the global steps [w*Q, min(N, (w+1)*Q)) (or a range from the plan's table) and
+// walks them as one flat software
 // pipeline: the K/V loads of step i + NBUF are issued while step i is computed, across segment
 // boundaries, so the load queue never drains inside a wave.  Step descriptors are wave-uniform:
 // they come in through scalar loads a few steps ahead and live in scalar registers.  When a run
@@ -10,8 +11,11 @@
 // `Math` supplies the registers and arithmetic of one step:
 //   struct Q (query rows in flight), struct Regs (one step of K/V), struct State;
 //   struct Desc (step descriptor) with static accessors ga/gb/meta/sigma; columns(params);
-//   Math(lane, params); load_q(Q&, q, desc) one step ahead; install_q(State&, Q&, q, desc);
+//   Math(lane, params); load_q(Q&, State&, q, desc): issued right after the last step of the
+//   previous run was computed (the state's own query registers are dead by then, so a Math may
+//   load straight into them and leave Q empty); install_q(State&, Q&) at the run's first step;
 //   issue(Regs&, k_pool, v_pool, ga, gb); reset(State&); compute(State&, Regs&, desc);
+//   used_columns(desc): leading record columns that carry query rows (the rest is not stored);
 //   finish(State&, float* acc, float* ml): writes the run's [columns][D] accumulators to acc
 //   and its [columns] (max, sum) pairs to ml (an LDS record, or global memory when a record
 //   does not fit the LDS buffer).
@@ -36,9 +40,11 @@ __device__ inline u32x4 kv_load(const uint16_t* p) {
 // acknowledgement is slow while the chip streams at full rate: every later load would wait
 // behind it.  Records are therefore kept in LDS ([G][D] accumulators then [G] (max, sum)
 // pairs, the same shape as a global record) and copied out when the wave has finished its
-// range, or earlier if the buffer fills up.  `cols` is the number of (query row, head) columns
-// a record holds: G for the decode step, 16 for the multi-token step.
-constexpr int kStashFloats = 4096;  // 16 KB per wave, 64 KB per workgroup
+// range, or earlier if the buffer fills up (then only when the next record needs the room, so
+// the last records of a wave always leave after its last load: stores that reach HBM while the
+// chip streams reads cost far more than their bytes).  `cols` is the number of (query row,
+// head) columns a record holds.  Each Math states the floats per wave it wants
+// (`Math::kStashFloats`; four waves share the 160 KB of a CU).
 
 struct PartialStash {
   float* mem;    // this wave's LDS area
@@ -47,20 +53,27 @@ struct PartialStash {
   int cap;       // records that fit
   int count;     // records held
   int slots;     // lane r holds the slot id of record r
+  int used;      // ... and the number of leading columns of it that carry query rows
   int lane;
 
-  __device__ PartialStash(float* mem_, int cols, int D, int lane_)
-      : mem(mem_), rec(cols * (D + 2)), gd(cols * D), cap(kStashFloats / (cols * (D + 2))),
-        count(0), slots(0), lane(lane_) {}
+  __device__ PartialStash(float* mem_, int floats, int cols, int D, int lane_)
+      : mem(mem_), rec(cols * (D + 2)), gd(cols * D), cap(floats / (cols * (D + 2))),
+        count(0), slots(0), used(0), lane(lane_) {}
 
-  // LDS area of the record being added; the caller fills [col][d] at col*D + d and the
-  // (max, sum) pair of column col at gd + 2*col, then calls commit().
-  __device__ float* next() const { return mem + count * rec; }
-
-  __device__ void commit(int slot, float2* __restrict__ pml, float* __restrict__ pacc) {
-    if (lane == count) slots = slot;
-    ++count;
+  // LDS area of the record being added (older records are stored first if the buffer is
+  // full); the caller fills [col][d] at col*D + d and the (max, sum) pair of column col at
+  // gd + 2*col, then calls commit().
+  __device__ float* next(float2* __restrict__ pml, float* __restrict__ pacc) {
     if (count == cap) flush(pml, pacc);
+    return mem + count * rec;
+  }
+
+  __device__ void commit(int slot, int used_cols) {
+    if (lane == count) {
+      slots = slot;
+      used = used_cols;
+    }
+    ++count;
   }
 
   __device__ void flush(float2* __restrict__ pml, float* __restrict__ pacc) {
@@ -69,13 +82,14 @@ struct PartialStash {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     for (int r = 0; r < count; ++r) {
       const int slot = __builtin_amdgcn_readlane(slots, r);
+      const int floats = __builtin_amdgcn_readlane(used, r) * (gd / ((rec - gd) / 2));
       const float* src = mem + r * rec;
       float* dst = pacc + (size_t)slot * gd;
-      for (int x = lane * 4; x < gd; x += kWave * 4)
+      for (int x = lane * 4; x < floats; x += kWave * 4)
         *reinterpret_cast<float4*>(dst + x) = *reinterpret_cast<const float4*>(src + x);
-      if (2 * lane < rec - gd)
-        pml[(size_t)slot * (rec - gd) / 2 + lane] =
-            *reinterpret_cast<const float2*>(src + gd + 2 * lane);
+      for (int x = lane; 2 * x < rec - gd; x += kWave)
+        pml[(size_t)slot * (rec - gd) / 2 + x] =
+            *reinterpret_cast<const float2*>(src + gd + 2 * x);
     }
     count = 0;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -94,11 +108,20 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
   constexpr int LA = NBUF + 1;  // descriptor look-ahead in steps
   const int lane = threadIdx.x & (kWave - 1);
   const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6));
-  const int N = p.n_steps >= 0 ? p.n_steps : header[kHdrSteps];
-  const int Q = p.n_steps >= 0 ? p.per_wave : header[kHdrPerWave];
-  const int64_t x0 = (int64_t)w * Q;
-  if (x0 >= N) return;
-  const int nsteps = (int)min((int64_t)Q, (int64_t)N - x0);
+  int64_t x0;
+  int nsteps;
+  if (p.ranges_off > 0) {  // ranges of unequal length, balanced by the plan
+    const int32_t* r = header + p.ranges_off;
+    x0 = r[w];
+    nsteps = r[w + 1] - r[w];
+    if (nsteps <= 0) return;
+  } else {
+    const int N = p.n_steps >= 0 ? p.n_steps : header[kHdrSteps];
+    const int Q = p.n_steps >= 0 ? p.per_wave : header[kHdrPerWave];
+    x0 = (int64_t)w * Q;
+    if (x0 >= N) return;
+    nsteps = (int)min((int64_t)Q, (int64_t)N - x0);
+  }
 
   // Descriptors are wave-uniform: they are fetched with scalar loads LA steps ahead and live in
   // scalar registers.  dq[k] is the descriptor of step i + k.
@@ -107,13 +130,13 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
 #pragma unroll
   for (int k = 0; k <= LA; ++k) dq[k] = dbase[min(k, nsteps - 1)];
 
-  __shared__ float stash_mem[kWavesPerGroup][kStashFloats];
-  PartialStash stash(stash_mem[threadIdx.x >> 6], Math::columns(p), p.D, lane);
+  __shared__ float stash_mem[kWavesPerGroup][Math::kStashFloats];
+  PartialStash stash(stash_mem[threadIdx.x >> 6], Math::kStashFloats, Math::columns(p), p.D, lane);
   Math math(lane, p);
   typename Math::State st;
   typename Math::Q qnext;
   typename Math::Regs ring[NBUF];
-  math.load_q(qnext, q, dq[0]);
+  math.load_q(qnext, st, q, dq[0]);
   math.reset(st);
 #pragma unroll
   for (int b = 0; b < NBUF; ++b) {
@@ -135,10 +158,11 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
     const int sigma = Math::sigma(dcur);                                                   \
     if (meta & kMetaFirst) {                                                               \
       math.reset(st);                                                                      \
-      math.install_q(st, qnext, q, dcur);                                                  \
+      math.install_q(st, qnext);                                                           \
     }                                                                                      \
     math.compute(st, ring[B], dcur);                                                       \
-    if (i + 1 < nsteps && (Math::meta(dq[1]) & kMetaFirst)) math.load_q(qnext, q, dq[1]);  \
+    if (i + 1 < nsteps && (Math::meta(dq[1]) & kMetaFirst))                                \
+      math.load_q(qnext, st, q, dq[1]);                                                    \
     if (REFILL) {                                                                          \
       const bool more = i + NBUF < nsteps;                                                 \
       math.template issue<true>(ring[B], k_pool, v_pool, more ? Math::ga(dq[NBUF]) : 0,    \
@@ -146,9 +170,9 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
     }                                                                                      \
     if (meta & kMetaLast) {                                                                \
       if (stash.cap > 0) {                                                                 \
-        float* rec = stash.next();                                                         \
+        float* rec = stash.next(pml, pacc);                                                \
         math.finish(st, rec, rec + stash.gd);                                              \
-        stash.commit(w + sigma, pml, pacc);                                                \
+        stash.commit(w + sigma, math.used_columns(dcur));                                  \
       } else { /* record larger than the LDS buffer: straight to global memory */          \
         const size_t slot = (size_t)(w + sigma);                                           \
         math.finish(st, pacc + slot * stash.gd,                                            \

@@ -61,6 +61,7 @@ struct MfmaMath {
   __device__ static int columns(const Params& p) { return p.G; }
 
   static constexpr int kBuffers = NBUF;
+  static constexpr int kStashFloats = 4096;  // 16 KB per wave: several decode records
   static constexpr int kMinWavesPerSimd = 1;
   static constexpr int KK = D / 32;  // score MFMAs per block = V loads per block
   static constexpr int NT = D / 16;  // output dim tiles
@@ -92,7 +93,7 @@ struct MfmaMath {
   }
 
   // Query operand of segment sigma: column n -> row sigma*G + (n mod G) for n < 2G, else zero.
-  __device__ void load_q(Q& out, const uint16_t* __restrict__ q, const Desc& dsc) const {
+  __device__ void load_q(Q& out, State&, const uint16_t* __restrict__ q, const Desc& dsc) const {
     const int sigma = dsc.w;
     const bool has = n < 2 * G;
     const int row = sigma * G + (has ? (n < G ? n : n - G) : 0);
@@ -104,9 +105,7 @@ struct MfmaMath {
     }
   }
 
-  __device__ void install_q(State& s, const Q& next, const uint16_t*, const Desc&) const {
-    s.q = next;
-  }
+  __device__ void install_q(State& s, const Q& next) const { s.q = next; }
 
   template <bool STREAM>
   __device__ void issue(Regs& r, const uint16_t* __restrict__ k_pool,
@@ -186,23 +185,19 @@ struct MfmaMath {
       pw[e >> 1] = pack_bf16(fmaf(-lo_mul, h0, p0), fmaf(-lo_mul, h1, p1));
     }
     s.l = s.l * alpha + psum;
-    const u32x2 pa = {pw[0], pw[1]}, pb = {pw[2], pw[3]};
     if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) s.acc[nt] *= alpha;
     }
-    // block A into all tiles, then block B: consecutive MFMAs never depend on each other
+    // One 32-deep MFMA per 16-dim tile covers both blocks: reduction slots 0-3 of a lane group
+    // are its four tokens of block A, slots 4-7 its four tokens of block B, for the V operand
+    // and for the probabilities alike.
+    const u32x4 pp = {pw[0], pw[1], pw[2], pw[3]};
 #pragma unroll
     for (int j = 0; j < KK; ++j) {
-      const u32x4 a = r.v[0][j];
-      s.acc[2 * j] = mfma16(u32x2{a.x, a.y}, pa, s.acc[2 * j]);
-      s.acc[2 * j + 1] = mfma16(u32x2{a.z, a.w}, pa, s.acc[2 * j + 1]);
-    }
-#pragma unroll
-    for (int j = 0; j < KK; ++j) {
-      const u32x4 b = r.v[1][j];
-      s.acc[2 * j] = mfma16(u32x2{b.x, b.y}, pb, s.acc[2 * j]);
-      s.acc[2 * j + 1] = mfma16(u32x2{b.z, b.w}, pb, s.acc[2 * j + 1]);
+      const u32x4 a = r.v[0][j], b = r.v[1][j];
+      s.acc[2 * j] = mfma32(u32x4{a.x, a.y, b.x, b.y}, pp, s.acc[2 * j]);
+      s.acc[2 * j + 1] = mfma32(u32x4{a.z, a.w, b.z, b.w}, pp, s.acc[2 * j + 1]);
     }
   }
 
@@ -210,6 +205,8 @@ struct MfmaMath {
   // their accumulators first, the hi columns [0,G) then add their own on top (lane (n,c) and
   // lane (n+G,c) address the same floats), so no register shuffles are needed.  A lane owns
   // dims 32j + 8c .. +8 of its column: even ones in tile 2j, odd ones in tile 2j+1.
+  __device__ int used_columns(const Desc&) const { return G; }
+
   __device__ void finish(State& s, float* __restrict__ rec, float* __restrict__ ml) const {
     float l = s.l;
     l += __shfl_xor(l, 16);

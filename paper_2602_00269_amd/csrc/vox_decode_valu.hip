@@ -56,6 +56,7 @@ struct ValuMath {
   __device__ static int columns(const Params& p) { return p.G; }
 
   static constexpr int kBuffers = 2;
+  static constexpr int kStashFloats = 4096;  // 16 KB per wave: several decode records
   static constexpr int kMinWavesPerSimd = 2;
   static constexpr int NL = D / 32;  // 16-byte loads per lane per granule
 
@@ -87,7 +88,7 @@ struct ValuMath {
   }
 
   // rows sigma*G .. sigma*G+G-1 of q are one contiguous run of QCHUNKS 16-byte pieces
-  __device__ void load_q(Q& out, const uint16_t* __restrict__ q, const Desc& dsc) const {
+  __device__ void load_q(Q& out, State&, const uint16_t* __restrict__ q, const Desc& dsc) const {
     const int sigma = dsc.w;
     const u32x4* src = reinterpret_cast<const u32x4*>(q + (size_t)sigma * G * D);
 #pragma unroll
@@ -97,7 +98,7 @@ struct ValuMath {
     }
   }
 
-  __device__ void install_q(State&, const Q& next, const uint16_t*, const Desc&) const {
+  __device__ void install_q(State&, const Q& next) const {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -205,6 +206,8 @@ struct ValuMath {
     block(s, r.k[0], r.v[0], min(ntok, kBlock));
     if (ntok > kBlock) block(s, r.k[1], r.v[1], ntok - kBlock);
   }
+
+  __device__ int used_columns(const Desc&) const { return G; }
 
   __device__ void finish(State& s, float* __restrict__ rec, float* __restrict__ ml) const {
     const int m = lane % (D / 2);  // dim pair owned by this lane

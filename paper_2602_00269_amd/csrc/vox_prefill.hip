@@ -20,7 +20,8 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kCols = 16;  // MFMA columns = record columns of the multi-token step
+constexpr int kCols = 16;   // MFMA columns of one column group
+constexpr int kBatch = 2;   // column groups whose stages are interleaved in one step  // MFMA columns = record columns of the multi-token step
 
 // Step descriptor of the multi-token step (32 bytes, wave-uniform).
 //   a: granule of block A, granule of block B, meta (valid tokens | first | last), segment
@@ -59,16 +60,19 @@ struct MqMath {
   __device__ static int columns(const Params&) { return kCols * NCG; }
 
   static constexpr int kBuffers = NBUF;
+  // 39 KB per wave (all four waves: 156 of the CU's 160 KB): 4, 2, 1 records at head_dim 128
+  // with 1, 2, 4 column groups; 9, 4, 2, 1 at head_dim 64 with 1, 2, 4, 8
+  static constexpr int kStashFloats = 9984;
   static constexpr int kMinWavesPerSimd = 1;
   static constexpr int KK = D / 32;
   static constexpr int NT = D / 16;
+  static constexpr int CB = NCG < kBatch ? NCG : kBatch;  // groups per batch
 
-  // With one column group the query rows of the next run are fetched a step ahead like in the
-  // decode step; with more groups they would cost too many registers and are loaded when the
-  // run starts (runs are long in that regime: a whole context per tile).
-  struct Q {
-    u32x4 b[NCG == 1 ? KK : 1];
-  };
+  // The query rows of the next run are loaded straight into the state's registers right
+  // after the last step of the previous run was computed (they are dead by then), ahead of
+  // that step's refill and of the record stores, so the first step of the new run waits for
+  // nothing younger than them.
+  struct Q {};
   struct Regs {
     u32x4 k[2][KK], v[2][KK];
   };
@@ -92,33 +96,25 @@ struct MqMath {
     v_off = c * D * 4 + n * 8;
   }
 
+  // Columns without a query row (tokens past the tile's last one, columns past tq * G) load
+  // the tile's first row instead: every column is computed independently of the others and
+  // the merge reads only the columns of real rows, so what they hold never matters.
   __device__ void load_group(u32x4 (&dst)[KK], const uint16_t* __restrict__ q, const Desc& d,
                              int cg) const {
     const int tok = cg * tq + jcol;
     const bool has = jcol < tq && tok < d.b.y;
-    const int row = (d.b.x + (has ? tok : 0)) * p.Hq + d.b.w * p.G + gcol;
+    const int row = (d.b.x + (has ? tok : 0)) * p.Hq + d.b.w * p.G + (has ? gcol : 0);
     const uint16_t* qrow = q + (size_t)row * D + c * 8;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      dst[kk] = *reinterpret_cast<const u32x4*>(qrow + 32 * kk);
-      if (!has) dst[kk] = u32x4{0, 0, 0, 0};
-    }
+    for (int kk = 0; kk < KK; ++kk) dst[kk] = *reinterpret_cast<const u32x4*>(qrow + 32 * kk);
   }
 
-  __device__ void load_q(Q& out, const uint16_t* __restrict__ q, const Desc& d) const {
-    if (NCG == 1) load_group(reinterpret_cast<u32x4(&)[KK]>(out.b), q, d, 0);
+  __device__ void load_q(Q&, State& s, const uint16_t* __restrict__ q, const Desc& d) const {
+#pragma unroll
+    for (int cg = 0; cg < NCG; ++cg) load_group(s.q[cg], q, d, cg);
   }
 
-  __device__ void install_q(State& s, const Q& next, const uint16_t* __restrict__ q,
-                            const Desc& d) const {
-    if (NCG == 1) {
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) s.q[0][kk] = next.b[NCG == 1 ? kk : 0];
-    } else {
-#pragma unroll
-      for (int cg = 0; cg < NCG; ++cg) load_group(s.q[cg], q, d, cg);
-    }
-  }
+  __device__ void install_q(State&, const Q&) const {}
 
   template <bool STREAM>
   __device__ void issue(Regs& r, const uint16_t* __restrict__ k_pool,
@@ -166,84 +162,107 @@ struct MqMath {
         r.v[1][j] &= mb;
       }
     }
+    // Column groups are taken CB at a time, stage by stage, so that the latencies of one group
+    // (dependent MFMAs, the two cross-lane maxima, the exponentials) hide behind the work of
+    // the others: a single wave per SIMD has nobody else to switch to.
 #pragma unroll
-    for (int cg = 0; cg < NCG; ++cg) {
-      f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+    for (int cg0 = 0; cg0 < NCG; cg0 += CB) {
+      if (cg0 > 0 && cg0 * tq >= d.b.y) break;  // the tile's tokens end before this batch
+      float t[CB][8];
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        sa = mfma32(r.k[0][kk], s.q[cg][kk], sa);
-        sb = mfma32(r.k[1][kk], s.q[cg][kk], sb);
-      }
-      float t[8] = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
+      for (int b = 0; b < CB; ++b) {
+        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) t[e] *= p.scale_log2;
-      if (cm0 + cg * tq < kStepTokens) {
-        // causal edge: the column of token j sees the first cm0 + j tokens of this step
-        const int lim = cm0 + cg * tq + jcol;
-        const int va = lim - 4 * c, vb = lim - kBlock - 4 * c;
+        for (int kk = 0; kk < KK; ++kk) {
+          sa = mfma32(r.k[0][kk], s.q[cg0 + b][kk], sa);
+          sb = mfma32(r.k[1][kk], s.q[cg0 + b][kk], sb);
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          if (e >= va) t[e] = -INFINITY;
-          if (e >= vb) t[4 + e] = -INFINITY;
+          t[b][e] = sa[e] * p.scale_log2;
+          t[b][4 + e] = sb[e] * p.scale_log2;
         }
       }
-      float mx = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])),
-                       fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(s.m[cg], mx);
-      // a column may have seen no token yet (its run starts past its causal limit): keep the
-      // exponent arguments finite, everything it contributes is zero
-      const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(s.m[cg] - m_ref);
-      s.m[cg] = m_new;
-      float psum = 0.f;
-      uint32_t ph[4], pl[4];
+      if (cm0 + cg0 * tq < kStepTokens) {
+        // causal edge: the column of token j sees the first cm0 + j tokens of this step
 #pragma unroll
-      for (int e = 0; e < 8; e += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(t[e] - m_ref);
-        const float p1 = __builtin_amdgcn_exp2f(t[e + 1] - m_ref);
-        psum += p0 + p1;
-        const float h0 = round_bf16(p0), h1 = round_bf16(p1);
-        ph[e >> 1] = pack_bf16(h0, h1);
-        pl[e >> 1] = pack_bf16(p0 - h0, p1 - h1);
-      }
-      s.l[cg] = s.l[cg] * alpha + psum;
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
+        for (int b = 0; b < CB; ++b) {
+          const int lim = cm0 + (cg0 + b) * tq + jcol;
+          const int va = lim - 4 * c, vb = lim - kBlock - 4 * c;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) s.acc[cg][nt] *= alpha;
+          for (int e = 0; e < 4; ++e) {
+            if (e >= va) t[b][e] = -INFINITY;
+            if (e >= vb) t[b][4 + e] = -INFINITY;
+          }
+        }
       }
-      const u32x2 pah = {ph[0], ph[1]}, pbh = {ph[2], ph[3]};
-      const u32x2 pal = {pl[0], pl[1]}, pbl = {pl[2], pl[3]};
+      float mx[CB];
+#pragma unroll
+      for (int b = 0; b < CB; ++b)
+        mx[b] = fmaxf(fmaxf(fmaxf(t[b][0], t[b][1]), fmaxf(t[b][2], t[b][3])),
+                      fmaxf(fmaxf(t[b][4], t[b][5]), fmaxf(t[b][6], t[b][7])));
+#pragma unroll
+      for (int b = 0; b < CB; ++b) mx[b] = fmaxf(mx[b], __shfl_xor(mx[b], 16));
+#pragma unroll
+      for (int b = 0; b < CB; ++b) mx[b] = fmaxf(mx[b], __shfl_xor(mx[b], 32));
+      float alpha[CB];
+      uint32_t ph[CB][4], pl[CB][4];
+      bool rescale = false;
+#pragma unroll
+      for (int b = 0; b < CB; ++b) {
+        const int cg = cg0 + b;
+        const float m_new = fmaxf(s.m[cg], mx[b]);
+        // a column may have seen no token yet (its run starts past its causal limit): keep
+        // the exponent arguments finite, everything it contributes is zero
+        const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+        alpha[b] = __builtin_amdgcn_exp2f(s.m[cg] - m_ref);
+        rescale |= alpha[b] != 1.f;
+        s.m[cg] = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(t[b][e] - m_ref);
+          const float p1 = __builtin_amdgcn_exp2f(t[b][e + 1] - m_ref);
+          psum += p0 + p1;
+          const float h0 = round_bf16(p0), h1 = round_bf16(p1);
+          ph[b][e >> 1] = pack_bf16(h0, h1);
+          pl[b][e >> 1] = pack_bf16(p0 - h0, p1 - h1);
+        }
+        s.l[cg] = s.l[cg] * alpha[b] + psum;
+      }
+      if (__builtin_amdgcn_ballot_w64(rescale)) {
+#pragma unroll
+        for (int b = 0; b < CB; ++b)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) s.acc[cg0 + b][nt] *= alpha[b];
+      }
+      // one 32-deep MFMA per 16-dim tile covers both blocks (reduction slots 0-3: the lane
+      // group's tokens of block A, 4-7: of block B), once for the hi and once for the lo part
 #pragma unroll
       for (int j = 0; j < KK; ++j) {
-        const u32x4 a = r.v[0][j];
-        s.acc[cg][2 * j] = mfma16(u32x2{a.x, a.y}, pah, s.acc[cg][2 * j]);
-        s.acc[cg][2 * j + 1] = mfma16(u32x2{a.z, a.w}, pah, s.acc[cg][2 * j + 1]);
-      }
+        const u32x4 va = r.v[0][j], vb = r.v[1][j];
+        const u32x4 even = {va.x, va.y, vb.x, vb.y}, odd = {va.z, va.w, vb.z, vb.w};
 #pragma unroll
-      for (int j = 0; j < KK; ++j) {
-        const u32x4 b = r.v[1][j];
-        s.acc[cg][2 * j] = mfma16(u32x2{b.x, b.y}, pbh, s.acc[cg][2 * j]);
-        s.acc[cg][2 * j + 1] = mfma16(u32x2{b.z, b.w}, pbh, s.acc[cg][2 * j + 1]);
-      }
+        for (int b = 0; b < CB; ++b) {
+          const u32x4 pph = {ph[b][0], ph[b][1], ph[b][2], ph[b][3]};
+          s.acc[cg0 + b][2 * j] = mfma32(even, pph, s.acc[cg0 + b][2 * j]);
+          s.acc[cg0 + b][2 * j + 1] = mfma32(odd, pph, s.acc[cg0 + b][2 * j + 1]);
+        }
 #pragma unroll
-      for (int j = 0; j < KK; ++j) {
-        const u32x4 a = r.v[0][j];
-        s.acc[cg][2 * j] = mfma16(u32x2{a.x, a.y}, pal, s.acc[cg][2 * j]);
-        s.acc[cg][2 * j + 1] = mfma16(u32x2{a.z, a.w}, pal, s.acc[cg][2 * j + 1]);
-      }
-#pragma unroll
-      for (int j = 0; j < KK; ++j) {
-        const u32x4 b = r.v[1][j];
-        s.acc[cg][2 * j] = mfma16(u32x2{b.x, b.y}, pbl, s.acc[cg][2 * j]);
-        s.acc[cg][2 * j + 1] = mfma16(u32x2{b.z, b.w}, pbl, s.acc[cg][2 * j + 1]);
+        for (int b = 0; b < CB; ++b) {
+          const u32x4 ppl = {pl[b][0], pl[b][1], pl[b][2], pl[b][3]};
+          s.acc[cg0 + b][2 * j] = mfma32(even, ppl, s.acc[cg0 + b][2 * j]);
+          s.acc[cg0 + b][2 * j + 1] = mfma32(odd, ppl, s.acc[cg0 + b][2 * j + 1]);
+        }
       }
     }
   }
 
   // Record: [16 * NCG columns][D] accumulators and as many (max, sum) pairs; column cg*16 + n.
   // A lane owns dims 32j + 8c .. +8 of its columns: even ones in tile 2j, odd ones in 2j+1.
+  // whole column groups up to the tile's last token
+  __device__ int used_columns(const Desc& d) const { return (d.b.y + tq - 1) / tq * kCols; }
+
   __device__ void finish(State& s, float* __restrict__ rec, float* __restrict__ ml) const {
 #pragma unroll
     for (int cg = 0; cg < NCG; ++cg) {
@@ -364,13 +383,71 @@ __global__ __launch_bounds__(256) void mq_tiles_kernel(
   if (t == total - 1) tile_first[total] = ps[p.S] * p.Hkv;
 }
 
+// Start of the run of segment sigma = t * Hkv + h on the global step axis.
+__device__ inline int64_t segment_first(const int32_t* tile_first, const int32_t* tile_steps,
+                                        int sigma, int Hkv) {
+  const int t = sigma / Hkv, h = sigma - t * Hkv;
+  return (int64_t)tile_first[t] + (int64_t)h * tile_steps[t];
+}
+
+// Ranges balanced by cost rather than by step count.  A run costs its steps plus a fixed
+// `run_cost` (in steps) for fetching its query rows and storing its record, which matters when
+// runs are a few steps long (tiles of a short prompt): on the cost axis segment sigma occupies
+// [first(sigma) + run_cost * sigma, ... + run_cost + steps(sigma)), overhead units first.
+// Wave w starts at the step under cost w * quota, quota = ceil(total cost / waves); cost units
+// inside an overhead zone map to the segment's first step, so a range can be empty but never
+// lies strictly inside another segment's span of ranges.
+__global__ __launch_bounds__(256) void mq_ranges_kernel(
+    Params p, int waves, int run_cost, const int32_t* __restrict__ header,
+    const int32_t* __restrict__ pt, const int32_t* __restrict__ tile_first,
+    const int32_t* __restrict__ tile_steps, int32_t* __restrict__ ranges) {
+  const int w = blockIdx.x * blockDim.x + threadIdx.x;
+  const int launched = (waves + kWavesPerGroup - 1) / kWavesPerGroup * kWavesPerGroup;
+  if (w > launched) return;  // waves past `waves` exist only to fill a workgroup: empty ranges
+  const int N = header[kHdrSteps];
+  const int segments = pt[p.S] * p.Hkv;
+  const int64_t total = (int64_t)N + (int64_t)run_cost * segments;
+  const int64_t quota = max((int64_t)1, (total + waves - 1) / waves);
+  const int64_t target = (int64_t)w * quota;
+  if (w >= waves || target >= total || segments == 0) {
+    ranges[w] = N;
+    return;
+  }
+  int a = 0, b = segments;  // largest sigma whose cost interval starts at or before target
+  while (b - a > 1) {
+    const int mid = (a + b) >> 1;
+    if (segment_first(tile_first, tile_steps, mid, p.Hkv) + (int64_t)run_cost * mid <= target)
+      a = mid;
+    else
+      b = mid;
+  }
+  const int64_t first = segment_first(tile_first, tile_steps, a, p.Hkv);
+  const int64_t into = target - (first + (int64_t)run_cost * a) - run_cost;
+  const int64_t steps = tile_steps[a / p.Hkv];
+  ranges[w] = (int)min((int64_t)N, first + min(steps, max((int64_t)0, into)));
+}
+
+// Largest w with ranges[w] <= x: the wave that owns step x (empty ranges share their start
+// with the next one, so the last of equal starts is the owner).
+__device__ inline int owner_wave(const int32_t* ranges, int waves, int64_t x) {
+  int a = 0, b = waves;
+  while (b - a > 1) {
+    const int mid = (a + b) >> 1;
+    if (ranges[mid] <= x)
+      a = mid;
+    else
+      b = mid;
+  }
+  return a;
+}
+
 __global__ __launch_bounds__(256) void mq_expand_kernel(
     Params p, const int32_t* __restrict__ bt, const int32_t* __restrict__ header,
     const int32_t* __restrict__ pt, const int32_t* __restrict__ tile_first,
     const int32_t* __restrict__ tile_steps, const TileInfo* __restrict__ tile_info,
-    MqDesc* __restrict__ desc) {
+    const int32_t* __restrict__ ranges, int waves, MqDesc* __restrict__ desc) {
   const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int N = header[kHdrSteps], Q = header[kHdrPerWave];
+  const int N = header[kHdrSteps];
   if (x >= N) return;
   int a = 0, b = pt[p.S];  // largest t with tile_first[t] <= x
   while (b - a > 1) {
@@ -390,8 +467,9 @@ __global__ __launch_bounds__(256) void mq_expand_kernel(
   const int ida = row[2 * st];
   const int idb = (2 * st + 1 < nb) ? row[2 * st + 1] : ida;
   int meta = min(kStepTokens, ctx - kStepTokens * st);
-  if (st == 0 || x % Q == 0) meta |= kMetaFirst;
-  if (st == f - 1 || x % Q == Q - 1 || x == N - 1) meta |= kMetaLast;
+  const int w = owner_wave(ranges, waves, x);
+  if (st == 0 || x == ranges[w]) meta |= kMetaFirst;
+  if (st == f - 1 || x == ranges[w + 1] - 1) meta |= kMetaLast;
   MqDesc d;
   d.a = make_int4(ida * p.Hkv + h, idb * p.Hkv + h, meta, t * p.Hkv + h);
   d.b = make_int4(info.q_row0, info.nq, info.pos0 + 1 - kStepTokens * st, h);
@@ -403,7 +481,7 @@ __global__ __launch_bounds__(256) void mq_expand_kernel(
 template <int D>
 __global__ __launch_bounds__(256) void mq_merge_kernel(
     Params p, int total_q, int ncg, const int32_t* __restrict__ header,
-    const int32_t* __restrict__ tile_first, const int32_t* __restrict__ tile_steps,
+    const int32_t* __restrict__ ranges, int waves, const int32_t* __restrict__ tile_first, const int32_t* __restrict__ tile_steps,
     const TileInfo* __restrict__ tile_info, const int32_t* __restrict__ row_tile,
     const float2* __restrict__ pml, const float* __restrict__ pacc, float* __restrict__ out,
     float* __restrict__ lse) {
@@ -414,7 +492,6 @@ __global__ __launch_bounds__(256) void mq_merge_kernel(
   const int h = i / p.G, g = i % p.G;
   const int t = row_tile[row];
   const TileInfo info = tile_info[t];
-  const int Q = header[kHdrPerWave];
   const int64_t N = header[kHdrSteps];
   const int f = tile_steps[t];
   const int64_t first = (int64_t)tile_first[t] + (int64_t)h * f;
@@ -422,7 +499,7 @@ __global__ __launch_bounds__(256) void mq_merge_kernel(
   int64_t slot0 = 0;
   if (first < N) {
     const int64_t last = min(N, first + f) - 1;
-    const int64_t w0 = first / Q, w1 = last / Q;
+    const int64_t w0 = owner_wave(ranges, waves, first), w1 = owner_wave(ranges, waves, last);
     n = (int)(w1 - w0 + 1);
     slot0 = w0 + (int64_t)t * p.Hkv + h;
   }
@@ -476,7 +553,7 @@ __global__ __launch_bounds__(256) void kv_append_multi_kernel(
 // Workspace map of the multi-token step (byte offsets), for `tiles` tiles at most, `total_q`
 // query rows, `slots` partial records and `desc_capacity` step descriptors.
 PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, int64_t total_q,
-                                       int64_t slots, int64_t desc_capacity) {
+                                       int64_t slots, int64_t desc_capacity, int waves) {
   PrefillWorkspace w;
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -485,6 +562,8 @@ PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, 
     return at;
   };
   w.header = take(64 * sizeof(int32_t));
+  // one entry per launched wave (whole workgroups) plus the end
+  w.ranges = take(((size_t)waves + kWavesPerGroup + 1) * sizeof(int32_t));
   w.pt = take(((size_t)p.S + 1) * sizeof(int32_t));
   w.ps = take(((size_t)p.S + 1) * sizeof(int32_t));
   w.tile_first = take(((size_t)tiles + 1) * sizeof(int32_t));
@@ -520,10 +599,16 @@ hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_ne
 
 int prefill_column_groups(const Params& p, int max_new_tokens) {
   const int tq = kCols / p.G;
-  const int want = (max_new_tokens + tq - 1) / tq;
-  // register budget: four groups at head_dim 64, two at head_dim 128
-  const int most = p.D == 64 ? 4 : 2;
-  return want >= 4 && most >= 4 ? 4 : want >= 2 ? 2 : 1;
+  const int want = (max_new_tokens + tq - 1) / tq;  // groups the longest stream fills
+  // register budget: eight groups at head_dim 64, four at head_dim 128
+  const int most = p.D == 64 ? 8 : 4;
+  // fewest tiles first (each tile streams the context again), then the smallest kernel that
+  // holds a tile: 15 tokens of 5 per group take one tile of four groups, not two of two
+  const int tiles = (want + most - 1) / most;
+  const int per_tile = tiles > 0 ? (want + tiles - 1) / tiles : 1;
+  int ncg = 1;
+  while (ncg < per_tile) ncg *= 2;
+  return ncg;
 }
 
 template <int D, int NBUF, int NCG>
@@ -539,7 +624,7 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
                           int64_t tiles, int64_t steps, int64_t desc_capacity, int waves,
                           int total_q, const void* q, const void* k_pool, const void* v_pool,
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
-                          float* lse, hipStream_t st) {
+                          float* lse, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
   const int tq = (kCols / p.G) * ncg;  // query tokens per tile
   int32_t* header = (int32_t*)(ws + m.header);
   int32_t* pt = (int32_t*)(ws + m.pt);
@@ -551,6 +636,10 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
   float2* pml = (float2*)(ws + m.partial_ml);
   float* pacc = (float*)(ws + m.partial_acc);
   MqDesc* desc = (MqDesc*)(ws + m.desc);
+  int32_t* ranges = (int32_t*)(ws + m.ranges);
+  // measured: a run boundary (query rows of the next run, record of the finished one) costs
+  // about as much as four to six steps of a wave
+  const int run_cost = 4;
 
   hipLaunchKernelGGL(mq_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, p, tq, lens, qo, waves,
                      desc_capacity, header, pt, ps);
@@ -558,36 +647,43 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
     hipLaunchKernelGGL(mq_tiles_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, st,
                        p, tq, lens, qo, header, pt, ps, tile_first, tile_steps, tile_info,
                        row_tile);
+    hipLaunchKernelGGL(mq_ranges_kernel, dim3((unsigned)((waves + kWavesPerGroup) / 256 + 1)), dim3(256), 0,
+                       st, p, waves, run_cost, header, pt, tile_first, tile_steps, ranges);
     hipLaunchKernelGGL(mq_expand_kernel, dim3((unsigned)((steps + 255) / 256)), dim3(256), 0, st,
-                       p, bt, header, pt, tile_first, tile_steps, tile_info, desc);
-    int launch_waves = waves;
-    if (steps < launch_waves)
-      launch_waves = (int)((steps + kWavesPerGroup - 1) / kWavesPerGroup * kWavesPerGroup);
-    const unsigned grid = (unsigned)(launch_waves / kWavesPerGroup);
-    Params pk = p;  // the kernels read N and Q from the header the scan kernel wrote
+                       p, bt, header, pt, tile_first, tile_steps, tile_info, ranges, waves, desc);
+    const unsigned grid = (unsigned)((waves + kWavesPerGroup - 1) / kWavesPerGroup);
+    Params pk = p;  // every wave reads its range from the table the plan wrote
     pk.n_steps = pk.per_wave = -1;
+    pk.ranges_off = (int32_t)((m.ranges - m.header) / sizeof(int32_t));
+    if (ev_before) (void)hipEventRecord(ev_before, st);
     if (p.D == 128) {
-      if (ncg == 2)
+      if (ncg == 4)
+        launch_mq<128, 2, 4>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
+      else if (ncg == 2)
         launch_mq<128, 2, 2>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
       else
         launch_mq<128, 3, 1>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
     } else {
-      if (ncg == 4)
+      if (ncg == 8)
+        launch_mq<64, 2, 8>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
+      else if (ncg == 4)
         launch_mq<64, 2, 4>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
       else if (ncg == 2)
         launch_mq<64, 2, 2>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
       else
         launch_mq<64, 2, 1>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
     }
+    if (ev_after) (void)hipEventRecord(ev_after, st);
     const unsigned mg =
         (unsigned)(((int64_t)total_q * p.Hq + kWavesPerGroup - 1) / kWavesPerGroup);
     if (p.D == 128)
       hipLaunchKernelGGL(mq_merge_kernel<128>, dim3(mg), dim3(256), 0, st, p, total_q, ncg,
-                         header, tile_first, tile_steps, tile_info, row_tile, pml, pacc, out,
-                         lse);
+                         header, ranges, waves, tile_first, tile_steps, tile_info, row_tile, pml,
+                         pacc, out, lse);
     else
       hipLaunchKernelGGL(mq_merge_kernel<64>, dim3(mg), dim3(256), 0, st, p, total_q, ncg, header,
-                         tile_first, tile_steps, tile_info, row_tile, pml, pacc, out, lse);
+                         ranges, waves, tile_first, tile_steps, tile_info, row_tile, pml, pacc,
+                         out, lse);
   }
   return hipGetLastError();
 }

@@ -212,3 +212,84 @@ def make_custom(lens, num_q_heads: int, num_kv_heads: int, head_dim: int, seed: 
     w.k_pool.append(_fill_pool(p, num_kv_heads, BLOCK * head_dim, None, unused, gen, dev))
     w.v_pool.append(_fill_pool(p, num_kv_heads, BLOCK * head_dim, None, unused, gen, dev))
     return w
+
+
+# ----------------------------------------------------------------------------------------------
+# Multi-token steps: stream s brings n_s new tokens (a prompt, an admission chunk, a chunk of a
+# stateful detokenizer whose self-attention cache lives in the same paged pools).  The paper
+# fixes chunk sizes per model (Appendix A: 15, 25 and 28 tokens) and describes prompts only as
+# text / reference-audio prompts of its request traces (Section 4.1); lengths below stand in.
+
+@dataclass
+class MultiWorkload:
+    """Inputs of one multi-token step; ``base.context_lens`` already counts the new tokens."""
+
+    name: str
+    base: Workload
+    new_tokens: np.ndarray  # int32 [S]
+    q_offsets: np.ndarray   # int32 [S+1], exclusive prefix sums of new_tokens
+    q: torch.Tensor         # [total_q, Hq, D] bf16
+    k_new: torch.Tensor     # [total_q, Hkv, D] bf16
+    v_new: torch.Tensor
+
+    @property
+    def total_q(self) -> int:
+        return int(self.q_offsets[-1])
+
+
+# name -> streams, q heads, kv heads, head dim
+_MULTI_PRESETS = {
+    "chunk15": ("chunk15_256x24q8kv128", 256, 24, 8, 128),
+    "chunk25": ("chunk25_256x24q8kv128", 256, 24, 8, 128),
+    "chunk28": ("chunk28_1024x14q2kv64", 1024, 14, 2, 64),
+    "prefill": ("prefill_32x24q8kv128", 32, 24, 8, 128),
+    "admit": ("admit_512x24q8kv128", 512, 24, 8, 128),
+}
+MULTI_NAMES = tuple(_MULTI_PRESETS)
+
+
+def draw_multi_lens(kind: str, num_streams: int, rng: np.random.Generator):
+    """(context lengths including the new tokens, new tokens per stream)."""
+    s = num_streams
+    if kind in ("chunk15", "chunk25"):  # detokenizer chunk on top of a cache of earlier chunks
+        n = np.full(s, int(kind[5:]), dtype=np.int64)
+        lens = np.maximum(rng.integers(500, 4001, size=s), n)
+    elif kind == "chunk28":
+        n = np.full(s, 28, dtype=np.int64)
+        lens = np.maximum(rng.integers(64, 4097, size=s), n)
+    elif kind == "prefill":  # whole prompts into empty caches
+        lens = rng.integers(64, 513, size=s)
+        n = lens.copy()
+    elif kind == "admit":  # steady-state streams decode one token, one in ten is a new prompt
+        lens = np.clip(np.rint(np.exp(math.log(1000.0) + 0.8 * rng.standard_normal(s))), 1, 8192)
+        lens = lens.astype(np.int64)
+        n = np.ones(s, dtype=np.int64)
+        fresh = rng.permutation(s)[: max(1, s // 10)]
+        lens[fresh] = rng.integers(32, 257, size=fresh.size)
+        n[fresh] = lens[fresh]
+    else:
+        raise ValueError(f"unknown multi-token workload {kind!r}")
+    return lens.astype(np.int32), n.astype(np.int32)
+
+
+def make_multi_workload(kind: str, seed: Optional[int] = None, device="cpu",
+                        num_streams: Optional[int] = None) -> MultiWorkload:
+    name, s, hq, hkv, d = _MULTI_PRESETS[kind]
+    if num_streams is not None:
+        s = num_streams
+    seed = SEED_BASE + 0x100 + MULTI_NAMES.index(kind) if seed is None else seed
+    rng = np.random.default_rng(seed)
+    lens, n = draw_multi_lens(kind, s, rng)
+    base = make_custom(lens, hq, hkv, d, seed=seed, device=device,
+                       slack_blocks=max(3, int(0.25 * ((lens.astype(np.int64) + 15) // 16).sum())))
+    base.name = name
+    qo = np.zeros(s + 1, dtype=np.int32)
+    qo[1:] = np.cumsum(n)
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed + 1)
+    tq = int(qo[-1])
+    return MultiWorkload(name=name, base=base, new_tokens=n, q_offsets=qo,
+                         q=_randn_bf16((tq, hq, d), gen, dev),
+                         k_new=_randn_bf16((tq, hkv, d), gen, dev),
+                         v_new=_randn_bf16((tq, hkv, d), gen, dev))

@@ -442,6 +442,12 @@ PREFILL_CASES = [
     ([700, 1500, 90], [28, 25, 15], 14, 2, 64),                    # detokenizer-style chunks, G = 7
     ([2000, 40], [500, 40], 8, 8, 128),                            # long prompt, G = 1
     ([129, 4097], [129, 2], 8, 1, 128),                            # G = 8
+    # the number of 16-column groups per tile follows the largest n_s: 1, 2, 4 (8 at D = 64)
+    ([100, 260, 31], [7, 10, 3], 24, 8, 128),                      # two groups, D = 128
+    ([100, 260, 31], [5, 2, 0], 24, 8, 128),                       # one group, D = 128
+    ([50, 90, 400], [4, 3, 1], 8, 2, 64),                          # one group, D = 64
+    ([50, 90, 400], [8, 5, 1], 8, 2, 64),                          # two groups, D = 64
+    ([50, 90, 400], [16, 13, 2], 8, 2, 64),                        # four groups, D = 64
 ]
 
 
