@@ -83,6 +83,13 @@ def bench_multi(args, dev) -> int:
         binding.paged_prefill(sh, m.q, kp, vp, bt, lens, qo, base.context_lens, m.q_offsets, out,
                               ws, events=events)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()

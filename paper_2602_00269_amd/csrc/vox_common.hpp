@@ -56,8 +56,8 @@ struct Workspace {
 
 // Workspace map of the multi-token (prefill / chunk) step.
 struct PrefillWorkspace {
-  size_t header, ranges, pt, ps, tile_first, tile_steps, tile_info, row_tile, partial_ml,
-      partial_acc, desc, total;
+  size_t header, ranges, pt, ps, tile_first, tile_steps, tile_info, seg_runs, row_tile,
+      partial_ml, partial_acc, desc, total;
 };
 
 // Everything a kernel needs besides its buffers.

@@ -445,7 +445,8 @@ __global__ __launch_bounds__(256) void mq_expand_kernel(
     Params p, const int32_t* __restrict__ bt, const int32_t* __restrict__ header,
     const int32_t* __restrict__ pt, const int32_t* __restrict__ tile_first,
     const int32_t* __restrict__ tile_steps, const TileInfo* __restrict__ tile_info,
-    const int32_t* __restrict__ ranges, int waves, MqDesc* __restrict__ desc) {
+    const int32_t* __restrict__ ranges, int waves, MqDesc* __restrict__ desc,
+    int2* __restrict__ seg_runs) {
   const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int N = header[kHdrSteps];
   if (x >= N) return;
@@ -474,14 +475,17 @@ __global__ __launch_bounds__(256) void mq_expand_kernel(
   d.a = make_int4(ida * p.Hkv + h, idb * p.Hkv + h, meta, t * p.Hkv + h);
   d.b = make_int4(info.q_row0, info.nq, info.pos0 + 1 - kStepTokens * st, h);
   desc[x] = d;
+  if (st == 0) {  // the segment's runs: waves w .. owner of its last step, slots w + sigma ..
+    const int w1 = owner_wave(ranges, waves, min((int64_t)N, x + f) - 1);
+    seg_runs[t * p.Hkv + h] = make_int2(w + t * p.Hkv + h, w1 - w + 1);
+  }
 }
 
 // ---------------------------------------------------------------------------------------
 // Merge: one wave per (query row, q head).
 template <int D>
 __global__ __launch_bounds__(256) void mq_merge_kernel(
-    Params p, int total_q, int ncg, const int32_t* __restrict__ header,
-    const int32_t* __restrict__ ranges, int waves, const int32_t* __restrict__ tile_first, const int32_t* __restrict__ tile_steps,
+    Params p, int total_q, int ncg, const int2* __restrict__ seg_runs,
     const TileInfo* __restrict__ tile_info, const int32_t* __restrict__ row_tile,
     const float2* __restrict__ pml, const float* __restrict__ pacc, float* __restrict__ out,
     float* __restrict__ lse) {
@@ -491,27 +495,16 @@ __global__ __launch_bounds__(256) void mq_merge_kernel(
   const int row = w / p.Hq, i = w % p.Hq;
   const int h = i / p.G, g = i % p.G;
   const int t = row_tile[row];
-  const TileInfo info = tile_info[t];
-  const int64_t N = header[kHdrSteps];
-  const int f = tile_steps[t];
-  const int64_t first = (int64_t)tile_first[t] + (int64_t)h * f;
-  int n = 0;
-  int64_t slot0 = 0;
-  if (first < N) {
-    const int64_t last = min(N, first + f) - 1;
-    const int64_t w0 = owner_wave(ranges, waves, first), w1 = owner_wave(ranges, waves, last);
-    n = (int)(w1 - w0 + 1);
-    slot0 = w0 + (int64_t)t * p.Hkv + h;
-  }
-  const int tqg = kCols / p.G, j = row - info.q_row0;  // column group j / tqg, column inside it
+  const int q_row0 = tile_info[t].q_row0;
+  const int2 runs = seg_runs[t * p.Hkv + h];  // first slot, number of runs (every tile has steps)
+  const int tqg = kCols / p.G, j = row - q_row0;  // column group j / tqg, column inside it
   const int col = (j / tqg) * kCols + (j % tqg) * p.G + g;
-  merge_runs<D>(pml, pacc, slot0, n, kCols * ncg, col, lane, out + (size_t)w * D,
+  merge_runs<D>(pml, pacc, runs.x, runs.y, kCols * ncg, col, lane, out + (size_t)w * D,
                 lse ? lse + w : nullptr);
 }
 
 // ---------------------------------------------------------------------------------------
-// Multi-token append: one wave per (new row, kv head).  Rows of one stream may share a 4-token
-// V quad, so the V slots are stored as 2-byte writes (no read-modify-write of shared bytes).
+// Multi-token append: one wave per (new row, kv head).
 template <int D>
 __global__ __launch_bounds__(256) void kv_append_multi_kernel(
     Params p, int total_q, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
@@ -521,13 +514,15 @@ __global__ __launch_bounds__(256) void kv_append_multi_kernel(
   const int w = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
   if (w >= total_q * p.Hkv) return;
   const int row = w / p.Hkv, h = w % p.Hkv;
-  int a = 0, b = p.S;  // largest s with qo[s] <= row
+  // largest s with qo[s] <= row, found by the whole wave: 64 probes per round trip to memory
+  int a = 0, b = p.S;
   while (b - a > 1) {
-    const int mid = (a + b) >> 1;
-    if (qo[mid] <= row)
-      a = mid;
-    else
-      b = mid;
+    const int step = (b - a + kWave - 1) / kWave;
+    const int idx = a + lane * step;
+    const bool le = idx < b && qo[idx] <= row;
+    const int hits = __builtin_popcountll(__builtin_amdgcn_ballot_w64(le));  // lane 0 always hits
+    a += (hits - 1) * step;
+    b = min(b, a + step);
   }
   const int s = a;
   const int n = qo[s + 1] - qo[s];
@@ -541,7 +536,27 @@ __global__ __launch_bounds__(256) void kv_append_multi_kernel(
   if (lane < D / 8)
     *reinterpret_cast<u32x4*>(k_pool + g + k_elem(t, lane * 8)) =
         *reinterpret_cast<const u32x4*>(krow + lane * 8);
-  if (lane < D / 2) {
+  // V keeps four tokens of a dim together.  The row at the start of a quad whose other three
+  // tokens are new as well writes the whole quad, 16 bytes (two dims) per lane, from the four
+  // rows; the other three rows of such a quad skip V.  Quads that also hold older tokens, or
+  // end past the stream's last token, are written one 2-byte element at a time, so bytes of
+  // tokens that are not being appended are never touched.
+  const int j = row - qo[s];             // index among the stream's new tokens
+  const int q0 = j - (t & 3);            // index of the quad's first token (may be < 0)
+  const bool full_quad = q0 >= 0 && q0 + 3 < n;
+  if (full_quad) {
+    if ((t & 3) == 0 && lane < D / 2) {
+      const size_t stride = (size_t)p.Hkv * D;  // next new row of the same kv head
+      uint32_t x[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        x[k] = *reinterpret_cast<const uint32_t*>(vrow + k * stride + 2 * lane);
+      // dims 2*lane and 2*lane+1, tokens t..t+3 each: eight consecutive elements
+      const u32x4 out = {(x[0] & 0xFFFFu) | (x[1] << 16), (x[2] & 0xFFFFu) | (x[3] << 16),
+                         (x[0] >> 16) | (x[1] & 0xFFFF0000u), (x[2] >> 16) | (x[3] & 0xFFFF0000u)};
+      *reinterpret_cast<u32x4*>(v_pool + g + v_elem(t, 2 * lane, D)) = out;
+    }
+  } else if (lane < D / 2) {
     const uint32_t two = *reinterpret_cast<const uint32_t*>(vrow + 2 * lane);
     v_pool[g + v_elem(t, 2 * lane, D)] = (uint16_t)(two & 0xFFFFu);
     v_pool[g + v_elem(t, 2 * lane + 1, D)] = (uint16_t)(two >> 16);
@@ -569,6 +584,7 @@ PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, 
   w.tile_first = take(((size_t)tiles + 1) * sizeof(int32_t));
   w.tile_steps = take((size_t)tiles * sizeof(int32_t));
   w.tile_info = take((size_t)tiles * sizeof(TileInfo));
+  w.seg_runs = take((size_t)tiles * p.Hkv * sizeof(int2));
   w.row_tile = take((size_t)total_q * sizeof(int32_t));
   w.partial_ml = take((size_t)slots * kCols * ncg * sizeof(float2));
   w.partial_acc = take((size_t)slots * kCols * ncg * p.D * sizeof(float));
@@ -636,6 +652,7 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
   float2* pml = (float2*)(ws + m.partial_ml);
   float* pacc = (float*)(ws + m.partial_acc);
   MqDesc* desc = (MqDesc*)(ws + m.desc);
+  int2* seg_runs = (int2*)(ws + m.seg_runs);
   int32_t* ranges = (int32_t*)(ws + m.ranges);
   // measured: a run boundary (query rows of the next run, record of the finished one) costs
   // about as much as four to six steps of a wave
@@ -650,7 +667,8 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
     hipLaunchKernelGGL(mq_ranges_kernel, dim3((unsigned)((waves + kWavesPerGroup) / 256 + 1)), dim3(256), 0,
                        st, p, waves, run_cost, header, pt, tile_first, tile_steps, ranges);
     hipLaunchKernelGGL(mq_expand_kernel, dim3((unsigned)((steps + 255) / 256)), dim3(256), 0, st,
-                       p, bt, header, pt, tile_first, tile_steps, tile_info, ranges, waves, desc);
+                       p, bt, header, pt, tile_first, tile_steps, tile_info, ranges, waves, desc,
+                       seg_runs);
     const unsigned grid = (unsigned)((waves + kWavesPerGroup - 1) / kWavesPerGroup);
     Params pk = p;  // every wave reads its range from the table the plan wrote
     pk.n_steps = pk.per_wave = -1;
@@ -678,12 +696,10 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
         (unsigned)(((int64_t)total_q * p.Hq + kWavesPerGroup - 1) / kWavesPerGroup);
     if (p.D == 128)
       hipLaunchKernelGGL(mq_merge_kernel<128>, dim3(mg), dim3(256), 0, st, p, total_q, ncg,
-                         header, ranges, waves, tile_first, tile_steps, tile_info, row_tile, pml,
-                         pacc, out, lse);
+                         seg_runs, tile_info, row_tile, pml, pacc, out, lse);
     else
-      hipLaunchKernelGGL(mq_merge_kernel<64>, dim3(mg), dim3(256), 0, st, p, total_q, ncg, header,
-                         ranges, waves, tile_first, tile_steps, tile_info, row_tile, pml, pacc,
-                         out, lse);
+      hipLaunchKernelGGL(mq_merge_kernel<64>, dim3(mg), dim3(256), 0, st, p, total_q, ncg,
+                         seg_runs, tile_info, row_tile, pml, pacc, out, lse);
   }
   return hipGetLastError();
 }
