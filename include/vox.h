@@ -184,6 +184,7 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
  *   q_offsets         : int32 [S+1] device, q_offsets[0] == 0
  *   context_lens_host, q_offsets_host : HOST copies, both required (the scheduler that admits
  *                       a prompt knows its length); sizes of the launches come from them
+ * With no query rows at all (total_q == 0) both calls return VOX_OK and touch nothing.
  * vox_paged_prefill_workspace_bytes(shape, total_q) is enough for any lengths the shape
  * admits; a smaller workspace is accepted when the actual step count fits.
  */

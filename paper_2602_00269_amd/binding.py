@@ -106,7 +106,7 @@ def _dev(t: Optional[torch.Tensor], dtype, what: str, optional=False):
         raise TypeError(f"{what} is required")
     if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
         raise TypeError(f"{what} must be a contiguous CUDA tensor of dtype {dtype}")
-    return ctypes.c_void_p(t.data_ptr())
+    return ctypes.c_void_p(t.data_ptr())  # NULL for an empty tensor
 
 
 def _host_lens(a):

@@ -286,6 +286,7 @@ int vox_kv_append_multi(const vox_shape_t* shape, const void* k_new, const void*
                         void* hip_stream) {
   if (int rc = validate(shape)) return rc;
   if (total_q < 0) return VOX_ERR_ARG;
+  if (total_q == 0) return VOX_OK;  // no rows: the row arrays may be empty (NULL)
   if (!k_new || !v_new || !k_pool || !v_pool || !block_tables || !context_lens || !q_offsets)
     return VOX_ERR_NULL;
   const Params p = make_params(shape);
@@ -313,8 +314,11 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
                                float* out, float* lse, void* workspace, size_t workspace_bytes,
                                void* hip_stream, void* event_before, void* event_after) {
   if (int rc = validate(shape)) return rc;
-  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !q_offsets ||
-      !context_lens_host || !q_offsets_host || !out || !workspace)
+  if (!context_lens_host || !q_offsets_host) return VOX_ERR_NULL;
+  if (q_offsets_host[shape->num_streams] == 0 && q_offsets_host[0] == 0)
+    return VOX_OK;  // no query rows: nothing to compute, the row arrays may be empty (NULL)
+  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !q_offsets || !out ||
+      !workspace)
     return VOX_ERR_NULL;
   if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
   const Params p = make_params(shape);

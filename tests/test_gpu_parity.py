@@ -496,3 +496,23 @@ def test_prefill_with_one_token_per_stream_equals_decode(dev):
                          context_lens_host=w.context_lens)
     torch.cuda.synchronize()
     assert (out - out_d).abs().max().item() <= 1e-5
+
+
+def test_multi_token_step_with_no_rows_is_a_no_op(dev):
+    w = synth.make_custom([40, 7], 8, 2, 64, seed=95, device=dev)
+    sh = binding.shape_of(w)
+    bt, lens_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev)
+    qo = np.zeros(3, dtype=np.int32)
+    kp0, vp0 = _host_pools(w)
+    empty_kv = torch.empty((0, 2, 64), dtype=torch.bfloat16, device=dev)
+    binding.kv_append_multi(sh, empty_kv, empty_kv, w.k_pool[0], w.v_pool[0], bt, lens_d,
+                            _i32(qo, dev))
+    q = torch.empty((0, 8, 64), dtype=torch.bfloat16, device=dev)
+    out = torch.empty((0, 8, 64), device=dev)
+    ws = torch.empty(binding.paged_prefill_workspace_bytes(sh, 0), dtype=torch.uint8, device=dev)
+    binding.paged_prefill(sh, q, w.k_pool[0], w.v_pool[0], bt, lens_d, _i32(qo, dev),
+                          w.context_lens, qo, out, ws)
+    torch.cuda.synchronize()
+    kp, vp = _host_pools(w)
+    assert np.array_equal(kp.view(np.uint16), kp0.view(np.uint16))
+    assert np.array_equal(vp.view(np.uint16), vp0.view(np.uint16))

@@ -29,7 +29,9 @@ def _declared():
 def test_every_declared_symbol_is_exported(lib):
     names = _declared()
     assert {"vox_kv_append", "vox_kv_gather", "vox_paged_decode", "vox_decode_step",
-            "vox_paged_decode_workspace_bytes", "vox_paged_decode_profiled", "vox_strerror"} <= set(names)
+            "vox_paged_decode_workspace_bytes", "vox_paged_decode_profiled", "vox_strerror",
+            "vox_kv_append_multi", "vox_paged_prefill", "vox_paged_prefill_profiled",
+            "vox_paged_prefill_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -81,6 +83,37 @@ def test_null_pointers_and_bad_scalars(lib):
     # misaligned workspace
     assert lib.vox_paged_decode(ctypes.byref(sh), one, one, one, one, one, None, one, None,
                                 ctypes.c_void_p(257), 1 << 20, None) == -5
+
+
+def test_multi_token_calls_validate_on_the_host(lib):
+    sh = _shape()
+    one = ctypes.c_void_p(256)
+    i32 = ctypes.c_int32
+    lens = (i32 * 4)(40, 7, 0, 3)
+    zeros = (i32 * 5)(0, 0, 0, 0, 0)
+    # no rows: accepted with empty (NULL) row arrays, nothing is launched
+    assert lib.vox_kv_append_multi(ctypes.byref(sh), None, None, one, one, one, one, one, 0,
+                                   None) == 0
+    assert lib.vox_paged_prefill(ctypes.byref(sh), None, one, one, one, one, one, lens, zeros,
+                                 None, None, one, 1 << 20, None) == 0
+    assert lib.vox_kv_append_multi(ctypes.byref(sh), one, one, one, one, one, one, one, -1,
+                                   None) == -5
+    # host copies are required
+    assert lib.vox_paged_prefill(ctypes.byref(sh), one, one, one, one, one, one, None, zeros,
+                                 one, None, one, 1 << 20, None) == -1
+    # more new tokens than the stream holds, offsets that do not start at zero
+    bad = (i32 * 5)(0, 41, 41, 41, 41)
+    assert lib.vox_paged_prefill(ctypes.byref(sh), one, one, one, one, one, one, lens, bad, one,
+                                 None, one, 1 << 20, None) == -5
+    shifted = (i32 * 5)(1, 2, 2, 2, 2)
+    assert lib.vox_paged_prefill(ctypes.byref(sh), one, one, one, one, one, one, lens, shifted,
+                                 one, None, one, 1 << 20, None) == -5
+    # workspace too small for one real row
+    ok = (i32 * 5)(0, 1, 1, 1, 1)
+    assert lib.vox_paged_prefill(ctypes.byref(sh), one, one, one, one, one, one, lens, ok, one,
+                                 None, one, 64, None) == -3
+    assert lib.vox_paged_prefill_workspace_bytes(ctypes.byref(sh), 5) > 0
+    assert lib.vox_paged_prefill_workspace_bytes(ctypes.byref(sh), -1) == 0
 
 
 def test_workspace_too_small_is_reported(lib):
