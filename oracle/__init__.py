@@ -28,6 +28,8 @@ def _load():
         lib.vox_oracle_kv_append_multi.restype = i
         lib.vox_oracle_paged_prefill.argtypes = [i] * 7 + [f] + [p] * 8
         lib.vox_oracle_paged_prefill.restype = i
+        lib.vox_oracle_rope_append.argtypes = [i] * 7 + [p] * 3 + [i] + [p] * 5
+        lib.vox_oracle_rope_append.restype = i
         lib.vox_oracle_num_threads.restype = i
         _lib = lib
     return _lib
@@ -135,3 +137,27 @@ def paged_prefill(q, k_pool, v_pool, block_tables, context_lens, q_offsets, scal
                                           _ptr(lens), _ptr(qo), _ptr(out), _ptr(lse))
     _check(rc, "paged_prefill")
     return out, lse
+
+
+def rope_append(qkv, rope_cos, rope_sin, k_pool, v_pool, block_tables, context_lens, *,
+                num_q_heads, num_kv_heads, block_size=16, q_out=None):
+    """Rotate q and k heads of packed rows [S, Hq + 2*Hkv, D] at position L_s - 1, append k / v
+    in place, return the rotated q [S, Hq, D] (uint16; rows of empty streams keep ``q_out``)."""
+    qkv = _u16(qkv)
+    bt, lens = _i32(block_tables), _i32(context_lens)
+    cos = np.ascontiguousarray(rope_cos, dtype=np.float32)
+    sin = np.ascontiguousarray(rope_sin, dtype=np.float32)
+    s, heads, d = qkv.shape
+    if heads != num_q_heads + 2 * num_kv_heads or cos.shape != sin.shape or cos.shape[1] != d // 2:
+        raise ValueError("qkv / table shapes do not match the head counts")
+    for pool in (k_pool, v_pool):
+        if pool.dtype != np.uint16 or not pool.flags.c_contiguous or not pool.flags.writeable:
+            raise TypeError("pools must be writable C-contiguous uint16 arrays")
+    if q_out is None:
+        q_out = np.zeros((s, num_q_heads, d), dtype=np.uint16)
+    rc = _load().vox_oracle_rope_append(s, num_q_heads, num_kv_heads, d, block_size,
+                                        k_pool.shape[0], bt.shape[1], _ptr(qkv), _ptr(cos),
+                                        _ptr(sin), cos.shape[0], _ptr(q_out), _ptr(k_pool),
+                                        _ptr(v_pool), _ptr(bt), _ptr(lens))
+    _check(rc, "rope_append")
+    return q_out

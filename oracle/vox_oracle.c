@@ -243,6 +243,87 @@ int vox_oracle_paged_prefill(int S, int Hq, int Hkv, int D, int B, int P, int ma
 }
 
 /* Threads the decode loop would use (for reporting the baseline's core count). */
+/*
+ * Fused step input: rotary position embedding + split of the layer's packed Q/K/V rows +
+ * append (the work the serving loop does between the QKV projection and the attention call;
+ * Section 3.1.1 puts the whole LLM Forward stage on one captured fast path, so these small
+ * steps are folded into the append).  The paper does not describe the backbone's position
+ * encoding; the rotation is the published rotary embedding in the half-split convention of
+ * the Llama / Qwen family its backbones come from:
+ *
+ *   for i < D/2:  y[i]       = x[i] * cos[pos][i]       - x[i + D/2] * sin[pos][i]
+ *                 y[i + D/2] = x[i + D/2] * cos[pos][i] + x[i] * sin[pos][i]
+ *
+ * applied to every q head and every k head of stream s at pos = L_s - 1; v is not rotated.
+ * The result is a bf16 bit pattern, i.e. floating point decides a 16-bit code, so the
+ * arithmetic is fixed and is the library's: both products and their sum/difference are
+ * separate fp32 operations, each rounded to nearest (no fused multiply-add; this file is
+ * compiled with -ffp-contract=off), followed by one round-to-nearest-even to bf16.  cos / sin
+ * arrive as fp32 tables [positions][D/2] made by the caller.
+ *   qkv   : [S][Hq + 2*Hkv][D] bf16 (q heads, then k heads, then v heads)
+ *   q_out : [S][Hq][D] bf16; rows of streams with L_s = 0 are left untouched
+ * Pins (tests/test_oracle_rope_pins.py): quarter-turn worked example, identity at angle 0,
+ * agreement with an fp64 evaluation to half a bf16 ulp, relative-position property of the
+ * rotated dot product, v and untouched slots bit-identical, equality with kv_append when the
+ * angle is 0.
+ */
+static float bf16_to_f32(uint16_t bits) {
+  uint32_t u = (uint32_t)bits << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return f;
+}
+
+static uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u;
+  memcpy(&u, &f, sizeof u);
+  if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (uint16_t)((u >> 16) | 0x0040u); /* NaN */
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+static void rotate_head(int D, const uint16_t* x, const float* c, const float* s, uint16_t* y) {
+  int half = D / 2;
+  for (int i = 0; i < half; ++i) {
+    float a = bf16_to_f32(x[i]), b = bf16_to_f32(x[i + half]);
+    float ac = a * c[i], bs = b * s[i], bc = b * c[i], as = a * s[i];
+    y[i] = f32_to_bf16_rne(ac - bs);
+    y[i + half] = f32_to_bf16_rne(bc + as);
+  }
+}
+
+int vox_oracle_rope_append(int S, int Hq, int Hkv, int D, int B, int P, int max_nb,
+                           const uint16_t* qkv, const float* rope_cos, const float* rope_sin,
+                           int rope_positions, uint16_t* q_out, uint16_t* k_pool,
+                           uint16_t* v_pool, const int32_t* bt, const int32_t* lens) {
+  if (!shape_ok(S, Hq, Hkv, D, B, P, max_nb) || D % 2 || D > 1024) return ORACLE_ERR_ARG;
+  int heads = Hq + 2 * Hkv;
+  for (int s = 0; s < S; ++s) {
+    int L = lens[s];
+    if (L < 0) return ORACLE_ERR_ARG;
+    if (L == 0) continue;
+    int p = L - 1;
+    if (p >= rope_positions) return ORACLE_ERR_ARG;
+    int64_t blk = block_of(bt, max_nb, P, B, s, p);
+    if (blk < 0) return ORACLE_ERR_BLOCK;
+    int t = p % B;
+    const float* c = rope_cos + (size_t)p * (D / 2);
+    const float* sn = rope_sin + (size_t)p * (D / 2);
+    const uint16_t* row = qkv + (size_t)s * heads * D;
+    for (int i = 0; i < Hq; ++i) rotate_head(D, row + (size_t)i * D, c, sn, q_out + ((size_t)s * Hq + i) * D);
+    for (int h = 0; h < Hkv; ++h) {
+      uint16_t k_rot[1024];
+      rotate_head(D, row + (size_t)(Hq + h) * D, c, sn, k_rot);
+      const uint16_t* v = row + (size_t)(Hq + Hkv + h) * D;
+      for (int d = 0; d < D; ++d) {
+        k_pool[k_index(Hkv, D, B, blk, h, t, d)] = k_rot[d];
+        v_pool[v_index(Hkv, D, B, blk, h, t, d)] = v[d];
+      }
+    }
+  }
+  return ORACLE_OK;
+}
+
 int vox_oracle_num_threads(void) {
   int n = 1;
 #ifdef _OPENMP

@@ -293,3 +293,25 @@ def make_multi_workload(kind: str, seed: Optional[int] = None, device="cpu",
                          q=_randn_bf16((tq, hq, d), gen, dev),
                          k_new=_randn_bf16((tq, hkv, d), gen, dev),
                          v_new=_randn_bf16((tq, hkv, d), gen, dev))
+
+
+# ----------------------------------------------------------------------------------------------
+# Inputs of the fused RoPE + split + append step: the packed output rows of a layer's QKV
+# projection and the caller's cos / sin tables.  Tables are evaluated in fp64 and rounded once.
+
+def rope_tables(positions: int, head_dim: int, theta: float = 10000.0):
+    """fp32 (cos, sin) of shape [positions, head_dim/2]; angle = pos * theta**(-2i/head_dim)."""
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    inv_freq = theta ** (-2.0 * i / head_dim)
+    ang = np.arange(positions, dtype=np.float64)[:, None] * inv_freq[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def make_qkv(w: Workload, seed: int, device="cpu", layers: Optional[int] = None) -> List[torch.Tensor]:
+    """One packed [S, Hq + 2*Hkv, D] bf16 tensor of N(0,1) values per layer."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    n = w.layers if layers is None else layers
+    return [_randn_bf16((w.num_streams, w.num_q_heads + 2 * w.num_kv_heads, w.head_dim), gen, dev)
+            for _ in range(n)]

@@ -14,6 +14,16 @@ int vox_oracle_paged_decode(int, int, int, int, int, int, int, float, const uint
                             const uint16_t*, const uint16_t*, const int32_t*, const int32_t*, int,
                             int, double*, double*);
 
+int vox_oracle_kv_append_multi(int, int, int, int, int, int, const uint16_t*, const uint16_t*,
+                               uint16_t*, uint16_t*, const int32_t*, const int32_t*,
+                               const int32_t*);
+int vox_oracle_paged_prefill(int, int, int, int, int, int, int, float, const uint16_t*,
+                             const uint16_t*, const uint16_t*, const int32_t*, const int32_t*,
+                             const int32_t*, double*, double*);
+int vox_oracle_rope_append(int, int, int, int, int, int, int, const uint16_t*, const float*,
+                           const float*, int, uint16_t*, uint16_t*, uint16_t*, const int32_t*,
+                           const int32_t*);
+
 static uint32_t state = 12345u;
 static uint16_t rnd_bf16(void) { /* values in about [-2, 2) with a few mantissa bits */
   state = state * 1664525u + 1013904223u;
@@ -64,6 +74,40 @@ int main(void) {
   if (vox_oracle_paged_decode(S, Hq, Hkv, D, B, P, MAXNB, 0.125f, q, kp, vp, bt, lens, 4, 1, out,
                               NULL))
     return 7;
+  /* multi-token step: whole prompts, a chunk, one token, nothing */
+  const int32_t qo[S + 1] = {0, 1, 17, 20, 20, 31};
+  enum { TQ = 31 };
+  uint16_t* qm = malloc((size_t)TQ * Hq * D * 2);
+  uint16_t* km = malloc((size_t)TQ * Hkv * D * 2);
+  uint16_t* vm = malloc((size_t)TQ * Hkv * D * 2);
+  for (size_t i = 0; i < (size_t)TQ * Hq * D; ++i) qm[i] = rnd_bf16();
+  for (size_t i = 0; i < (size_t)TQ * Hkv * D; ++i) { km[i] = rnd_bf16(); vm[i] = rnd_bf16(); }
+  if (vox_oracle_kv_append_multi(S, Hkv, D, B, P, MAXNB, km, vm, kp, vp, bt, lens, qo)) return 8;
+  double* outm = malloc((size_t)TQ * Hq * D * sizeof(double));
+  double* lsem = malloc((size_t)TQ * Hq * sizeof(double));
+  if (vox_oracle_paged_prefill(S, Hq, Hkv, D, B, P, MAXNB, 0.125f, qm, kp, vp, bt, lens, qo, outm,
+                               lsem))
+    return 9;
+  for (int i = 0; i < TQ * Hq * D; ++i)
+    if (!isfinite(outm[i]) || fabs(outm[i]) > 2.0) return 10;
+  /* rotary embedding + split + append; the table covers exactly the positions in use */
+  enum { POS = 96 };
+  float* rc = malloc((size_t)POS * (D / 2) * sizeof(float));
+  float* rs = malloc((size_t)POS * (D / 2) * sizeof(float));
+  for (int p = 0; p < POS; ++p)
+    for (int i = 0; i < D / 2; ++i) {
+      rc[p * (D / 2) + i] = cosf((float)p * 0.01f * (float)(i + 1));
+      rs[p * (D / 2) + i] = sinf((float)p * 0.01f * (float)(i + 1));
+    }
+  uint16_t* qkv = malloc((size_t)S * (Hq + 2 * Hkv) * D * 2);
+  uint16_t* qr = malloc((size_t)S * Hq * D * 2);
+  for (size_t i = 0; i < (size_t)S * (Hq + 2 * Hkv) * D; ++i) qkv[i] = rnd_bf16();
+  if (vox_oracle_rope_append(S, Hq, Hkv, D, B, P, MAXNB, qkv, rc, rs, POS, qr, kp, vp, bt, lens))
+    return 11;
+  if (vox_oracle_rope_append(S, Hq, Hkv, D, B, P, MAXNB, qkv, rc, rs, POS - 1, qr, kp, vp, bt,
+                             lens) == 0)
+    return 12; /* position 95 is outside a 95-row table */
+  free(qm); free(km); free(vm); free(outm); free(lsem); free(rc); free(rs); free(qkv); free(qr);
   free(kp); free(vp); free(q); free(kn); free(vn); free(ko); free(vo); free(out); free(lse);
   puts("oracle sanitizer driver ok");
   return 0;
