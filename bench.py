@@ -216,6 +216,9 @@ def main() -> int:
                     help="also run one plain 1 GiB device copy (known traffic for scaling HBM counters)")
     ap.add_argument("--hip-graph", action="store_true",
                     help="capture one step per pool set into a HIP graph and time the replays")
+    ap.add_argument("--rope", action="store_true",
+                    help="time vox_decode_step_rope: rotary embedding + Q/K/V split fused into "
+                         "the append (inputs are packed QKV rows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -266,8 +269,21 @@ def main() -> int:
     step_args = [binding.StepArgs(w.q, w.k_new, w.v_new, w.k_pool, w.v_pool, o)
                  for w, o in zip(sets, outs)]
 
+    if args.rope:
+        cos, sin = synth.rope_tables(base.max_blocks_per_stream * 16, base.head_dim)
+        cos_d, sin_d = torch.from_numpy(cos).to(dev), torch.from_numpy(sin).to(dev)
+        qkv = synth.make_qkv(base, base.seed + 7, device=dev)
+        q_rot = [torch.zeros_like(t) for t in base.q]
+        step_args = [binding.RopeStepArgs(qkv, q_rot, w.k_pool, w.v_pool, o, cos_d, sin_d)
+                     for w, o in zip(sets, outs)]
+
     def eager_step(i):
-        binding.decode_step(sh, step_args[i % copies], bt, lens, ws, context_lens_host=host_lens)
+        if args.rope:
+            binding.decode_step_rope(sh, step_args[i % copies], bt, lens, ws,
+                                     context_lens_host=host_lens)
+        else:
+            binding.decode_step(sh, step_args[i % copies], bt, lens, ws,
+                                context_lens_host=host_lens)
 
     step = eager_step
     if args.hip_graph:  # one captured step per pool set, replayed on the current stream
@@ -405,6 +421,7 @@ def main() -> int:
             "split_waves": args.split_waves,
             "host_lens": bool(args.host_lens),
             "hip_graph": bool(args.hip_graph),
+            "rope_fused_append": bool(args.rope),
         },
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "stream_steps_per_s": round(base.num_streams / (ms_per_step * 1e-3), 1),

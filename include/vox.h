@@ -169,6 +169,37 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
                     size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Fused step input (the paper puts the whole LLM Forward stage on one captured fast path,
+ * Section 3.1.1, so the small steps between the QKV projection and the attention call are
+ * folded into the append): rotary position embedding of q and k, split of the packed rows,
+ * append of k and v.  For every stream with L_s > 0, at position pos = L_s - 1:
+ *     i < D/2:  y[i]       = x[i] * cos[pos][i]       - x[i + D/2] * sin[pos][i]
+ *               y[i + D/2] = x[i + D/2] * cos[pos][i] + x[i] * sin[pos][i]
+ * for each q head (result to q_out) and each k head (result into the cache); v heads are copied
+ * unrotated.  Arithmetic: fp32 products and sum as separate roundings, then round to nearest
+ * even to bf16; the result is bit-reproducible.
+ *   qkv       : [S][Hq + 2*Hkv][D] bf16 device: q heads, then k heads, then v heads
+ *   rope_cos, rope_sin : fp32 device [rope_positions][D/2]; rope_positions must be at least
+ *               max_blocks_per_stream * 16 (else VOX_ERR_ARG): the tables are indexed from
+ *               device-side lengths
+ *   q_out     : [S][Hq][D] bf16 device; rows of streams with L_s = 0 are left untouched
+ * vox_decode_step_rope is vox_decode_step with this in place of the plain append: layer l
+ * reads qkv[l], writes q_rot[l] (which the layer's attention then reads) and its pools; q_rot
+ * entries may all name one buffer, since a layer's attention has finished before the next
+ * layer's rows are written.
+ */
+int vox_rope_append(const vox_shape_t* shape, const void* qkv, const float* rope_cos,
+                    const float* rope_sin, int32_t rope_positions, void* q_out, void* k_pool,
+                    void* v_pool, const int32_t* block_tables, const int32_t* context_lens,
+                    void* hip_stream);
+int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const void* const* qkv,
+                         const float* rope_cos, const float* rope_sin, int32_t rope_positions,
+                         void* const* q_rot, void* const* k_pool, void* const* v_pool,
+                         const int32_t* block_tables, const int32_t* context_lens,
+                         const int32_t* context_lens_host, float* const* out, void* workspace,
+                         size_t workspace_bytes, void* hip_stream);
+
+/*
  * Multi-token step: the prefill operation of the Worker (paper Section 3) and every other case
  * where a stream brings several new tokens at once: chunked admission of a prompt during the
  * startup phase (Section 3.2.1), or a detokenizer that keeps attention caches per request and

@@ -68,6 +68,10 @@ def load() -> ctypes.CDLL:
     lib.vox_paged_decode_profiled.restype = ctypes.c_int
     lib.vox_decode_step.argtypes = [sp, i32] + [vp] * 10 + [ctypes.c_size_t, vp]
     lib.vox_decode_step.restype = ctypes.c_int
+    lib.vox_rope_append.argtypes = [sp, vp, vp, vp, i32] + [vp] * 6
+    lib.vox_rope_append.restype = ctypes.c_int
+    lib.vox_decode_step_rope.argtypes = [sp, i32, vp, vp, vp, i32] + [vp] * 8 + [ctypes.c_size_t, vp]
+    lib.vox_decode_step_rope.restype = ctypes.c_int
     lib.vox_paged_prefill_workspace_bytes.argtypes = [sp, i32]
     lib.vox_paged_prefill_workspace_bytes.restype = ctypes.c_size_t
     lib.vox_kv_append_multi.argtypes = [sp] + [vp] * 7 + [i32, vp]
@@ -215,6 +219,66 @@ def decode_step(shape, args: StepArgs, block_tables, context_lens, workspace,
                                 _stream(stream))
     del keep
     _check(rc, "vox_decode_step")
+
+
+def rope_append(shape, qkv, rope_cos, rope_sin, q_out, k_pool, v_pool, block_tables,
+                context_lens, stream=None):
+    """Rotate q / k heads of packed rows at position L_s - 1, write q_out, append k / v."""
+    bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+    if rope_cos.shape != rope_sin.shape:
+        raise ValueError("rope_cos and rope_sin must have the same shape")
+    rc = load().vox_rope_append(ctypes.byref(shape), _dev(qkv, bf, "qkv"),
+                                _dev(rope_cos, f32, "rope_cos"), _dev(rope_sin, f32, "rope_sin"),
+                                int(rope_cos.shape[0]), _dev(q_out, bf, "q_out"),
+                                _dev(k_pool, bf, "k_pool"), _dev(v_pool, bf, "v_pool"),
+                                _dev(block_tables, i32, "block_tables"),
+                                _dev(context_lens, i32, "context_lens"), _stream(stream))
+    _check(rc, "vox_rope_append")
+
+
+class RopeStepArgs:
+    """Host arrays of per-layer device pointers for ``decode_step_rope``."""
+
+    def __init__(self, qkv: Sequence[torch.Tensor], q_rot, k_pool, v_pool, out, rope_cos,
+                 rope_sin):
+        bf, f32 = torch.bfloat16, torch.float32
+        n = len(qkv)
+        if not all(len(x) == n for x in (q_rot, k_pool, v_pool, out)):
+            raise ValueError("per-layer lists must have the same length")
+        if rope_cos.shape != rope_sin.shape:
+            raise ValueError("rope_cos and rope_sin must have the same shape")
+        self.num_layers = n
+        self._keep = (qkv, q_rot, k_pool, v_pool, out, rope_cos, rope_sin)
+
+        def arr(ts, dtype, what):
+            a = (ctypes.c_void_p * n)()
+            for i, t in enumerate(ts):
+                a[i] = _dev(t, dtype, f"{what}[{i}]").value
+            return a
+
+        self.qkv = arr(qkv, bf, "qkv")
+        self.q_rot = arr(q_rot, bf, "q_rot")
+        self.k_pool = arr(k_pool, bf, "k_pool")
+        self.v_pool = arr(v_pool, bf, "v_pool")
+        self.out = arr(out, f32, "out")
+        self.rope_cos = _dev(rope_cos, f32, "rope_cos")
+        self.rope_sin = _dev(rope_sin, f32, "rope_sin")
+        self.rope_positions = int(rope_cos.shape[0])
+
+
+def decode_step_rope(shape, args: RopeStepArgs, block_tables, context_lens, workspace,
+                     context_lens_host=None, stream=None):
+    i32 = torch.int32
+    keep, host = _host_lens(context_lens_host)
+    rc = load().vox_decode_step_rope(ctypes.byref(shape), args.num_layers, args.qkv,
+                                     args.rope_cos, args.rope_sin, args.rope_positions,
+                                     args.q_rot, args.k_pool, args.v_pool,
+                                     _dev(block_tables, i32, "block_tables"),
+                                     _dev(context_lens, i32, "context_lens"), host, args.out,
+                                     _dev(workspace, torch.uint8, "workspace"),
+                                     workspace.numel(), _stream(stream))
+    del keep
+    _check(rc, "vox_decode_step_rope")
 
 
 def paged_prefill_workspace_bytes(shape, total_q: int) -> int:

@@ -138,6 +138,21 @@ WsPtrs ws_ptrs(const Plan& plan, char* ws) {
 }
 
 // The split-K attention launch alone (the merge follows separately).
+AppendArgs plain_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool) {
+  return AppendArgs{(const uint16_t*)k_new, (const uint16_t*)v_new, (uint16_t*)k_pool,
+                    (uint16_t*)v_pool, nullptr, nullptr, nullptr, nullptr};
+}
+AppendArgs rope_append(const void* qkv, const float* rope_cos, const float* rope_sin, void* q_out,
+                       void* k_pool, void* v_pool) {
+  return AppendArgs{nullptr, nullptr, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)qkv,
+                    rope_cos, rope_sin, (uint16_t*)q_out};
+}
+// The cos / sin tables must cover every position the shape admits: the kernels index them with
+// L_s - 1 from device memory and cannot report a short table.
+bool rope_table_ok(const vox_shape_t* s, int32_t rope_positions) {
+  return rope_positions >= s->max_blocks_per_stream * kBlock;
+}
+
 int enqueue_attention(const vox_shape_t* s, const Params& p, const Plan& plan, const WsPtrs& w,
                       const void* q, const void* k_pool, const void* v_pool, hipStream_t st,
                       hipEvent_t ev_before = nullptr, hipEvent_t ev_after = nullptr) {
@@ -172,8 +187,8 @@ int vox_kv_append(const vox_shape_t* shape, const void* k_new, const void* v_new
   if (!k_new || !v_new || !k_pool || !v_pool || !block_tables || !context_lens)
     return VOX_ERR_NULL;
   const Params p = make_params(shape);
-  return launch_kv_append(p, k_new, v_new, k_pool, v_pool, block_tables, context_lens,
-                          (hipStream_t)hip_stream) == hipSuccess
+  return launch_append(p, plain_append(k_new, v_new, k_pool, v_pool), block_tables, context_lens,
+                       (hipStream_t)hip_stream) == hipSuccess
              ? VOX_OK
              : VOX_ERR_HIP;
 }
@@ -254,16 +269,77 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
   // Launch chain: [plan + append(0)] attention(0) [merge(0) + append(1)] attention(1) ...
   // merge(L-1).  Each bracket is one launch of two independent roles.
   if (launch_plan_append(p, block_tables, context_lens, plan.waves, plan.desc_capacity,
-                         plan.max_steps, w.header, w.step_prefix, w.desc, k_new[0], v_new[0],
-                         k_pool[0], v_pool[0], st) != hipSuccess)
+                         plan.max_steps, w.header, w.step_prefix, w.desc,
+                         plain_append(k_new[0], v_new[0], k_pool[0], v_pool[0]), st) != hipSuccess)
     return VOX_ERR_HIP;
   for (int l = 0; l < num_layers; ++l) {
     if (int rc = enqueue_attention(shape, p, plan, w, q[l], k_pool[l], v_pool[l], st)) return rc;
     hipError_t e =
         l + 1 < num_layers
             ? launch_merge_append(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], block_tables,
-                                  context_lens, k_new[l + 1], v_new[l + 1], k_pool[l + 1],
-                                  v_pool[l + 1], st)
+                                  context_lens,
+                                  plain_append(k_new[l + 1], v_new[l + 1], k_pool[l + 1],
+                                               v_pool[l + 1]),
+                                  st)
+            : launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], nullptr, st);
+    if (e != hipSuccess) return VOX_ERR_HIP;
+  }
+  return VOX_OK;
+}
+
+int vox_rope_append(const vox_shape_t* shape, const void* qkv, const float* rope_cos,
+                    const float* rope_sin, int32_t rope_positions, void* q_out, void* k_pool,
+                    void* v_pool, const int32_t* block_tables, const int32_t* context_lens,
+                    void* hip_stream) {
+  if (int rc = validate(shape)) return rc;
+  if (!qkv || !rope_cos || !rope_sin || !q_out || !k_pool || !v_pool || !block_tables ||
+      !context_lens)
+    return VOX_ERR_NULL;
+  if (!rope_table_ok(shape, rope_positions)) return VOX_ERR_ARG;
+  const Params p = make_params(shape);
+  return launch_append(p, rope_append(qkv, rope_cos, rope_sin, q_out, k_pool, v_pool),
+                       block_tables, context_lens, (hipStream_t)hip_stream) == hipSuccess
+             ? VOX_OK
+             : VOX_ERR_HIP;
+}
+
+int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const void* const* qkv,
+                         const float* rope_cos, const float* rope_sin, int32_t rope_positions,
+                         void* const* q_rot, void* const* k_pool, void* const* v_pool,
+                         const int32_t* block_tables, const int32_t* context_lens,
+                         const int32_t* context_lens_host, float* const* out, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  if (int rc = validate(shape)) return rc;
+  if (num_layers <= 0) return VOX_ERR_ARG;
+  if (!qkv || !rope_cos || !rope_sin || !q_rot || !k_pool || !v_pool || !block_tables ||
+      !context_lens || !out || !workspace)
+    return VOX_ERR_NULL;
+  for (int l = 0; l < num_layers; ++l)
+    if (!qkv[l] || !q_rot[l] || !k_pool[l] || !v_pool[l] || !out[l]) return VOX_ERR_NULL;
+  if (!rope_table_ok(shape, rope_positions)) return VOX_ERR_ARG;
+  if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
+  Plan plan;
+  if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
+  Params p = make_params(shape);
+  set_step_hints(&p, plan);
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  const WsPtrs w = ws_ptrs(plan, ws);
+  // [plan + rope/append(0)] attention(0) [merge(0) + rope/append(1)] attention(1) ... merge(L-1)
+  const auto layer = [&](int l) {
+    return rope_append(qkv[l], rope_cos, rope_sin, q_rot[l], k_pool[l], v_pool[l]);
+  };
+  if (launch_plan_append(p, block_tables, context_lens, plan.waves, plan.desc_capacity,
+                         plan.max_steps, w.header, w.step_prefix, w.desc, layer(0),
+                         st) != hipSuccess)
+    return VOX_ERR_HIP;
+  for (int l = 0; l < num_layers; ++l) {
+    if (int rc = enqueue_attention(shape, p, plan, w, q_rot[l], k_pool[l], v_pool[l], st))
+      return rc;
+    hipError_t e =
+        l + 1 < num_layers
+            ? launch_merge_append(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], block_tables,
+                                  context_lens, layer(l + 1), st)
             : launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], nullptr, st);
     if (e != hipSuccess) return VOX_ERR_HIP;
   }

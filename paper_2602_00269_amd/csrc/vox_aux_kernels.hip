@@ -48,19 +48,97 @@ __device__ inline void append_role(const Params& p, int group, const uint16_t* _
   }
 }
 
-// The buffers of one layer's append, passed by value to the kernels that carry an append role.
-struct AppendArgs {
-  const uint16_t* k_new;
-  const uint16_t* v_new;
-  uint16_t* k_pool;
-  uint16_t* v_pool;
-};
+// Fused-mode append: one wave per (stream, q head or kv head).  Lane j < D/4 owns the rotation
+// pairs (i, i + D/2) for i = 2j, 2j+1.  The arithmetic is fixed, because it decides bf16 codes:
+// two fp32 products and their sum or difference as separate roundings (contraction is off in
+// this function), then round-to-nearest-even to bf16 done on the bits.
+__device__ inline uint32_t bf16_rne_bits(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (u >> 16) | 0x0040u;  // NaN
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ inline float bf16_bits_to_f32(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
+
+template <int D>
+__device__ inline void insert_v(uint16_t* __restrict__ v_pool, size_t g, int t, int lane,
+                                const uint16_t* __restrict__ vrow) {
+  if (lane < D / 2) {
+    uint16_t* quad = v_pool + g + v_elem(t & ~3, 2 * lane, D);  // dims 2*lane, 2*lane+1
+    au32x4 r = *reinterpret_cast<const au32x4*>(quad);
+    const uint32_t two = *reinterpret_cast<const uint32_t*>(vrow + 2 * lane);
+    const int e = t & 3;  // slot of the token inside each 4-token quad
+    const uint32_t d0 = two & 0xFFFFu, d1 = two >> 16;
+    const uint32_t keep = (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+    const int sh = (e & 1) * 16;
+    r[e >> 1] = (r[e >> 1] & keep) | (d0 << sh);
+    r[2 + (e >> 1)] = (r[2 + (e >> 1)] & keep) | (d1 << sh);
+    *reinterpret_cast<au32x4*>(quad) = r;
+  }
+}
+
+template <int D>
+__device__ inline void rope_append_role(const Params& p, int group, const AppendArgs& a,
+                                        const int32_t* __restrict__ bt,
+                                        const int32_t* __restrict__ lens) {
+#pragma clang fp contract(off)
+  const int lane = threadIdx.x & (kWave - 1);
+  const int x = group * kWavesPerGroup + (threadIdx.x >> 6);
+  const int slots = p.Hq + p.Hkv;
+  if (x >= p.S * slots) return;
+  const int s = x / slots, hs = x % slots;
+  const int L = lens[s];
+  if (L <= 0) return;
+  const int pos = L - 1;
+  const uint16_t* row = a.qkv + ((size_t)s * (p.Hq + 2 * p.Hkv) + hs) * D;  // q heads, then k heads
+  uint32_t lo = 0, hi = 0;
+  if (lane < D / 4) {
+    const uint32_t x1 = *reinterpret_cast<const uint32_t*>(row + 2 * lane);
+    const uint32_t x2 = *reinterpret_cast<const uint32_t*>(row + D / 2 + 2 * lane);
+    const float2 c = *reinterpret_cast<const float2*>(a.rope_cos + (size_t)pos * (D / 2) + 2 * lane);
+    const float2 sn = *reinterpret_cast<const float2*>(a.rope_sin + (size_t)pos * (D / 2) + 2 * lane);
+    const float a0 = bf16_bits_to_f32(x1 & 0xFFFFu), a1 = bf16_bits_to_f32(x1 >> 16);
+    const float b0 = bf16_bits_to_f32(x2 & 0xFFFFu), b1 = bf16_bits_to_f32(x2 >> 16);
+    const float a0c = a0 * c.x, b0s = b0 * sn.x, b0c = b0 * c.x, a0s = a0 * sn.x;
+    const float a1c = a1 * c.y, b1s = b1 * sn.y, b1c = b1 * c.y, a1s = a1 * sn.y;
+    lo = bf16_rne_bits(a0c - b0s) | (bf16_rne_bits(a1c - b1s) << 16);
+    hi = bf16_rne_bits(b0c + a0s) | (bf16_rne_bits(b1c + a1s) << 16);
+  }
+  if (hs < p.Hq) {
+    if (lane < D / 4) {
+      uint16_t* dst = a.q_out + ((size_t)s * p.Hq + hs) * D;
+      *reinterpret_cast<uint32_t*>(dst + 2 * lane) = lo;
+      *reinterpret_cast<uint32_t*>(dst + D / 2 + 2 * lane) = hi;
+    }
+    return;
+  }
+  const int h = hs - p.Hq;
+  const int64_t blk = bt[(int64_t)s * p.max_nb + (pos >> 4)];
+  const int t = pos & (kBlock - 1);
+  const size_t g = granule_offset(blk, h, p.Hkv, D);
+  if (lane < D / 4) {
+    *reinterpret_cast<uint32_t*>(a.k_pool + g + k_elem(t, 2 * lane)) = lo;
+    *reinterpret_cast<uint32_t*>(a.k_pool + g + k_elem(t, D / 2 + 2 * lane)) = hi;
+  }
+  insert_v<D>(a.v_pool, g, t, lane, row + (size_t)p.Hkv * D);  // v head h follows the k heads
+}
+
+// Either mode of the append, by what the arguments carry.
+template <int D>
+__device__ inline void any_append_role(const Params& p, int group, const AppendArgs& a,
+                                       const int32_t* __restrict__ bt,
+                                       const int32_t* __restrict__ lens) {
+  if (a.qkv)
+    rope_append_role<D>(p, group, a, bt, lens);
+  else
+    append_role<D>(p, group, a.k_new, a.v_new, a.k_pool, a.v_pool, bt, lens);
+}
 
 template <int D>
 __global__ __launch_bounds__(256) void kv_append_kernel(Params p, AppendArgs a,
                                                         const int32_t* __restrict__ bt,
                                                         const int32_t* __restrict__ lens) {
-  append_role<D>(p, blockIdx.x, a.k_new, a.v_new, a.k_pool, a.v_pool, bt, lens);
+  any_append_role<D>(p, blockIdx.x, a, bt, lens);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -200,7 +278,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
   if ((int)blockIdx.x < plan_groups)
     plan_role(p, blockIdx.x, bt, lens, waves, desc_capacity, header, step_prefix, desc);
   else
-    append_role<D>(p, blockIdx.x - plan_groups, a.k_new, a.v_new, a.k_pool, a.v_pool, bt, lens);
+    any_append_role<D>(p, blockIdx.x - plan_groups, a, bt, lens);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -255,17 +333,14 @@ __global__ __launch_bounds__(256) void merge_append_kernel(
   if ((int)blockIdx.x < merge_grps)
     merge_role<D>(p, blockIdx.x, header, step_prefix, pml, pacc, out, nullptr);
   else
-    append_role<D>(p, blockIdx.x - merge_grps, a.k_new, a.v_new, a.k_pool, a.v_pool, bt, lens);
+    any_append_role<D>(p, blockIdx.x - merge_grps, a, bt, lens);
 }
 
 }  // namespace
 
-static AppendArgs append_args(const void* k_new, const void* v_new, void* k_pool, void* v_pool) {
-  return AppendArgs{(const uint16_t*)k_new, (const uint16_t*)v_new, (uint16_t*)k_pool,
-                    (uint16_t*)v_pool};
-}
-static unsigned host_append_groups(const Params& p) {
-  return (unsigned)(((int64_t)p.S * p.Hkv + kWavesPerGroup - 1) / kWavesPerGroup);
+static unsigned host_append_groups(const Params& p, const AppendArgs& a) {
+  const int64_t waves = (int64_t)p.S * (a.qkv ? p.Hq + p.Hkv : p.Hkv);
+  return (unsigned)((waves + kWavesPerGroup - 1) / kWavesPerGroup);
 }
 static unsigned host_merge_groups(const Params& p) {
   return (unsigned)(((int64_t)p.S * p.Hq + kWavesPerGroup - 1) / kWavesPerGroup);
@@ -274,16 +349,14 @@ static unsigned host_plan_groups(int64_t max_steps) {
   return (unsigned)max((int64_t)1, (max_steps + kPlanThreads - 1) / kPlanThreads);
 }
 
-hipError_t launch_kv_append(const Params& p, const void* k_new, const void* v_new, void* k_pool,
-                            void* v_pool, const int32_t* bt, const int32_t* lens,
-                            hipStream_t st) {
-  const AppendArgs a = append_args(k_new, v_new, k_pool, v_pool);
+hipError_t launch_append(const Params& p, const AppendArgs& a, const int32_t* bt,
+                         const int32_t* lens, hipStream_t st) {
   if (p.D == 128)
-    hipLaunchKernelGGL(kv_append_kernel<128>, dim3(host_append_groups(p)), dim3(256), 0, st, p, a,
-                       bt, lens);
+    hipLaunchKernelGGL(kv_append_kernel<128>, dim3(host_append_groups(p, a)), dim3(256), 0, st, p,
+                       a, bt, lens);
   else
-    hipLaunchKernelGGL(kv_append_kernel<64>, dim3(host_append_groups(p)), dim3(256), 0, st, p, a,
-                       bt, lens);
+    hipLaunchKernelGGL(kv_append_kernel<64>, dim3(host_append_groups(p, a)), dim3(256), 0, st, p,
+                       a, bt, lens);
   return hipGetLastError();
 }
 
@@ -309,17 +382,16 @@ hipError_t launch_plan(const Params& p, const int32_t* bt, const int32_t* lens, 
 
 hipError_t launch_plan_append(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
                               int64_t desc_capacity, int64_t max_steps, int32_t* header,
-                              int32_t* step_prefix, int4* desc, const void* k_new,
-                              const void* v_new, void* k_pool, void* v_pool, hipStream_t st) {
+                              int32_t* step_prefix, int4* desc, const AppendArgs& a,
+                              hipStream_t st) {
   if (p.S > kPlanMaxStreams) return hipErrorInvalidValue;
   const unsigned pg = host_plan_groups(max_steps);
-  const AppendArgs a = append_args(k_new, v_new, k_pool, v_pool);
   if (p.D == 128)
-    hipLaunchKernelGGL(plan_append_kernel<128>, dim3(pg + host_append_groups(p)),
+    hipLaunchKernelGGL(plan_append_kernel<128>, dim3(pg + host_append_groups(p, a)),
                        dim3(kPlanThreads), 0, st, p, (int)pg, a, bt, lens, waves, desc_capacity,
                        header, step_prefix, desc);
   else
-    hipLaunchKernelGGL(plan_append_kernel<64>, dim3(pg + host_append_groups(p)),
+    hipLaunchKernelGGL(plan_append_kernel<64>, dim3(pg + host_append_groups(p, a)),
                        dim3(kPlanThreads), 0, st, p, (int)pg, a, bt, lens, waves, desc_capacity,
                        header, step_prefix, desc);
   return hipGetLastError();
@@ -339,16 +411,15 @@ hipError_t launch_merge(const Params& p, const int32_t* header, const int32_t* s
 
 hipError_t launch_merge_append(const Params& p, const int32_t* header, const int32_t* step_prefix,
                                const float2* partial_ml, const float* partial_acc, float* out,
-                               const int32_t* bt, const int32_t* lens, const void* k_new,
-                               const void* v_new, void* k_pool, void* v_pool, hipStream_t st) {
+                               const int32_t* bt, const int32_t* lens, const AppendArgs& a,
+                               hipStream_t st) {
   const unsigned mg = host_merge_groups(p);
-  const AppendArgs a = append_args(k_new, v_new, k_pool, v_pool);
   if (p.D == 128)
-    hipLaunchKernelGGL(merge_append_kernel<128>, dim3(mg + host_append_groups(p)), dim3(256), 0,
+    hipLaunchKernelGGL(merge_append_kernel<128>, dim3(mg + host_append_groups(p, a)), dim3(256), 0,
                        st, p, (int)mg, header, step_prefix, partial_ml, partial_acc, out, a, bt,
                        lens);
   else
-    hipLaunchKernelGGL(merge_append_kernel<64>, dim3(mg + host_append_groups(p)), dim3(256), 0,
+    hipLaunchKernelGGL(merge_append_kernel<64>, dim3(mg + host_append_groups(p, a)), dim3(256), 0,
                        st, p, (int)mg, header, step_prefix, partial_ml, partial_acc, out, a, bt,
                        lens);
   return hipGetLastError();

@@ -83,24 +83,38 @@ __host__ __device__ inline int k_elem(int t, int d) {
 }
 __host__ __device__ inline int v_elem(int t, int d, int D) { return ((t >> 2) * D + d) * 4 + (t & 3); }
 
+// The buffers of one layer's append, passed by value to the kernels that carry an append role.
+// Plain mode (qkv == nullptr): k_new / v_new rows are copied.  Fused mode: the rows come from
+// the packed [S][Hq + 2*Hkv][D] output of the QKV projection; q and k heads are rotated with
+// the cos / sin rows of position L_s - 1, q goes to q_out, k and v into the cache.
+struct AppendArgs {
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  uint16_t* k_pool;
+  uint16_t* v_pool;
+  const uint16_t* qkv;
+  const float* rope_cos;
+  const float* rope_sin;
+  uint16_t* q_out;
+};
+
 // Launchers implemented in the kernel translation units; each returns hipGetLastError().
-hipError_t launch_kv_append(const Params& p, const void* k_new, const void* v_new, void* k_pool,
-                            void* v_pool, const int32_t* bt, const int32_t* lens,
-                            hipStream_t st);
+hipError_t launch_append(const Params& p, const AppendArgs& a, const int32_t* bt,
+                         const int32_t* lens, hipStream_t st);
+hipError_t launch_plan_append(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
+                              int64_t desc_capacity, int64_t max_steps, int32_t* header,
+                              int32_t* step_prefix, int4* desc, const AppendArgs& a,
+                              hipStream_t st);
+hipError_t launch_merge_append(const Params& p, const int32_t* header, const int32_t* step_prefix,
+                               const float2* partial_ml, const float* partial_acc, float* out,
+                               const int32_t* bt, const int32_t* lens, const AppendArgs& a,
+                               hipStream_t st);
 hipError_t launch_kv_gather(const Params& p, const void* k_pool, const void* v_pool,
                             const int32_t* bt, const int32_t* lens, const int64_t* row_offsets,
                             void* k_out, void* v_out, hipStream_t st);
 hipError_t launch_plan(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
                        int64_t desc_capacity, int64_t max_steps, int32_t* header,
                        int32_t* step_prefix, int4* desc, hipStream_t st);
-hipError_t launch_plan_append(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
-                              int64_t desc_capacity, int64_t max_steps, int32_t* header,
-                              int32_t* step_prefix, int4* desc, const void* k_new,
-                              const void* v_new, void* k_pool, void* v_pool, hipStream_t st);
-hipError_t launch_merge_append(const Params& p, const int32_t* header, const int32_t* step_prefix,
-                               const float2* partial_ml, const float* partial_acc, float* out,
-                               const int32_t* bt, const int32_t* lens, const void* k_new,
-                               const void* v_new, void* k_pool, void* v_pool, hipStream_t st);
 PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, int64_t total_q,
                                        int64_t slots, int64_t desc_capacity, int waves);
 int prefill_column_groups(const Params& p, int max_new_tokens);

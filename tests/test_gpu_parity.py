@@ -516,3 +516,108 @@ def test_multi_token_step_with_no_rows_is_a_no_op(dev):
     kp, vp = _host_pools(w)
     assert np.array_equal(kp.view(np.uint16), kp0.view(np.uint16))
     assert np.array_equal(vp.view(np.uint16), vp0.view(np.uint16))
+
+
+# ---------------------------------------------------------------------------------------
+# Fused step input: rotary embedding + Q/K/V split + append
+
+ROPE_CASES = [
+    ([33, 0, 700, 64, 1, 255, 16, 17], 24, 8, 128),
+    ([1, 2, 15, 16, 17, 31, 32, 0, 300], 8, 2, 64),
+    ([129, 4096], 14, 2, 64),
+    ([500, 77, 1024], 8, 8, 128),
+]
+
+
+def _rope_inputs(dev, w, layers, seed):
+    cos, sin = synth.rope_tables(w.max_blocks_per_stream * 16, w.head_dim)
+    qkv = synth.make_qkv(w, seed, device=dev, layers=layers)
+    return qkv, cos, sin, torch.from_numpy(cos).to(dev), torch.from_numpy(sin).to(dev)
+
+
+@pytest.mark.parametrize("case", range(len(ROPE_CASES)))
+def test_rope_append_is_bit_exact(dev, case):
+    lens, hq, hkv, d = ROPE_CASES[case]
+    w = synth.make_custom(lens, hq, hkv, d, seed=120 + case, device=dev)
+    qkv, cos, sin, cos_d, sin_d = _rope_inputs(dev, w, 1, 130 + case)
+    sh = binding.shape_of(w)
+    bt, lens_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev)
+    kp_ref, vp_ref = _host_pools(w)
+    q_ref = np.full((len(lens), hq, d), 0x7FC1, np.uint16)
+    oracle.rope_append(bits_of(qkv[0]), cos, sin, kp_ref, vp_ref, w.block_tables, w.context_lens,
+                       num_q_heads=hq, num_kv_heads=hkv, q_out=q_ref)
+    q_out = torch.from_numpy(np.full((len(lens), hq, d), 0x7FC1, np.uint16).view(np.int16)).to(
+        dev).view(torch.bfloat16)
+    binding.rope_append(sh, qkv[0], cos_d, sin_d, q_out, w.k_pool[0], w.v_pool[0], bt, lens_d)
+    torch.cuda.synchronize()
+    kp, vp = _host_pools(w)
+    assert np.array_equal(bits_of(q_out), q_ref)
+    assert np.array_equal(kp, kp_ref) and np.array_equal(vp, vp_ref)
+
+
+def test_decode_step_rope_matches_oracle_and_replays_from_a_graph(dev):
+    layers = 3
+    w = synth.make_workload(1, device=dev, layers=layers)
+    qkv, cos, sin, cos_d, sin_d = _rope_inputs(dev, w, layers, 140)
+    sh = binding.shape_of(w)
+    bt, lens_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev)
+    s, hq, hkv, d = w.num_streams, w.num_q_heads, w.num_kv_heads, w.head_dim
+    outs = [torch.full((s, hq, d), float("nan"), device=dev) for _ in range(layers)]
+    q_rot = [torch.zeros((s, hq, d), dtype=torch.bfloat16, device=dev) for _ in range(layers)]
+    ws = binding.alloc_workspace(sh, dev)
+    pools0 = [(k.clone(), v.clone()) for k, v in zip(w.k_pool, w.v_pool)]
+    args = binding.RopeStepArgs(qkv, q_rot, w.k_pool, w.v_pool, outs, cos_d, sin_d)
+    # oracle, layer by layer
+    refs = []
+    for l in range(layers):
+        kp_ref, vp_ref = _host_pools(w, l)
+        q_ref = oracle.rope_append(bits_of(qkv[l]), cos, sin, kp_ref, vp_ref, w.block_tables,
+                                   w.context_lens, num_q_heads=hq, num_kv_heads=hkv)
+        out_ref, _ = oracle.paged_decode(q_ref, kp_ref, vp_ref, w.block_tables, w.context_lens,
+                                         w.scale, num_kv_heads=hkv)
+        refs.append((q_ref, kp_ref, vp_ref, out_ref))
+    binding.decode_step_rope(sh, args, bt, lens_d, ws, context_lens_host=w.context_lens)
+    torch.cuda.synchronize()
+    live = w.context_lens > 0
+    for l in range(layers):
+        q_ref, kp_ref, vp_ref, out_ref = refs[l]
+        kp, vp = _host_pools(w, l)
+        assert np.array_equal(bits_of(q_rot[l])[live], q_ref[live])
+        assert np.array_equal(kp, kp_ref) and np.array_equal(vp, vp_ref)
+        _assert_close(outs[l].cpu().numpy(), out_ref, f"rope step layer {l}")
+    eager = [o.clone() for o in outs]
+    # one shared q buffer for all layers gives the same result
+    shared = torch.zeros((s, hq, d), dtype=torch.bfloat16, device=dev)
+    outs2 = [torch.full((s, hq, d), float("nan"), device=dev) for _ in range(layers)]
+    for (k0, v0), k, v in zip(pools0, w.k_pool, w.v_pool):
+        k.copy_(k0)
+        v.copy_(v0)
+    args2 = binding.RopeStepArgs(qkv, [shared] * layers, w.k_pool, w.v_pool, outs2, cos_d, sin_d)
+    binding.decode_step_rope(sh, args2, bt, lens_d, ws, context_lens_host=w.context_lens)
+    torch.cuda.synchronize()
+    for a, b in zip(outs2, eager):
+        assert torch.equal(a, b)
+    # captured once, replayed with eager work in between; every replay equals the eager result
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        binding.decode_step_rope(sh, args, bt, lens_d, ws, context_lens_host=w.context_lens)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        binding.decode_step_rope(sh, args, bt, lens_d, ws, context_lens_host=w.context_lens)
+    for rep in range(3):
+        for (k0, v0), k, v in zip(pools0, w.k_pool, w.v_pool):
+            k.copy_(k0)
+            v.copy_(v0)
+        for o in outs:
+            o.fill_(float("nan"))
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(layers):
+            assert torch.equal(outs[l], eager[l]), f"replay {rep} layer {l}"
+            kp, vp = _host_pools(w, l)
+            assert np.array_equal(kp, refs[l][1]) and np.array_equal(vp, refs[l][2])

@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"vox_kv_append", "vox_kv_gather", "vox_paged_decode", "vox_decode_step",
             "vox_paged_decode_workspace_bytes", "vox_paged_decode_profiled", "vox_strerror",
             "vox_kv_append_multi", "vox_paged_prefill", "vox_paged_prefill_profiled",
-            "vox_paged_prefill_workspace_bytes"} <= set(names)
+            "vox_paged_prefill_workspace_bytes", "vox_rope_append", "vox_decode_step_rope"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -114,6 +114,19 @@ def test_multi_token_calls_validate_on_the_host(lib):
                                  None, one, 64, None) == -3
     assert lib.vox_paged_prefill_workspace_bytes(ctypes.byref(sh), 5) > 0
     assert lib.vox_paged_prefill_workspace_bytes(ctypes.byref(sh), -1) == 0
+
+
+def test_rope_calls_validate_on_the_host(lib):
+    sh = _shape()  # 16 blocks per stream: positions 0..255
+    one = ctypes.c_void_p(256)
+    assert lib.vox_rope_append(ctypes.byref(sh), one, one, one, 255, one, one, one, one, one,
+                               None) == -5  # table shorter than the positions the shape admits
+    assert lib.vox_rope_append(ctypes.byref(sh), None, one, one, 256, one, one, one, one, one,
+                               None) == -1
+    assert lib.vox_decode_step_rope(ctypes.byref(sh), 0, one, one, one, 256, one, one, one, one,
+                                    one, None, one, one, 1 << 20, None) == -5
+    assert lib.vox_decode_step_rope(ctypes.byref(sh), 1, None, one, one, 256, one, one, one, one,
+                                    one, None, one, one, 1 << 20, None) == -1
 
 
 def test_workspace_too_small_is_reported(lib):
