@@ -30,6 +30,10 @@ def _load():
         lib.vox_oracle_paged_prefill.restype = i
         lib.vox_oracle_rope_append.argtypes = [i] * 7 + [p] * 3 + [i] + [p] * 5
         lib.vox_oracle_rope_append.restype = i
+        lib.vox_oracle_sample.argtypes = [i, i, p, p, p, i, p, p, p]
+        lib.vox_oracle_sample.restype = i
+        lib.vox_oracle_sample_weight.argtypes = [f]
+        lib.vox_oracle_sample_weight.restype = ctypes.c_uint64
         lib.vox_oracle_num_threads.restype = i
         _lib = lib
     return _lib
@@ -161,3 +165,46 @@ def rope_append(qkv, rope_cos, rope_sin, k_pool, v_pool, block_tables, context_l
                                         _ptr(v_pool), _ptr(bt), _ptr(lens))
     _check(rc, "rope_append")
     return q_out
+
+
+SAMPLING_DTYPE = np.dtype([("temperature", np.float32), ("top_p", np.float32),
+                           ("repetition_penalty", np.float32), ("top_k", np.int32)])
+
+
+def sampling_params(temperature, top_p, repetition_penalty, top_k, n=None):
+    """Structured array of per-stream sampling parameters (scalars broadcast to ``n``)."""
+    cols = [np.atleast_1d(np.asarray(c)) for c in (temperature, top_p, repetition_penalty, top_k)]
+    n = max(c.size for c in cols) if n is None else n
+    out = np.zeros(n, dtype=SAMPLING_DTYPE)
+    for name, c in zip(("temperature", "top_p", "repetition_penalty", "top_k"), cols):
+        out[name] = np.broadcast_to(c, (n,))
+    return out
+
+
+def sample(logits, params, uniforms, history=None):
+    """(tokens [S] int32, kept [S] int32) for fp32 logits [S, V] and ``sampling_params``."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    s, v = logits.shape
+    params = np.ascontiguousarray(params, dtype=SAMPLING_DTYPE)
+    u = np.ascontiguousarray(uniforms, dtype=np.float32)
+    if params.shape != (s,) or u.shape != (s,):
+        raise ValueError("params and uniforms must have one entry per stream")
+    window = 0
+    hist_ptr = None
+    if history is not None:
+        history = np.ascontiguousarray(history, dtype=np.int32)
+        if history.ndim != 2 or history.shape[0] != s:
+            raise ValueError("history must be [S, window]")
+        window = history.shape[1]
+        hist_ptr = _ptr(history)
+    tokens = np.zeros(s, dtype=np.int32)
+    kept = np.zeros(s, dtype=np.int32)
+    rc = _load().vox_oracle_sample(s, v, _ptr(logits), _ptr(params), hist_ptr, window, _ptr(u),
+                                   _ptr(tokens), _ptr(kept))
+    _check(rc, "sample")
+    return tokens, kept
+
+
+def sample_weight(d: float) -> int:
+    """The integer softmax weight 2^40 * exp(-d) of the fixed sampling arithmetic."""
+    return int(_load().vox_oracle_sample_weight(np.float32(d)))

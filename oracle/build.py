@@ -4,15 +4,15 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "vox_oracle.c")
+SRCS = [os.path.join(HERE, "vox_oracle.c"), os.path.join(HERE, "vox_oracle_sample.c")]
 LIB = os.path.join(HERE, "libvox_oracle.so")
 
 
 def build(force: bool = False) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(f) for f in SRCS):
         return LIB
     cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-           "-ffp-contract=off", SRC, "-o", LIB, "-lm"]
+           "-ffp-contract=off", *SRCS, "-o", LIB, "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 

@@ -24,6 +24,13 @@ int vox_oracle_rope_append(int, int, int, int, int, int, int, const uint16_t*, c
                            const float*, int, uint16_t*, uint16_t*, uint16_t*, const int32_t*,
                            const int32_t*);
 
+typedef struct {
+  float temperature, top_p, repetition_penalty;
+  int32_t top_k;
+} sampling_t;
+int vox_oracle_sample(int, int, const float*, const sampling_t*, const int32_t*, int,
+                      const float*, int32_t*, int32_t*);
+
 static uint32_t state = 12345u;
 static uint16_t rnd_bf16(void) { /* values in about [-2, 2) with a few mantissa bits */
   state = state * 1664525u + 1013904223u;
@@ -107,6 +114,25 @@ int main(void) {
   if (vox_oracle_rope_append(S, Hq, Hkv, D, B, P, MAXNB, qkv, rc, rs, POS - 1, qr, kp, vp, bt,
                              lens) == 0)
     return 12; /* position 95 is outside a 95-row table */
+  /* sampling: every mode, windows with empty and out-of-range slots */
+  enum { SV = 301, SS = 6, SW = 5 };
+  float* logits = malloc((size_t)SS * SV * sizeof(float));
+  for (int i = 0; i < SS * SV; ++i) {
+    state = state * 1664525u + 1013904223u;
+    logits[i] = (float)((int)(state >> 16) % 2000 - 1000) / 100.0f;
+  }
+  const sampling_t prm[SS] = {{1.0f, 1.0f, 1.0f, 0},  {0.8f, 0.95f, 1.1f, 50}, {0.6f, 0.8f, 1.3f, 0},
+                              {0.0f, 1.0f, 1.05f, 0}, {0.7f, 1e-9f, 1.0f, 3},  {1.0f, 1.0f, 1.0f, SV + 5}};
+  const int32_t hist[SS * SW] = {-1, -1, -1, -1, -1, 0,  300, 5,  5,  -1, 7,   7, 7, 301, 9,
+                                 12, 13, 14, 15, 16, -7, 1,   2,  3,  4,  300, 0, 1, 2,   3};
+  const float us[SS] = {0.0f, 0.5f, 0.999999f, 0.3f, 0.9f, 0.25f};
+  int32_t tok[SS], kept[SS];
+  if (vox_oracle_sample(SS, SV, logits, prm, hist, SW, us, tok, kept)) return 13;
+  for (int s = 0; s < SS; ++s)
+    if (tok[s] < 0 || tok[s] >= SV || kept[s] < 1 || kept[s] > SV) return 14;
+  if (kept[1] > 50 || kept[3] != 1 || kept[4] != 1 || kept[5] != SV) return 15;
+  if (vox_oracle_sample(SS, SV, logits, prm, NULL, 0, us, tok, NULL)) return 16;
+  free(logits);
   free(qm); free(km); free(vm); free(outm); free(lsem); free(rc); free(rs); free(qkv); free(qr);
   free(kp); free(vp); free(q); free(kn); free(vn); free(ko); free(vo); free(out); free(lse);
   puts("oracle sanitizer driver ok");

@@ -14,6 +14,7 @@ def test_oracle_runs_clean_under_asan_and_ubsan(tmp_path):
     cmd = ["gcc", "-O1", "-g", "-std=c11", "-fsanitize=address,undefined",
            "-fno-sanitize-recover=all", "-static-libasan", "-fopenmp",
            os.path.join(ROOT, "oracle", "vox_oracle.c"),
+           os.path.join(ROOT, "oracle", "vox_oracle_sample.c"),
            os.path.join(ROOT, "tests", "oracle_sanitizer_driver.c"), "-o", str(exe), "-lm"]
     build = subprocess.run(cmd, capture_output=True, text=True)
     if build.returncode != 0 and "asan" in build.stderr.lower():
