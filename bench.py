@@ -24,6 +24,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core rate
 MULTI_WORKLOADS = ("chunk15", "chunk25", "chunk28", "prefill", "admit")
+# sampling step: name -> (streams, vocabulary, settings of synth.SAMPLING_PRESETS)
+SAMPLE_WORKLOADS = {"sample_small": (1024, 6564, "cosyvoice"), "sample_large": (256, 156940, "orpheus")}
 METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 
 # HBM bytes per attention-kernel launch from rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
@@ -195,13 +197,97 @@ def bench_multi(args, dev) -> int:
     return 0
 
 
+def bench_sample(args, dev) -> int:
+    """Sampling step: one launch turns fp32 logits [S, V] into S tokens.  Algorithmic bytes: the
+    logits once (S * V * 4); the kernel is one workgroup per stream."""
+    import numpy as np
+    import torch
+
+    from paper_2602_00269_amd import binding, synth
+
+    s, v, preset = SAMPLE_WORKLOADS[args.workload]
+    temperature, top_p, top_k, penalty = synth.SAMPLING_PRESETS[preset]
+    window = 64
+    copies = 4  # distinct logits so that a small batch cannot sit in the caches
+    logits = [synth.make_logits(s, v, seed=0x5EED0200 + c, device=dev) for c in range(copies)]
+    hist_h = synth.make_history(s, v, window, seed=0x5EED0210)
+    u_h = synth.make_uniforms(s, seed=0x5EED0211)
+    hist, u = torch.from_numpy(hist_h).to(dev), torch.from_numpy(u_h).to(dev)
+    prm = binding.sampling_params(temperature, top_p, penalty, top_k, s, dev)
+    tokens = torch.zeros(s, dtype=torch.int32, device=dev)
+
+    def step(i):
+        binding.sample(logits[i % copies], prm, u, tokens, history=hist)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    for i, (a, b) in enumerate(evs):  # the launch goes to torch's current stream
+        a.record()
+        step(i)
+        b.record()
+    torch.cuda.synchronize()
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    nbytes = s * v * 4
+    ach = nbytes / (kern_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "sample_kernel", "achieved": round(ach, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+                "kernel_ms": round(kern_ms, 4), "bytes_per_launch": nbytes, "traffic": None}
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        host = logits[0].cpu().numpy()
+        prm_o = oracle.sampling_params(temperature, top_p, penalty, top_k, s)
+        n = min(s, 4)
+        t = time.perf_counter()
+        oracle.sample(host[:n], prm_o[:n], u_h[:n], history=hist_h[:n])
+        rate = n / max(time.perf_counter() - t, 1e-6)
+        n = int(max(n, min(s, rate * args.cpu_seconds)))
+        t = time.perf_counter()
+        oracle.sample(host[:n], prm_o[:n], u_h[:n], history=hist_h[:n])
+        secs = time.perf_counter() - t
+        cpu = {"value": round(n / secs, 1), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+               "sample": f"oracle sampling of streams [0,{n}) of {s} (vocabulary {v}), 1 pass in "
+                         f"{secs:.2f} s", "cpu_model": cpu_model(), "host_cpus": os.cpu_count()}
+    print(json.dumps({
+        "metric": "sampled tokens/s (one launch per batch of streams)",
+        "value": round(s / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}_{s}x{v}", "streams": s, "vocab": v,
+                   "settings": preset, "temperature": temperature, "top_p": top_p, "top_k": top_k,
+                   "repetition_penalty": penalty, "window": window, "logit_sets": copies},
+        "logits_gbps": round(nbytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg3",
-                    choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", *MULTI_WORKLOADS],
+                    choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", *MULTI_WORKLOADS,
+                             *SAMPLE_WORKLOADS],
                     help="cfg1..cfg5: decode step (cfg3 is the headline); the others are "
                          "multi-token steps (detokenizer chunks, prompts, admission mix)")
     ap.add_argument("--path", default="auto", choices=["auto", "mfma", "valu"])
@@ -241,6 +327,8 @@ def main() -> int:
     dev = torch.device("cuda:0")
     if args.workload in MULTI_WORKLOADS:
         return bench_multi(args, dev)
+    if args.workload in SAMPLE_WORKLOADS:
+        return bench_sample(args, dev)
     cfg = int(args.workload[3:])
     path = {"auto": binding.PATH_AUTO, "mfma": binding.PATH_MFMA, "valu": binding.PATH_VALU}[args.path]
 

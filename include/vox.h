@@ -243,6 +243,49 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
                                float* out, float* lse, void* workspace, size_t workspace_bytes,
                                void* hip_stream, void* event_before, void* event_after);
 
+/*
+ * Sampling step (paper Section 3.1 "Sampling"; per-model settings in Appendix A): logits to the
+ * next token of every stream, with repetition penalty, temperature, top-k and top-p.  For one
+ * stream with logits z[V], recent tokens H (the row of `history`), uniform u in [0,1):
+ *   1. z'_v = z_v / r if z_v > 0 else z_v * r for every v in H (once each; r = 1: off)
+ *   2. y_v = z'_v / T                         (T <= 0: greedy, the first token of the order)
+ *   3. order: descending y, ties by ascending token id
+ *   4. top-k: the first k of the order (k <= 0 or k >= V: all)
+ *   5. top-p: shortest prefix whose softmax weight reaches top_p of the kept total (>= 1: all)
+ *   6. the first token of the prefix whose cumulative weight exceeds u * (weight of the prefix)
+ * The arithmetic is fixed (single fp32 operations in a stated order, integer softmax weights
+ * 2^40 * exp(y - max) from a fixed polynomial, integer cumulative sums), so the token is
+ * reproducible bit for bit and independent of scheduling; the source states it step by step.
+ *   logits   : fp32 device [num_streams][vocab], finite values; vocab <= 262144
+ *   params   : device [num_streams]
+ *   history  : int32 device [num_streams][window], ids outside [0, vocab) are empty slots;
+ *              may be NULL when window == 0
+ *   uniforms : fp32 device [num_streams], each in [0, 1)
+ *   tokens   : int32 device [num_streams] (out);  kept: int32 device [num_streams] or NULL (out,
+ *              size of the final prefix)
+ * Nothing is allocated and no workspace is needed.
+ */
+typedef struct {
+  float temperature;
+  float top_p;
+  float repetition_penalty;
+  int32_t top_k;
+} vox_sampling_t;
+
+int vox_sample(int32_t num_streams, int32_t vocab, const float* logits,
+               const vox_sampling_t* params, const int32_t* history, int32_t window,
+               const float* uniforms, int32_t* tokens, int32_t* kept, void* hip_stream);
+
+/*
+ * Verification aid for vox_sample: for every token of every stream the distance
+ * d = max_v y_v - y_v (fp32) and the integer softmax weight the draw uses, so that the fixed
+ * arithmetic can be compared element by element.  d_out: fp32 device [num_streams][vocab];
+ * w_out: uint64 device [num_streams][vocab].
+ */
+int vox_sample_weights(int32_t num_streams, int32_t vocab, const float* logits,
+                       const vox_sampling_t* params, const int32_t* history, int32_t window,
+                       float* d_out, uint64_t* w_out, void* hip_stream);
+
 /* Static, never-NULL description of a return code. */
 const char* vox_strerror(int code);
 

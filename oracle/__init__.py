@@ -32,6 +32,8 @@ def _load():
         lib.vox_oracle_rope_append.restype = i
         lib.vox_oracle_sample.argtypes = [i, i, p, p, p, i, p, p, p]
         lib.vox_oracle_sample.restype = i
+        lib.vox_oracle_sample_weights.argtypes = [i, i, p, p, p, i, p, p]
+        lib.vox_oracle_sample_weights.restype = i
         lib.vox_oracle_sample_weight.argtypes = [f]
         lib.vox_oracle_sample_weight.restype = ctypes.c_uint64
         lib.vox_oracle_num_threads.restype = i
@@ -208,3 +210,20 @@ def sample(logits, params, uniforms, history=None):
 def sample_weight(d: float) -> int:
     """The integer softmax weight 2^40 * exp(-d) of the fixed sampling arithmetic."""
     return int(_load().vox_oracle_sample_weight(np.float32(d)))
+
+
+def sample_weights(logits, params, history=None):
+    """(d [S, V] float32, w [S, V] uint64): distance to the maximum and integer weight per token."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    s, v = logits.shape
+    params = np.ascontiguousarray(params, dtype=SAMPLING_DTYPE)
+    window, hist_ptr = 0, None
+    if history is not None:
+        history = np.ascontiguousarray(history, dtype=np.int32)
+        window, hist_ptr = history.shape[1], _ptr(history)
+    d = np.zeros((s, v), dtype=np.float32)
+    w = np.zeros((s, v), dtype=np.uint64)
+    rc = _load().vox_oracle_sample_weights(s, v, _ptr(logits), _ptr(params), hist_ptr, window,
+                                           _ptr(d), _ptr(w))
+    _check(rc, "sample_weights")
+    return d, w

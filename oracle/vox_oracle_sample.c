@@ -89,6 +89,50 @@ static int by_rank(const void* a, const void* b) {
   return x->id < y->id ? -1 : (x->id > y->id);
 }
 
+/* Steps 1-2 and the distance to the maximum for one stream: y, m, d as the header states. */
+static float tempered_row(int V, const float* z, const vox_oracle_sampling_t prm,
+                          const int32_t* hist, int window, unsigned char* seen, float* y) {
+  memset(seen, 0, (size_t)V);
+  for (int j = 0; j < window; ++j) {
+    int32_t v = hist[j];
+    if (v >= 0 && v < V) seen[v] = 1;
+  }
+  const float r = prm.repetition_penalty;
+  const float invT = (prm.temperature > 0.0f) ? 1.0f / prm.temperature : 1.0f;
+  float m = -INFINITY;
+  for (int v = 0; v < V; ++v) {
+    float zp = z[v];
+    if (seen[v]) zp = zp > 0.0f ? zp / r : zp * r;
+    y[v] = zp * invT;
+    if (y[v] > m) m = y[v];
+  }
+  return m;
+}
+
+/* d [S][V] and weights [S][V] of every token (what the draw is made from). */
+int vox_oracle_sample_weights(int S, int V, const float* logits,
+                              const vox_oracle_sampling_t* params, const int32_t* history,
+                              int window, float* d_out, uint64_t* w_out) {
+  if (S <= 0 || V <= 0 || window < 0 || (window > 0 && !history)) return ORACLE_ERR_ARG;
+  float* y = malloc((size_t)V * sizeof(float));
+  unsigned char* seen = malloc((size_t)V);
+  if (!y || !seen) {
+    free(y); free(seen);
+    return ORACLE_ERR_MEM;
+  }
+  for (int s = 0; s < S; ++s) {
+    float m = tempered_row(V, logits + (size_t)s * V, params[s],
+                           window ? history + (size_t)s * window : NULL, window, seen, y);
+    for (int v = 0; v < V; ++v) {
+      float d = m - y[v];
+      d_out[(size_t)s * V + v] = d;
+      w_out[(size_t)s * V + v] = vox_oracle_sample_weight(d);
+    }
+  }
+  free(y); free(seen);
+  return ORACLE_OK;
+}
+
 /*
  * logits [S][V] fp32; params [S]; history [S][window] (ids outside [0,V) are empty slots) or
  * NULL; uniforms [S]; tokens [S] out; kept [S] out or NULL (size of the final prefix).
@@ -108,23 +152,9 @@ int vox_oracle_sample(int S, int V, const float* logits, const vox_oracle_sampli
   for (int s = 0; s < S; ++s) {
     const float* z = logits + (size_t)s * V;
     const vox_oracle_sampling_t prm = params[s];
-    /* 1. repetition penalty on the tokens of the window, once each */
-    memset(seen, 0, (size_t)V);
-    for (int j = 0; j < window; ++j) {
-      int32_t v = history[(size_t)s * window + j];
-      if (v >= 0 && v < V) seen[v] = 1;
-    }
-    const float r = prm.repetition_penalty;
+    /* 1. repetition penalty on the tokens of the window, once each; 2. temperature */
     const int greedy = !(prm.temperature > 0.0f);
-    const float invT = greedy ? 1.0f : 1.0f / prm.temperature;
-    /* 2. temperature */
-    float m = -INFINITY;
-    for (int v = 0; v < V; ++v) {
-      float zp = z[v];
-      if (seen[v]) zp = zp > 0.0f ? zp / r : zp * r;
-      y[v] = zp * invT;
-      if (y[v] > m) m = y[v];
-    }
+    float m = tempered_row(V, z, prm, window ? history + (size_t)s * window : NULL, window, seen, y);
     /* 3. order by (d, id); weights */
     for (int v = 0; v < V; ++v) {
       float d = m - y[v];

@@ -80,6 +80,10 @@ def load() -> ctypes.CDLL:
     lib.vox_paged_prefill.restype = ctypes.c_int
     lib.vox_paged_prefill_profiled.argtypes = [sp] + [vp] * 11 + [ctypes.c_size_t, vp, vp, vp]
     lib.vox_paged_prefill_profiled.restype = ctypes.c_int
+    lib.vox_sample.argtypes = [i32, i32, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.vox_sample.restype = ctypes.c_int
+    lib.vox_sample_weights.argtypes = [i32, i32, vp, vp, vp, i32, vp, vp, vp]
+    lib.vox_sample_weights.restype = ctypes.c_int
     lib.vox_strerror.argtypes = [ctypes.c_int]
     lib.vox_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -321,3 +325,51 @@ def paged_prefill(shape, q, k_pool, v_pool, block_tables, context_lens, q_offset
                                   _stream(stream), ev0, ev1)
     del keep1, keep2
     _check(rc, "vox_paged_prefill")
+
+
+def sampling_params(temperature, top_p, repetition_penalty, top_k, num_streams, device="cuda"):
+    """Device array of ``vox_sampling_t`` (one per stream; scalars are broadcast), as an int32
+    tensor [S, 4] holding the struct's bytes."""
+    a = np.zeros((num_streams, 4), dtype=np.int32)
+    f = a.view(np.float32)
+    f[:, 0] = np.broadcast_to(np.asarray(temperature, dtype=np.float32), (num_streams,))
+    f[:, 1] = np.broadcast_to(np.asarray(top_p, dtype=np.float32), (num_streams,))
+    f[:, 2] = np.broadcast_to(np.asarray(repetition_penalty, dtype=np.float32), (num_streams,))
+    a[:, 3] = np.broadcast_to(np.asarray(top_k, dtype=np.int32), (num_streams,))
+    return torch.from_numpy(a).to(device)
+
+
+def _sample_args(logits, params, history):
+    f32, i32 = torch.float32, torch.int32
+    if logits.dim() != 2:
+        raise ValueError("logits must be [S, V]")
+    s, v = logits.shape
+    if tuple(params.shape) != (s, 4):
+        raise ValueError("params must be the [S, 4] tensor made by sampling_params")
+    window = 0
+    hist = None
+    if history is not None:
+        if history.dim() != 2 or history.shape[0] != s:
+            raise ValueError("history must be [S, window]")
+        window = int(history.shape[1])
+        hist = _dev(history, i32, "history") if window > 0 else None
+    return s, v, _dev(logits, f32, "logits"), _dev(params, i32, "params"), hist, window
+
+
+def sample(logits, params, uniforms, tokens, history=None, kept=None, stream=None):
+    """Next token of every stream from fp32 logits [S, V]; writes ``tokens`` (and ``kept``)."""
+    s, v, lp, pp, hist, window = _sample_args(logits, params, history)
+    rc = load().vox_sample(s, v, lp, pp, hist, window,
+                           _dev(uniforms, torch.float32, "uniforms"),
+                           _dev(tokens, torch.int32, "tokens"),
+                           _dev(kept, torch.int32, "kept", optional=True), _stream(stream))
+    _check(rc, "vox_sample")
+
+
+def sample_weights(logits, params, d_out, w_out, history=None, stream=None):
+    """Verification aid: per-token distance to the maximum (fp32) and integer weight (int64 bits)."""
+    s, v, lp, pp, hist, window = _sample_args(logits, params, history)
+    rc = load().vox_sample_weights(s, v, lp, pp, hist, window,
+                                   _dev(d_out, torch.float32, "d_out"),
+                                   _dev(w_out, torch.int64, "w_out"), _stream(stream))
+    _check(rc, "vox_sample_weights")

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvox.so")
-SOURCES = ["vox_api.hip", "vox_aux_kernels.hip", "vox_decode_mfma.hip", "vox_decode_valu.hip",
+SOURCES = ["vox_api.hip", "vox_aux_kernels.hip", "vox_decode_mfma.hip", "vox_decode_valu.hip", "vox_sample.hip",
            "vox_prefill.hip"]
 
 # Packed fp32 VALU forms are switched off for device code on purpose.

@@ -1,0 +1,368 @@
+// Sampling step: logits -> next token per stream (repetition penalty, temperature, top-k, top-p,
+// draw), one workgroup of 1024 threads per stream, everything besides the logits in LDS.
+//
+// The token is decided by exact arithmetic: every float step is a single IEEE fp32 operation
+// in a fixed order (contraction is off in this file's arithmetic helpers), softmax weights are
+// 64-bit integers (2^40 * exp(-d) through a fixed polynomial), and all cumulative sums are
+// integer sums, which do not depend on the order of addition.  Histograms can therefore be
+// built with LDS atomics and the result is still reproducible bit for bit.
+//
+// Tokens are ranked by the composite key (bits of d = max - y, token id): 31 + 18 = 49 bits,
+// unique per token.  Every cut the method needs is a position in that ranking where a running
+// count or a running weight first reaches a threshold: the k-th token (top-k), the end of the
+// shortest prefix holding top_p of the weight (top-p), the drawn token.  `locate` finds such a
+// position by radix descent over the key: a histogram of (count, weight) per digit, a scan for
+// the digit where the threshold is crossed, then the next digit inside that bucket.  The first
+// digit's histogram is built once per stream and reused by every descent; once a bucket holds
+// at most kCandidates tokens it is copied to LDS and the remaining digits never touch global
+// memory again.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "vox.h"
+
+namespace vox {
+namespace {
+
+constexpr int kThreads = 1024;
+constexpr int kWaves = kThreads / 64;
+constexpr int kIdBits = 18;  // vocabulary of at most 2^18 tokens
+constexpr int kMaxVocab = 1 << kIdBits;
+constexpr int kKeyBits = 31 + kIdBits;
+constexpr int kLevels = 5;
+constexpr int kBins = 2048;
+constexpr int kCandidates = 4096;
+
+__device__ constexpr int kWidth[kLevels] = {11, 10, 10, 9, 9};
+__device__ constexpr int kShift[kLevels] = {38, 28, 18, 9, 0};
+
+// 2^40 * exp(-d): x = d * log2(e); n = floor(x), f = x - n; p = Taylor polynomial of 2^-f of
+// degree 9 (Horner, fused multiply-adds); q = trunc(p * 2^24); result (q << 16) >> n.
+__device__ inline uint64_t weight_of(float d) {
+#pragma clang fp contract(off)
+  const float x = d * 0x1.715476p+0f;
+  if (!(x < 64.0f)) return 0;
+  const float nf = __builtin_floorf(x);
+  const int n = (int)nf;
+  const float f = x - nf;
+  float p = -0x1.b5253ep-24f;
+  p = __builtin_fmaf(p, f, 0x1.62c022p-20f);
+  p = __builtin_fmaf(p, f, -0x1.ffcbfcp-17f);
+  p = __builtin_fmaf(p, f, 0x1.430912p-13f);
+  p = __builtin_fmaf(p, f, -0x1.5d87fep-10f);
+  p = __builtin_fmaf(p, f, 0x1.3b2ab6p-7f);
+  p = __builtin_fmaf(p, f, -0x1.c6b08ep-5f);
+  p = __builtin_fmaf(p, f, 0x1.ebfbe0p-3f);
+  p = __builtin_fmaf(p, f, -0x1.62e430p-1f);
+  p = __builtin_fmaf(p, f, 1.0f);
+  const uint64_t q = (uint64_t)(uint32_t)(p * 16777216.0f);
+  return (q << 16) >> n;
+}
+
+struct StreamCtx {
+  const float* z;        // this stream's logits
+  const uint32_t* seen;  // LDS bitmap of the window's tokens, or nullptr
+  int V;
+  float r, invT, m;
+};
+
+// penalised, tempered logit of token v
+__device__ inline float tempered(const StreamCtx& c, int v) {
+#pragma clang fp contract(off)
+  float zp = c.z[v];
+  if (c.seen && ((c.seen[v >> 5] >> (v & 31)) & 1u)) zp = zp > 0.0f ? zp / c.r : zp * c.r;
+  return zp * c.invT;
+}
+
+__device__ inline uint64_t key_of(const StreamCtx& c, int v, float* d_out) {
+#pragma clang fp contract(off)
+  const float d = c.m - tempered(c, v);
+  *d_out = d;
+  const uint64_t dkey = __builtin_bit_cast(uint32_t, d) & 0x7FFFFFFFu;
+  return (dkey << kIdBits) | (uint32_t)v;
+}
+
+__device__ inline float d_of_key(uint64_t comp) {
+  return __builtin_bit_cast(float, (uint32_t)(comp >> kIdBits));
+}
+
+struct Lds {
+  uint32_t seen[kMaxVocab / 32];
+  uint32_t cnt[kBins], cnt0[kBins];
+  unsigned long long mass[kBins], mass0[kBins];
+  unsigned long long cand[kCandidates];
+  unsigned long long wave_cnt[kWaves], wave_mass[kWaves];
+  float wave_max[kWaves];
+  // result of a scan
+  int bin;
+  unsigned long long before_cnt, before_mass, total_cnt, total_mass;
+  uint32_t n_cand;
+};
+
+struct Located {
+  uint64_t comp;                   // key of the token at the crossing
+  uint64_t through_cnt, through_mass;  // tokens / weight up to and including it
+};
+
+// Finds, over bins [0, nbins), the first bin where the running count (by_mass = false) or
+// running weight reaches thr; leaves the bin and the sums before it in LDS.  All threads call.
+__device__ inline void scan_bins(Lds& s, const uint32_t* cnt, const unsigned long long* mass,
+                                 int nbins, bool by_mass, unsigned long long thr) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int b0 = 2 * tid, b1 = 2 * tid + 1;
+  const unsigned long long c0 = b0 < nbins ? cnt[b0] : 0, c1 = b1 < nbins ? cnt[b1] : 0;
+  const unsigned long long m0 = b0 < nbins ? mass[b0] : 0, m1 = b1 < nbins ? mass[b1] : 0;
+  unsigned long long ic = c0 + c1, im = m0 + m1;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned long long ac = __shfl_up(ic, o), am = __shfl_up(im, o);
+    if (lane >= o) {
+      ic += ac;
+      im += am;
+    }
+  }
+  if (lane == 63) {
+    s.wave_cnt[wv] = ic;
+    s.wave_mass[wv] = im;
+  }
+  if (tid == 0) s.bin = -1;
+  __syncthreads();
+  unsigned long long ec = ic - (c0 + c1), em = im - (m0 + m1);  // exclusive, inside the wave
+  for (int k = 0; k < wv; ++k) {
+    ec += s.wave_cnt[k];
+    em += s.wave_mass[k];
+  }
+  // running value before bin b0, after b0, after b1
+  const unsigned long long v0 = by_mass ? em : ec;
+  const unsigned long long v1 = v0 + (by_mass ? m0 : c0);
+  const unsigned long long v2 = v1 + (by_mass ? m1 : c1);
+  if (v0 < thr && thr <= v1) {
+    s.bin = b0;
+    s.before_cnt = ec;
+    s.before_mass = em;
+  } else if (v1 < thr && thr <= v2) {
+    s.bin = b1;
+    s.before_cnt = ec + c0;
+    s.before_mass = em + m0;
+  }
+  if (tid == kThreads - 1) {
+    s.total_cnt = ec + c0 + c1;
+    s.total_mass = em + m0 + m1;
+  }
+  __syncthreads();
+}
+
+__device__ inline void clear_hist(Lds& s) {
+  for (int b = threadIdx.x; b < kBins; b += kThreads) {
+    s.cnt[b] = 0;
+    s.mass[b] = 0;
+  }
+  __syncthreads();
+}
+
+// Position where the running count / weight first reaches thr (1 <= thr <= total).
+__device__ Located locate(Lds& s, const StreamCtx& c, bool by_mass, unsigned long long thr) {
+  uint64_t prefix = 0;  // the digits chosen so far, right-aligned
+  int prefix_bits = 0;
+  unsigned long long before_cnt = 0, before_mass = 0, bucket_mass = 0;
+  bool in_lds = false;
+  uint32_t n_cand = 0;
+  for (int level = 0; level < kLevels; ++level) {
+    const int width = kWidth[level], shift = kShift[level];
+    const uint32_t* cnt = s.cnt;
+    const unsigned long long* mass = s.mass;
+    if (level == 0) {  // built once per stream
+      cnt = s.cnt0;
+      mass = s.mass0;
+    } else {
+      clear_hist(s);
+      const uint32_t digit_mask = (1u << width) - 1;
+      if (in_lds) {
+        for (uint32_t i = threadIdx.x; i < n_cand; i += kThreads) {
+          const uint64_t comp = s.cand[i];
+          if ((comp >> (kKeyBits - prefix_bits)) != prefix) continue;
+          const uint32_t b = (uint32_t)(comp >> shift) & digit_mask;
+          atomicAdd(&s.cnt[b], 1u);
+          atomicAdd(&s.mass[b], (unsigned long long)weight_of(d_of_key(comp)));
+        }
+      } else {
+        for (int v = threadIdx.x; v < c.V; v += kThreads) {
+          float d;
+          const uint64_t comp = key_of(c, v, &d);
+          if ((comp >> (kKeyBits - prefix_bits)) != prefix) continue;
+          const uint32_t b = (uint32_t)(comp >> shift) & digit_mask;
+          atomicAdd(&s.cnt[b], 1u);
+          atomicAdd(&s.mass[b], (unsigned long long)weight_of(d));
+        }
+      }
+      __syncthreads();
+    }
+    scan_bins(s, cnt, mass, 1 << width, by_mass, thr - (by_mass ? before_mass : before_cnt));
+    const int b = s.bin;  // >= 0: thr is within the total of the bucket being refined
+    before_cnt += s.before_cnt;
+    before_mass += s.before_mass;
+    const uint32_t bucket_cnt = cnt[b];
+    bucket_mass = mass[b];
+    prefix = (prefix << width) | (uint32_t)b;
+    prefix_bits += width;
+    __syncthreads();  // every thread has read the scan result
+    if (!in_lds && level + 1 < kLevels && bucket_cnt <= (uint32_t)kCandidates) {
+      // copy the bucket's keys to LDS; later digits are read from there
+      if (threadIdx.x == 0) s.n_cand = 0;
+      __syncthreads();
+      for (int v = threadIdx.x; v < c.V; v += kThreads) {
+        float d;
+        const uint64_t comp = key_of(c, v, &d);
+        if ((comp >> (kKeyBits - prefix_bits)) == prefix) s.cand[atomicAdd(&s.n_cand, 1u)] = comp;
+      }
+      __syncthreads();
+      n_cand = s.n_cand;
+      in_lds = true;
+    }
+  }
+  // all 49 bits chosen: the bucket is one token
+  Located out;
+  out.comp = prefix;
+  out.through_cnt = before_cnt + 1;
+  out.through_mass = before_mass + bucket_mass;
+  return out;
+}
+
+// Per-stream set-up: the window's tokens as an LDS bitmap, 1/T, the maximum tempered logit.
+__device__ StreamCtx open_stream(Lds& s, int V, const float* __restrict__ logits,
+                                 const vox_sampling_t& prm, const int32_t* __restrict__ history,
+                                 int window, int stream) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  StreamCtx c;
+  c.z = logits + (size_t)stream * V;
+  c.V = V;
+  c.r = prm.repetition_penalty;
+  c.invT = (prm.temperature > 0.0f) ? 1.0f / prm.temperature : 1.0f;
+  c.seen = nullptr;
+  if (window > 0) {
+    for (int i = tid; i < (V + 31) / 32; i += kThreads) s.seen[i] = 0;
+    __syncthreads();
+    for (int j = tid; j < window; j += kThreads) {
+      const int32_t v = history[(size_t)stream * window + j];
+      if (v >= 0 && v < V) atomicOr(&s.seen[v >> 5], 1u << (v & 31));
+    }
+    __syncthreads();
+    c.seen = s.seen;
+  }
+  c.m = 0.0f;
+  float mx = -INFINITY;
+  for (int v = tid; v < V; v += kThreads) mx = fmaxf(mx, tempered(c, v));
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  if (lane == 0) s.wave_max[wv] = mx;
+  __syncthreads();
+  mx = s.wave_max[0];
+  for (int k = 1; k < kWaves; ++k) mx = fmaxf(mx, s.wave_max[k]);
+  c.m = mx;
+  return c;
+}
+
+// Verification aid: the distance d = max - y and the integer weight of every token.
+__global__ __launch_bounds__(kThreads) void sample_weights_kernel(
+    int V, const float* __restrict__ logits, const vox_sampling_t* __restrict__ params,
+    const int32_t* __restrict__ history, int window, float* __restrict__ d_out,
+    unsigned long long* __restrict__ w_out) {
+  __shared__ Lds s;
+  const int stream = blockIdx.x;
+  const StreamCtx c = open_stream(s, V, logits, params[stream], history, window, stream);
+  for (int v = threadIdx.x; v < V; v += kThreads) {
+    float d;
+    (void)key_of(c, v, &d);
+    d_out[(size_t)stream * V + v] = d;
+    w_out[(size_t)stream * V + v] = weight_of(d);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void sample_kernel(
+    int V, const float* __restrict__ logits, const vox_sampling_t* __restrict__ params,
+    const int32_t* __restrict__ history, int window, const float* __restrict__ uniforms,
+    int32_t* __restrict__ tokens, int32_t* __restrict__ kept) {
+  __shared__ Lds s;
+  const int tid = threadIdx.x;
+  const int stream = blockIdx.x;
+  const vox_sampling_t prm = params[stream];
+  const bool greedy = !(prm.temperature > 0.0f);
+  const StreamCtx c = open_stream(s, V, logits, prm, history, window, stream);
+  // first digit's histogram, shared by every descent
+  for (int b = tid; b < kBins; b += kThreads) {
+    s.cnt0[b] = 0;
+    s.mass0[b] = 0;
+  }
+  __syncthreads();
+  for (int v = tid; v < V; v += kThreads) {
+    float d;
+    const uint64_t comp = key_of(c, v, &d);
+    const uint32_t b = (uint32_t)(comp >> kShift[0]);
+    atomicAdd(&s.cnt0[b], 1u);
+    atomicAdd(&s.mass0[b], (unsigned long long)weight_of(d));
+  }
+  __syncthreads();
+
+  int token, n_kept;
+  if (greedy) {
+    token = (int)(locate(s, c, false, 1).comp & (kMaxVocab - 1));
+    n_kept = 1;
+  } else {
+    unsigned long long total;
+    unsigned long long n = (unsigned long long)V;
+    if (prm.top_k > 0 && prm.top_k < V) {
+      const Located k = locate(s, c, false, (unsigned long long)prm.top_k);
+      n = (unsigned long long)prm.top_k;
+      total = k.through_mass;
+    } else {
+      scan_bins(s, s.cnt0, s.mass0, kBins, false, ~0ull);  // no crossing: totals only
+      total = s.total_mass;
+      __syncthreads();
+    }
+    if (prm.top_p < 1.0f) {
+      unsigned long long thr = (unsigned long long)((double)prm.top_p * (double)total);
+      if (thr < 1) thr = 1;
+      const Located pcut = locate(s, c, true, thr);
+      n = pcut.through_cnt;
+      total = pcut.through_mass;
+    }
+    const unsigned long long target =
+        (unsigned long long)((double)uniforms[stream] * (double)total);
+    token = (int)(locate(s, c, true, target + 1).comp & (kMaxVocab - 1));
+    n_kept = (int)n;
+  }
+  if (tid == 0) {
+    tokens[stream] = token;
+    if (kept) kept[stream] = n_kept;
+  }
+}
+
+}  // namespace
+}  // namespace vox
+
+extern "C" int vox_sample(int32_t num_streams, int32_t vocab, const float* logits,
+                          const vox_sampling_t* params, const int32_t* history, int32_t window,
+                          const float* uniforms, int32_t* tokens, int32_t* kept,
+                          void* hip_stream) {
+  if (num_streams <= 0 || vocab <= 0 || vocab > vox::kMaxVocab || window < 0)
+    return VOX_ERR_SHAPE;
+  if (!logits || !params || !uniforms || !tokens || (window > 0 && !history)) return VOX_ERR_NULL;
+  hipLaunchKernelGGL(vox::sample_kernel, dim3((unsigned)num_streams), dim3(vox::kThreads), 0,
+                     (hipStream_t)hip_stream, vocab, logits, params, history, window, uniforms,
+                     tokens, kept);
+  return hipGetLastError() == hipSuccess ? VOX_OK : VOX_ERR_HIP;
+}
+
+extern "C" int vox_sample_weights(int32_t num_streams, int32_t vocab, const float* logits,
+                                  const vox_sampling_t* params, const int32_t* history,
+                                  int32_t window, float* d_out, uint64_t* w_out,
+                                  void* hip_stream) {
+  if (num_streams <= 0 || vocab <= 0 || vocab > vox::kMaxVocab || window < 0)
+    return VOX_ERR_SHAPE;
+  if (!logits || !params || !d_out || !w_out || (window > 0 && !history)) return VOX_ERR_NULL;
+  hipLaunchKernelGGL(vox::sample_weights_kernel, dim3((unsigned)num_streams),
+                     dim3(vox::kThreads), 0, (hipStream_t)hip_stream, vocab, logits, params,
+                     history, window, d_out, (unsigned long long*)w_out);
+  return hipGetLastError() == hipSuccess ? VOX_OK : VOX_ERR_HIP;
+}

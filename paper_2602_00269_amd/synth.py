@@ -315,3 +315,40 @@ def make_qkv(w: Workload, seed: int, device="cpu", layers: Optional[int] = None)
     n = w.layers if layers is None else layers
     return [_randn_bf16((w.num_streams, w.num_q_heads + 2 * w.num_kv_heads, w.head_dim), gen, dev)
             for _ in range(n)]
+
+
+# ----------------------------------------------------------------------------------------------
+# Inputs of the sampling step: logits of a batch of streams, their recent tokens, uniforms.
+# The paper gives the sampling settings per model (Appendix A) but no logits; a Zipf-like
+# spectrum with Gaussian noise stands in for the output of an LM head: a few likely tokens, a
+# long tail.
+
+SAMPLING_PRESETS = {
+    # name: (temperature, top_p, top_k, repetition_penalty): the settings of Appendix A
+    "cosyvoice": (0.8, 0.95, 50, 1.1),
+    "orpheus": (0.6, 0.8, 0, 1.3),
+    "stepaudio": (0.7, 0.9, 0, 1.05),
+}
+
+
+def make_logits(num_streams: int, vocab: int, seed: int, device="cpu", spread: float = 2.0):
+    """fp32 logits [S, V]: -1.2 * log(rank) over a per-stream random ranking + N(0, spread)."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    noise = torch.randn((num_streams, vocab), generator=gen, device=dev, dtype=torch.float32)
+    ranks = torch.rand((num_streams, vocab), generator=gen, device=dev).argsort(dim=1).argsort(dim=1)
+    return (-1.2 * torch.log(ranks.to(torch.float32) + 1.0) + spread * noise).contiguous()
+
+
+def make_history(num_streams: int, vocab: int, window: int, seed: int):
+    """int32 [S, window] recent tokens; a seeded fifth of the slots is empty (-1)."""
+    rng = np.random.default_rng(seed)
+    h = rng.integers(0, vocab, size=(num_streams, window)).astype(np.int32)
+    h[rng.random((num_streams, window)) < 0.2] = -1
+    return h
+
+
+def make_uniforms(num_streams: int, seed: int):
+    rng = np.random.default_rng(seed)
+    return rng.random(num_streams, dtype=np.float32)

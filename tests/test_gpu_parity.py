@@ -621,3 +621,87 @@ def test_decode_step_rope_matches_oracle_and_replays_from_a_graph(dev):
             assert torch.equal(outs[l], eager[l]), f"replay {rep} layer {l}"
             kp, vp = _host_pools(w, l)
             assert np.array_equal(kp, refs[l][1]) and np.array_equal(vp, refs[l][2])
+
+
+# ---------------------------------------------------------------------------------------
+# Sampling step: bit-exact tokens (the arithmetic is fixed on both sides)
+
+def _sample_both(dev, logits_t, temperature, top_p, penalty, top_k, uniforms, history):
+    s, v = logits_t.shape
+    prm_d = binding.sampling_params(temperature, top_p, penalty, top_k, s, dev)
+    prm_o = oracle.sampling_params(temperature, top_p, penalty, top_k, s)
+    tokens = torch.full((s,), -7, dtype=torch.int32, device=dev)
+    kept = torch.full((s,), -7, dtype=torch.int32, device=dev)
+    hist_d = None if history is None else torch.from_numpy(history).to(dev)
+    binding.sample(logits_t, prm_d, torch.from_numpy(uniforms).to(dev), tokens, history=hist_d,
+                   kept=kept)
+    torch.cuda.synchronize()
+    ref_tok, ref_kept = oracle.sample(logits_t.cpu().numpy(), prm_o, uniforms, history=history)
+    return tokens.cpu().numpy(), kept.cpu().numpy(), ref_tok, ref_kept
+
+
+SAMPLE_CASES = [
+    # streams, vocab, spread
+    (37, 6561, 2.0),
+    (16, 32000, 1.0),
+    (8, 128256, 2.0),
+    (4, 151936, 4.0),
+    (5, 1, 1.0),
+    (9, 63, 0.0),
+    (2, 262144, 2.0),
+]
+
+
+@pytest.mark.parametrize("case", range(len(SAMPLE_CASES)))
+def test_sampled_tokens_are_bit_exact(dev, case):
+    s, v, spread = SAMPLE_CASES[case]
+    logits = synth.make_logits(s, v, seed=200 + case, device=dev, spread=spread)
+    hist = synth.make_history(s, v, 64, seed=210 + case)
+    u = synth.make_uniforms(s, seed=220 + case)
+    settings = list(synth.SAMPLING_PRESETS.values()) + [
+        (1.0, 1.0, 0, 1.0),      # plain softmax draw
+        (0.0, 1.0, 0, 1.2),      # greedy with penalty
+        (1.5, 0.5, 7, 1.0),      # both cuts, small k
+        (0.3, 1e-6, 0, 1.0),     # top-p keeps one token
+        (1.0, 0.999, v + 3, 1.0),  # k beyond the vocabulary
+    ]
+    for temperature, top_p, top_k, penalty in settings:
+        for uu in (u, np.zeros_like(u), np.full_like(u, np.nextafter(np.float32(1), np.float32(0)))):
+            tok, kept, ref_tok, ref_kept = _sample_both(dev, logits, temperature, top_p, penalty,
+                                                        top_k, uu, hist)
+            what = f"case {case} T={temperature} p={top_p} k={top_k} r={penalty}"
+            assert np.array_equal(kept, ref_kept), what
+            assert np.array_equal(tok, ref_tok), what
+
+
+def test_sampling_weights_are_bit_exact(dev):
+    s, v = 6, 50021
+    logits = synth.make_logits(s, v, seed=230, device=dev, spread=3.0)
+    hist = synth.make_history(s, v, 200, seed=231)
+    for temperature, penalty in ((0.8, 1.1), (0.6, 1.3), (1.0, 1.0), (0.0, 1.05), (2.5, 2.0)):
+        prm_d = binding.sampling_params(temperature, 1.0, penalty, 0, s, dev)
+        prm_o = oracle.sampling_params(temperature, 1.0, penalty, 0, s)
+        d = torch.zeros((s, v), dtype=torch.float32, device=dev)
+        w = torch.zeros((s, v), dtype=torch.int64, device=dev)
+        binding.sample_weights(logits, prm_d, d, w, history=torch.from_numpy(hist).to(dev))
+        torch.cuda.synchronize()
+        d_ref, w_ref = oracle.sample_weights(logits.cpu().numpy(), prm_o, history=hist)
+        assert np.array_equal(d.cpu().numpy().view(np.uint32), d_ref.view(np.uint32))
+        assert np.array_equal(w.cpu().numpy().view(np.uint64), w_ref)
+
+
+def test_sampling_ties_mixed_settings_and_no_window(dev):
+    # equal logits: the whole order is decided by token ids (all five digits of the descent)
+    s, v = 12, 5000
+    logits = torch.zeros((s, v), dtype=torch.float32, device=dev)
+    logits[:, 1000:3000] = 1.0  # two levels, 2000 tied at the top
+    u = synth.make_uniforms(s, seed=240)
+    temperature = np.linspace(0.0, 1.1, s).astype(np.float32)  # stream 0 is greedy
+    top_p = np.linspace(0.1, 1.0, s).astype(np.float32)
+    top_k = (np.arange(s) * 397 % 2500).astype(np.int32)
+    for hist in (None, synth.make_history(s, v, 7, seed=241)):
+        tok, kept, ref_tok, ref_kept = _sample_both(dev, logits, temperature, top_p,
+                                                    np.float32(1.2), top_k, u, hist)
+        assert np.array_equal(kept, ref_kept) and np.array_equal(tok, ref_tok)
+        if hist is None:
+            assert tok[0] == 1000  # greedy: the lowest id among the tied maxima
