@@ -15,7 +15,10 @@
 // the digit where the threshold is crossed, then the next digit inside that bucket.  The first
 // digit's histogram is built once per stream and reused by every descent; once a bucket holds
 // at most kCandidates tokens it is copied to LDS and the remaining digits never touch global
-// memory again.
+// memory again.  That is the general path.  Usually the cuts all lie among a few thousand
+// tokens next to the maximum: the fast path in sample_kernel buckets tokens by distance,
+// copies everything up to the first cut's bucket to LDS in one pass, sorts it there and reads
+// the cuts off the running sums.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -67,20 +70,40 @@ struct StreamCtx {
   float r, invT, m;
 };
 
-// penalised, tempered logit of token v
-__device__ inline float tempered(const StreamCtx& c, int v) {
+// penalised, tempered logit of token v whose raw logit is z
+__device__ inline float tempered(const StreamCtx& c, int v, float z) {
 #pragma clang fp contract(off)
-  float zp = c.z[v];
+  float zp = z;
   if (c.seen && ((c.seen[v >> 5] >> (v & 31)) & 1u)) zp = zp > 0.0f ? zp / c.r : zp * c.r;
   return zp * c.invT;
 }
 
-__device__ inline uint64_t key_of(const StreamCtx& c, int v, float* d_out) {
+__device__ inline uint64_t key_of(const StreamCtx& c, int v, float z, float* d_out) {
 #pragma clang fp contract(off)
-  const float d = c.m - tempered(c, v);
+  const float d = c.m - tempered(c, v, z);
   *d_out = d;
   const uint64_t dkey = __builtin_bit_cast(uint32_t, d) & 0x7FFFFFFFu;
   return (dkey << kIdBits) | (uint32_t)v;
+}
+
+// Calls f(v, z[v]) for every token of the stream, this thread's share; the logits of kAhead
+// tokens are loaded before any of them is used, so the loads overlap.
+constexpr int kAhead = 8;
+template <class F>
+__device__ inline void for_each_token(const StreamCtx& c, F f) {
+  for (int v0 = threadIdx.x; v0 < c.V; v0 += kThreads * kAhead) {
+    float z[kAhead];
+#pragma unroll
+    for (int e = 0; e < kAhead; ++e) {
+      const int v = v0 + e * kThreads;
+      z[e] = v < c.V ? c.z[v] : 0.0f;
+    }
+#pragma unroll
+    for (int e = 0; e < kAhead; ++e) {
+      const int v = v0 + e * kThreads;
+      if (v < c.V) f(v, z[e]);
+    }
+  }
 }
 
 __device__ inline float d_of_key(uint64_t comp) {
@@ -90,7 +113,7 @@ __device__ inline float d_of_key(uint64_t comp) {
 struct Lds {
   uint32_t seen[kMaxVocab / 32];
   uint32_t cnt[kBins], cnt0[kBins];
-  unsigned long long mass[kBins], mass0[kBins];
+  unsigned long long mass[2 * kBins];  // [0, kBins): histogram in use; [kBins, 2 kBins): level 0
   unsigned long long cand[kCandidates];
   unsigned long long wave_cnt[kWaves], wave_mass[kWaves];
   float wave_max[kWaves];
@@ -174,7 +197,7 @@ __device__ Located locate(Lds& s, const StreamCtx& c, bool by_mass, unsigned lon
     const unsigned long long* mass = s.mass;
     if (level == 0) {  // built once per stream
       cnt = s.cnt0;
-      mass = s.mass0;
+      mass = s.mass + kBins;
     } else {
       clear_hist(s);
       const uint32_t digit_mask = (1u << width) - 1;
@@ -187,14 +210,14 @@ __device__ Located locate(Lds& s, const StreamCtx& c, bool by_mass, unsigned lon
           atomicAdd(&s.mass[b], (unsigned long long)weight_of(d_of_key(comp)));
         }
       } else {
-        for (int v = threadIdx.x; v < c.V; v += kThreads) {
+        for_each_token(c, [&](int v, float z) {
           float d;
-          const uint64_t comp = key_of(c, v, &d);
-          if ((comp >> (kKeyBits - prefix_bits)) != prefix) continue;
+          const uint64_t comp = key_of(c, v, z, &d);
+          if ((comp >> (kKeyBits - prefix_bits)) != prefix) return;
           const uint32_t b = (uint32_t)(comp >> shift) & digit_mask;
           atomicAdd(&s.cnt[b], 1u);
           atomicAdd(&s.mass[b], (unsigned long long)weight_of(d));
-        }
+        });
       }
       __syncthreads();
     }
@@ -211,11 +234,11 @@ __device__ Located locate(Lds& s, const StreamCtx& c, bool by_mass, unsigned lon
       // copy the bucket's keys to LDS; later digits are read from there
       if (threadIdx.x == 0) s.n_cand = 0;
       __syncthreads();
-      for (int v = threadIdx.x; v < c.V; v += kThreads) {
+      for_each_token(c, [&](int v, float z) {
         float d;
-        const uint64_t comp = key_of(c, v, &d);
+        const uint64_t comp = key_of(c, v, z, &d);
         if ((comp >> (kKeyBits - prefix_bits)) == prefix) s.cand[atomicAdd(&s.n_cand, 1u)] = comp;
-      }
+      });
       __syncthreads();
       n_cand = s.n_cand;
       in_lds = true;
@@ -252,7 +275,7 @@ __device__ StreamCtx open_stream(Lds& s, int V, const float* __restrict__ logits
   }
   c.m = 0.0f;
   float mx = -INFINITY;
-  for (int v = tid; v < V; v += kThreads) mx = fmaxf(mx, tempered(c, v));
+  for_each_token(c, [&](int v, float z) { mx = fmaxf(mx, tempered(c, v, z)); });
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
   if (lane == 0) s.wave_max[wv] = mx;
@@ -271,12 +294,91 @@ __global__ __launch_bounds__(kThreads) void sample_weights_kernel(
   __shared__ Lds s;
   const int stream = blockIdx.x;
   const StreamCtx c = open_stream(s, V, logits, params[stream], history, window, stream);
-  for (int v = threadIdx.x; v < V; v += kThreads) {
+  for_each_token(c, [&](int v, float z) {
     float d;
-    (void)key_of(c, v, &d);
+    (void)key_of(c, v, z, &d);
     d_out[(size_t)stream * V + v] = d;
     w_out[(size_t)stream * V + v] = weight_of(d);
+  });
+}
+
+// Level-0 histogram of the radix descent (digits of the key), for the general path.
+__device__ void build_key_histogram(Lds& s, const StreamCtx& c) {
+  for (int b = threadIdx.x; b < kBins; b += kThreads) {
+    s.cnt0[b] = 0;
+    s.mass[kBins + b] = 0;
   }
+  __syncthreads();
+  for_each_token(c, [&](int v, float z) {
+    float d;
+    const uint64_t comp = key_of(c, v, z, &d);
+    const uint32_t b = (uint32_t)(comp >> kShift[0]);
+    atomicAdd(&s.cnt0[b], 1u);
+    const unsigned long long w = weight_of(d);
+    if (w) atomicAdd(&s.mass[kBins + b], w);
+  });
+  __syncthreads();
+}
+
+// General path: every cut by radix descent over the whole vocabulary.
+__device__ void sample_general(Lds& s, const StreamCtx& c, const vox_sampling_t& prm, bool greedy,
+                               float u, int* token, int* n_kept) {
+  build_key_histogram(s, c);
+  if (greedy) {
+    *token = (int)(locate(s, c, false, 1).comp & (kMaxVocab - 1));
+    *n_kept = 1;
+    return;
+  }
+  unsigned long long total;
+  unsigned long long n = (unsigned long long)c.V;
+  if (prm.top_k > 0 && prm.top_k < c.V) {
+    const Located k = locate(s, c, false, (unsigned long long)prm.top_k);
+    n = (unsigned long long)prm.top_k;
+    total = k.through_mass;
+  } else {
+    scan_bins(s, s.cnt0, s.mass + kBins, kBins, false, ~0ull);  // no crossing: totals only
+    total = s.total_mass;
+    __syncthreads();
+  }
+  if (prm.top_p < 1.0f) {
+    unsigned long long thr = (unsigned long long)((double)prm.top_p * (double)total);
+    if (thr < 1) thr = 1;
+    const Located pcut = locate(s, c, true, thr);
+    n = pcut.through_cnt;
+    total = pcut.through_mass;
+  }
+  const unsigned long long target = (unsigned long long)((double)u * (double)total);
+  *token = (int)(locate(s, c, true, target + 1).comp & (kMaxVocab - 1));
+  *n_kept = (int)n;
+}
+
+// Fast path.  The cuts almost always lie among the few tokens next to the maximum.  In the same
+// pass that adds up every token's weight, the tokens with d < kNearRange are bucketed by
+// distance (64 buckets per unit of d) and copied to LDS.  If there are at most kSuperset of
+// them and the first cut that is needed (top-k by count, else top-p, else the draw itself, by
+// weight) falls inside their buckets, every later cut does too (each lies at or before the
+// previous one): the copies are sorted by key and the cuts are searches in the running sums of
+// their weights.  Otherwise the general path starts over.
+constexpr float kBucketsPerUnit = 64.0f;
+constexpr float kNearRange = 8.0f;
+constexpr int kNearBuckets = 512;  // kNearRange * kBucketsPerUnit
+constexpr float kCountRange = 32.0f;  // kBins / kBucketsPerUnit: counts are kept out to here
+constexpr int kSuperset = 4096;
+
+__device__ inline int bucket_of(float d) { return (int)(d * kBucketsPerUnit); }  // d in [0, 32)
+
+// First index i in [0, n) with cum[i] >= thr (n if none).
+__device__ inline int first_reaching(const unsigned long long* cum, int n,
+                                     unsigned long long thr) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (cum[mid] >= thr)
+      hi = mid;
+    else
+      lo = mid + 1;
+  }
+  return lo;
 }
 
 __global__ __launch_bounds__(kThreads) void sample_kernel(
@@ -284,53 +386,169 @@ __global__ __launch_bounds__(kThreads) void sample_kernel(
     const int32_t* __restrict__ history, int window, const float* __restrict__ uniforms,
     int32_t* __restrict__ tokens, int32_t* __restrict__ kept) {
   __shared__ Lds s;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int stream = blockIdx.x;
   const vox_sampling_t prm = params[stream];
   const bool greedy = !(prm.temperature > 0.0f);
+  const float u = uniforms[stream];
   const StreamCtx c = open_stream(s, V, logits, prm, history, window, stream);
-  // first digit's histogram, shared by every descent
-  for (int b = tid; b < kBins; b += kThreads) {
+  // One pass over the logits: tokens within kNearRange of the maximum go into the bucket
+  // histogram and into the candidate list, all others only add to the thread's weight total
+  // (and, when a top-k cut is wanted, to the bucket counts out to kCountRange, since the k-th
+  // token of a peaked distribution can lie farther out than the near range).
+  const bool use_k = !greedy && prm.top_k > 0 && prm.top_k < V;
+  const bool use_p = !greedy && prm.top_p < 1.0f;
+  const int count_buckets = use_k ? kBins : kNearBuckets;
+  for (int b = tid; b < count_buckets; b += kThreads) {
     s.cnt0[b] = 0;
-    s.mass0[b] = 0;
+    s.mass[kBins + b] = 0;  // only the near buckets receive weight
   }
+  if (tid == 0) s.n_cand = 0;
   __syncthreads();
-  for (int v = tid; v < V; v += kThreads) {
+  unsigned long long far_mass = 0;
+  for_each_token(c, [&](int v, float z) {
     float d;
-    const uint64_t comp = key_of(c, v, &d);
-    const uint32_t b = (uint32_t)(comp >> kShift[0]);
-    atomicAdd(&s.cnt0[b], 1u);
-    atomicAdd(&s.mass0[b], (unsigned long long)weight_of(d));
-  }
-  __syncthreads();
-
-  int token, n_kept;
-  if (greedy) {
-    token = (int)(locate(s, c, false, 1).comp & (kMaxVocab - 1));
-    n_kept = 1;
-  } else {
-    unsigned long long total;
-    unsigned long long n = (unsigned long long)V;
-    if (prm.top_k > 0 && prm.top_k < V) {
-      const Located k = locate(s, c, false, (unsigned long long)prm.top_k);
-      n = (unsigned long long)prm.top_k;
-      total = k.through_mass;
+    const uint64_t comp = key_of(c, v, z, &d);
+    const unsigned long long w = weight_of(d);
+    if (d < kNearRange) {
+      const int b = bucket_of(d);
+      atomicAdd(&s.cnt0[b], 1u);
+      atomicAdd(&s.mass[kBins + b], w);
+      const uint32_t slot = atomicAdd(&s.n_cand, 1u);
+      if (slot < (uint32_t)kSuperset) s.cand[slot] = comp;
     } else {
-      scan_bins(s, s.cnt0, s.mass0, kBins, false, ~0ull);  // no crossing: totals only
-      total = s.total_mass;
-      __syncthreads();
+      far_mass += w;
+      if (use_k && d < kCountRange) atomicAdd(&s.cnt0[bucket_of(d)], 1u);
     }
-    if (prm.top_p < 1.0f) {
-      unsigned long long thr = (unsigned long long)((double)prm.top_p * (double)total);
+  });
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) far_mass += __shfl_xor(far_mass, o);
+  if (lane == 0) s.wave_cnt[wv] = far_mass;
+  __syncthreads();
+  far_mass = 0;
+  for (int k = 0; k < kWaves; ++k) far_mass += s.wave_cnt[k];
+  uint32_t n_near = s.n_cand;
+  __syncthreads();
+  // the first cut that is needed: top-k by count, else top-p, else the draw itself, by weight
+  scan_bins(s, s.cnt0, s.mass + kBins, count_buckets, false,
+            greedy ? 1ull : use_k ? (unsigned long long)prm.top_k : ~0ull);
+  int last_bucket = s.bin;
+  const unsigned long long n_sup = last_bucket >= 0 ? s.before_cnt + s.cnt0[last_bucket] : 0;
+  bool fast = n_near <= (uint32_t)kSuperset &&
+              (!(greedy || use_k) || (last_bucket >= 0 && n_sup <= (unsigned long long)kSuperset));
+  const unsigned long long all_mass = s.total_mass + far_mass;  // the whole vocabulary
+  __syncthreads();
+  if (fast && !greedy && !use_k) {
+    unsigned long long thr;
+    if (use_p) {
+      thr = (unsigned long long)((double)prm.top_p * (double)all_mass);
       if (thr < 1) thr = 1;
-      const Located pcut = locate(s, c, true, thr);
-      n = pcut.through_cnt;
-      total = pcut.through_mass;
+    } else {
+      thr = (unsigned long long)((double)u * (double)all_mass) + 1;
     }
-    const unsigned long long target =
-        (unsigned long long)((double)uniforms[stream] * (double)total);
-    token = (int)(locate(s, c, true, target + 1).comp & (kMaxVocab - 1));
-    n_kept = (int)n;
+    scan_bins(s, s.cnt0, s.mass + kBins, kNearBuckets, true, thr);
+    fast = s.bin >= 0;
+    last_bucket = s.bin;
+    __syncthreads();
+  }
+  if (fast && last_bucket >= kNearBuckets) {
+    // the k-th token lies beyond the near range: one more pass adds the tokens between the
+    // near range and its bucket to the candidates
+    for_each_token(c, [&](int v, float z) {
+      float d;
+      const uint64_t comp = key_of(c, v, z, &d);
+      if (d >= kNearRange && d < kCountRange && bucket_of(d) <= last_bucket)
+        s.cand[atomicAdd(&s.n_cand, 1u)] = comp;
+    });
+    __syncthreads();
+    n_near = s.n_cand;  // = n_sup
+    __syncthreads();
+  }
+
+  int token = 0, n_kept = 1;
+  if (!fast) {
+    sample_general(s, c, prm, greedy, u, &token, &n_kept);
+  } else {
+    // keep the tokens up to the first cut's bucket (all later cuts lie among them), pad to a
+    // power of two, sort by key; the histogram array is free now and takes the kept keys
+    unsigned long long* keys = s.mass;
+    if (tid == 0) s.n_cand = 0;
+    __syncthreads();
+    for (uint32_t i = tid; i < n_near; i += kThreads) {
+      const unsigned long long comp = s.cand[i];
+      if (bucket_of(d_of_key(comp)) <= last_bucket) keys[atomicAdd(&s.n_cand, 1u)] = comp;
+    }
+    __syncthreads();
+    const int m = (int)s.n_cand;
+    int np2 = 64;
+    while (np2 < m) np2 <<= 1;
+    for (int i = m + tid; i < np2; i += kThreads) keys[i] = ~0ull;
+    __syncthreads();
+    for (int k = 2; k <= np2; k <<= 1) {
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        for (int t = tid; t < np2 / 2; t += kThreads) {
+          const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));  // lower index of the pair
+          const int p = i | j;
+          const bool up = (i & k) == 0;
+          const unsigned long long x = keys[i], y = keys[p];
+          if ((x > y) == up) {
+            keys[i] = y;
+            keys[p] = x;
+          }
+        }
+        __syncthreads();
+      }
+    }
+    // running sums of the sorted weights, in the candidate array (its keys were moved)
+    unsigned long long* cum = s.cand;
+    constexpr int kPer = kSuperset / kThreads;  // 4 consecutive entries per thread
+    unsigned long long w4[kPer], run = 0;
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+      const int i = tid * kPer + e;
+      w4[e] = i < m ? weight_of(d_of_key(keys[i])) : 0;
+      run += w4[e];
+    }
+    unsigned long long inc = run;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const unsigned long long a = __shfl_up(inc, o);
+      if (lane >= o) inc += a;
+    }
+    if (lane == 63) s.wave_mass[wv] = inc;
+    __syncthreads();
+    unsigned long long base = inc - run;
+    for (int k = 0; k < wv; ++k) base += s.wave_mass[k];
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+      base += w4[e];
+      cum[tid * kPer + e] = base;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      if (greedy) {
+        token = (int)(keys[0] & (kMaxVocab - 1));
+        n_kept = 1;
+      } else {
+        unsigned long long total = all_mass;
+        long long n = V;
+        if (use_k) {  // top_k <= m: the count crossing was found among the near tokens
+          n = prm.top_k;
+          total = cum[prm.top_k - 1];
+        }
+        if (use_p) {
+          unsigned long long thr = (unsigned long long)((double)prm.top_p * (double)total);
+          if (thr < 1) thr = 1;
+          const int j = first_reaching(cum, m, thr);  // < m: the crossing is among the near tokens
+          n = j + 1;
+          total = cum[j];
+        }
+        const unsigned long long target = (unsigned long long)((double)u * (double)total);
+        const int i = first_reaching(cum, m, target + 1);
+        token = (int)(keys[i] & (kMaxVocab - 1));
+        n_kept = (int)n;
+      }
+    }
   }
   if (tid == 0) {
     tokens[stream] = token;

@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"vox_kv_append", "vox_kv_gather", "vox_paged_decode", "vox_decode_step",
             "vox_paged_decode_workspace_bytes", "vox_paged_decode_profiled", "vox_strerror",
             "vox_kv_append_multi", "vox_paged_prefill", "vox_paged_prefill_profiled",
-            "vox_paged_prefill_workspace_bytes", "vox_rope_append", "vox_decode_step_rope"} <= set(names)
+            "vox_paged_prefill_workspace_bytes", "vox_rope_append", "vox_decode_step_rope", "vox_sample", "vox_sample_weights"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -127,6 +127,18 @@ def test_rope_calls_validate_on_the_host(lib):
                                     one, None, one, one, 1 << 20, None) == -5
     assert lib.vox_decode_step_rope(ctypes.byref(sh), 1, None, one, one, 256, one, one, one, one,
                                     one, None, one, one, 1 << 20, None) == -1
+
+
+def test_sampling_call_validates_on_the_host(lib):
+    one = ctypes.c_void_p(256)
+    # streams, vocab, logits, params, history, window, uniforms, tokens, kept, stream
+    assert lib.vox_sample(4, (1 << 18) + 1, one, one, None, 0, one, one, None, None) == -2
+    assert lib.vox_sample(0, 100, one, one, None, 0, one, one, None, None) == -2
+    assert lib.vox_sample(4, 100, one, one, None, -1, one, one, None, None) == -2
+    assert lib.vox_sample(4, 100, None, one, None, 0, one, one, None, None) == -1
+    assert lib.vox_sample(4, 100, one, one, None, 8, one, one, None, None) == -1  # window without history
+    assert lib.vox_sample_weights(4, 100, one, one, None, 0, None, one, None) == -1
+    assert ctypes.sizeof(ctypes.c_float) * 3 + 4 == 16  # vox_sampling_t: three floats and an int32
 
 
 def test_workspace_too_small_is_reported(lib):
