@@ -664,6 +664,10 @@ def test_sampled_tokens_are_bit_exact(dev, case):
         (1.5, 0.5, 7, 1.0),      # both cuts, small k
         (0.3, 1e-6, 0, 1.0),     # top-p keeps one token
         (1.0, 0.999, v + 3, 1.0),  # k beyond the vocabulary
+        (50.0, 0.9, 1000, 1.0),  # flat: every token is near the maximum (general path)
+        (50.0, 1.0, 0, 1.0),
+        (0.3, 0.9, 50, 1.0),     # peaked: the 50th token lies beyond the near range
+        (0.05, 1.0, 20, 1.1),    # ... and beyond the counted range
     ]
     for temperature, top_p, top_k, penalty in settings:
         for uu in (u, np.zeros_like(u), np.full_like(u, np.nextafter(np.float32(1), np.float32(0)))):
