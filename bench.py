@@ -30,8 +30,12 @@ METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 
 # HBM bytes per attention-kernel launch from rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
 # scaled by what the same counter reads for a plain 1 GiB device copy); the runs are summarised
-# in profiles/decode_kernel_<workload>.txt.  Workloads without a counter run report null.
-MEASURED_TRAFFIC = {"cfg3": 2353503963, "cfg4": 2726703340, "cfg5": 1100728728}
+# in profiles/*_<workload>*.txt.  Workloads without a counter run report null.
+MEASURED_TRAFFIC = {
+    "cfg3": 2353628525, "cfg4": 2727037161, "cfg5": 1100764377,
+    "chunk15": 2461071895, "chunk25": 4908707842, "chunk28": 2440519574, "admit": 3032587044,
+    "prefill": 512283406, "sample_small": 53909659, "sample_large": 330291029,
+}
 
 
 def cpu_model() -> str:
@@ -122,7 +126,8 @@ def bench_multi(args, dev) -> int:
         roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4)}
     roofline.update({"kernel": "decode_kernel<MqMath>", "kernel_ms": round(kern_ms, 4),
-                     "bytes_per_launch": kv_bytes, "flops_per_launch": flops, "traffic": None})
+                     "bytes_per_launch": kv_bytes, "flops_per_launch": flops,
+                     "traffic": MEASURED_TRAFFIC.get(args.workload)})
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -219,6 +224,12 @@ def bench_sample(args, dev) -> int:
     def step(i):
         binding.sample(logits[i % copies], prm, u, tokens, history=hist)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -239,7 +250,8 @@ def bench_sample(args, dev) -> int:
     ach = nbytes / (kern_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "sample_kernel", "achieved": round(ach, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
-                "kernel_ms": round(kern_ms, 4), "bytes_per_launch": nbytes, "traffic": None}
+                "kernel_ms": round(kern_ms, 4), "bytes_per_launch": nbytes,
+                "traffic": MEASURED_TRAFFIC.get(args.workload)}
     cpu = None
     if not args.no_cpu_baseline:
         import oracle

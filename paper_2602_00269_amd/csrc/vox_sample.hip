@@ -87,9 +87,9 @@ __device__ inline uint64_t key_of(const StreamCtx& c, int v, float z, float* d_o
 }
 
 // Calls f(v, z[v]) for every token of the stream, this thread's share; the logits of kAhead
-// tokens are loaded before any of them is used, so the loads overlap.
-constexpr int kAhead = 8;
-template <class F>
+// tokens are loaded before any of them is used, so the loads overlap (more of them for light
+// bodies, fewer where the body needs the registers).
+template <int kAhead = 4, class F>
 __device__ inline void for_each_token(const StreamCtx& c, F f) {
   for (int v0 = threadIdx.x; v0 < c.V; v0 += kThreads * kAhead) {
     float z[kAhead];
@@ -275,7 +275,7 @@ __device__ StreamCtx open_stream(Lds& s, int V, const float* __restrict__ logits
   }
   c.m = 0.0f;
   float mx = -INFINITY;
-  for_each_token(c, [&](int v, float z) { mx = fmaxf(mx, tempered(c, v, z)); });
+  for_each_token<16>(c, [&](int v, float z) { mx = fmaxf(mx, tempered(c, v, z)); });
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
   if (lane == 0) s.wave_max[wv] = mx;
