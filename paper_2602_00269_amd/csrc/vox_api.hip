@@ -352,7 +352,10 @@ size_t vox_paged_prefill_workspace_bytes(const vox_shape_t* shape, int32_t total
   const int64_t tiles = (int64_t)total_q + shape->num_streams;  // every tile holds >= 1 row
   const int64_t steps = tiles * ((shape->max_blocks_per_stream + 1) / 2) * shape->num_kv_heads;
   const int64_t slots = split_waves(shape) + tiles * shape->num_kv_heads;
-  const int ncg = prefill_column_groups(p, total_q);  // the widest records any call may use
+  // the widest records any call with this many rows may use: a smaller largest chunk can pick a
+  // wider tile than the largest possible one does
+  int ncg = prefill_column_groups(p, total_q);
+  if (p.D == 128 && total_q >= 5 * (16 / p.G) - (16 / p.G - 1) && ncg < 6) ncg = 6;
   return map_prefill_workspace(p, ncg, tiles, total_q, slots, steps, split_waves(shape)).total;
 }
 

@@ -50,7 +50,9 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
 }
 __device__ inline float round_bf16(float a) { return (float)(__bf16)a; }
 
-template <int D, int NBUF, int NCG>
+// QL: the query rows live in LDS (each lane's own copy, read back by the same lane, so no
+// synchronisation is involved) instead of registers: room for more column groups per tile.
+template <int D, int NBUF, int NCG, bool QL = false>
 struct MqMath {
   typedef MqDesc Desc;
   __device__ static int ga(const Desc& d) { return d.a.x; }
@@ -61,12 +63,13 @@ struct MqMath {
 
   static constexpr int kBuffers = NBUF;
   // 39 KB per wave (all four waves: 156 of the CU's 160 KB): 4, 2, 1 records at head_dim 128
-  // with 1, 2, 4 column groups; 9, 4, 2, 1 at head_dim 64 with 1, 2, 4, 8
-  static constexpr int kStashFloats = 9984;
+  // with 1, 2, 4 column groups; 9, 4, 2, 1 at head_dim 64 with 1, 2, 4, 8.  With the query rows
+  // in LDS there is no room for records: they go straight to global memory.
+  static constexpr int kStashFloats = QL ? 64 : 9984;
   static constexpr int kMinWavesPerSimd = 1;
   static constexpr int KK = D / 32;
   static constexpr int NT = D / 16;
-  static constexpr int CB = NCG < kBatch ? NCG : kBatch;  // groups per batch
+  static constexpr int CB = QL ? 1 : (NCG < kBatch ? NCG : kBatch);  // groups per batch
 
   // The query rows of the next run are loaded straight into the state's registers right
   // after the last step of the previous run was computed (they are dead by then), ahead of
@@ -77,7 +80,7 @@ struct MqMath {
     u32x4 k[2][KK], v[2][KK];
   };
   struct State {
-    u32x4 q[NCG][KK];
+    u32x4 q[QL ? 1 : NCG][KK];
     f32x4 acc[NCG][NT];
     float m[NCG], l[NCG];
   };
@@ -85,8 +88,15 @@ struct MqMath {
   const Params& p;
   int lane, n, c, jcol, gcol, tq;
   int k_off, v_off;
+  u32x4* q_lds;  // QL: this lane's slot of entry (cg, kk) is q_lds[(cg * KK + kk) * 64]
 
   __device__ MqMath(int lane_, const Params& p_) : p(p_), lane(lane_) {
+    if (QL) {
+      __shared__ u32x4 q_mem[kWavesPerGroup][NCG * KK * kWave];
+      q_lds = q_mem[threadIdx.x >> 6] + lane_;
+    } else {
+      q_lds = nullptr;
+    }
     n = lane & 15;
     c = lane >> 4;
     tq = kCols / p.G;  // query tokens per column group
@@ -110,8 +120,22 @@ struct MqMath {
   }
 
   __device__ void load_q(Q&, State& s, const uint16_t* __restrict__ q, const Desc& d) const {
+    if (QL) {
 #pragma unroll
-    for (int cg = 0; cg < NCG; ++cg) load_group(s.q[cg], q, d, cg);
+      for (int cg = 0; cg < NCG; ++cg) {
+        u32x4 t[KK];
+        load_group(t, q, d, cg);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) q_lds[(cg * KK + kk) * kWave] = t[kk];
+      }
+    } else {
+#pragma unroll
+      for (int cg = 0; cg < NCG; ++cg) load_group(s.q[cg], q, d, cg);
+    }
+  }
+
+  __device__ u32x4 q_at(const State& s, int cg, int kk) const {
+    return QL ? q_lds[(cg * KK + kk) * kWave] : s.q[QL ? 0 : cg][kk];
   }
 
   __device__ void install_q(State&, const Q&) const {}
@@ -174,8 +198,9 @@ struct MqMath {
         f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-          sa = mfma32(r.k[0][kk], s.q[cg0 + b][kk], sa);
-          sb = mfma32(r.k[1][kk], s.q[cg0 + b][kk], sb);
+          const u32x4 qv = q_at(s, cg0 + b, kk);
+          sa = mfma32(r.k[0][kk], qv, sa);
+          sb = mfma32(r.k[1][kk], qv, sb);
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -616,6 +641,9 @@ hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_ne
 int prefill_column_groups(const Params& p, int max_new_tokens) {
   const int tq = kCols / p.G;
   const int want = (max_new_tokens + tq - 1) / tq;  // groups the longest stream fills
+  // Six groups (query rows in LDS, records straight to global memory) cost more per step than
+  // four; they pay only where they save a second pass over the context: 5 or 6 groups wanted.
+  if (p.D == 128 && (want == 5 || want == 6)) return 6;
   // register budget: eight groups at head_dim 64, four at head_dim 128
   const int most = p.D == 64 ? 8 : 4;
   // fewest tiles first (each tile streams the context again), then the smallest kernel that
@@ -627,11 +655,11 @@ int prefill_column_groups(const Params& p, int max_new_tokens) {
   return ncg;
 }
 
-template <int D, int NBUF, int NCG>
+template <int D, int NBUF, int NCG, bool QL = false>
 static void launch_mq(const Params& pk, unsigned grid, const void* q, const void* k_pool,
                       const void* v_pool, const int32_t* header, const MqDesc* desc, float2* pml,
                       float* pacc, hipStream_t st) {
-  hipLaunchKernelGGL((decode_kernel<MqMath<D, NBUF, NCG>>), dim3(grid), dim3(256), 0, st, pk,
+  hipLaunchKernelGGL((decode_kernel<MqMath<D, NBUF, NCG, QL>>), dim3(grid), dim3(256), 0, st, pk,
                      (const uint16_t*)q, (const uint16_t*)k_pool, (const uint16_t*)v_pool, header,
                      desc, pml, pacc);
 }
@@ -675,7 +703,9 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
     pk.ranges_off = (int32_t)((m.ranges - m.header) / sizeof(int32_t));
     if (ev_before) (void)hipEventRecord(ev_before, st);
     if (p.D == 128) {
-      if (ncg == 4)
+      if (ncg == 6)
+        launch_mq<128, 2, 6, true>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
+      else if (ncg == 4)
         launch_mq<128, 2, 4>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
       else if (ncg == 2)
         launch_mq<128, 2, 2>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
