@@ -3,7 +3,7 @@
 // decode step is used; what changes is the meaning of the 16 MFMA columns and the plan.
 //
 // A column group is TQ = 16 / G consecutive new tokens of one stream: their TQ x G (token, head)
-// pairs fill the 16 columns of the score MFMAs, column n = j * G + g.  A tile is 1, 2 or 4
+// pairs fill the 16 columns of the score MFMAs, column n = j * G + g.  A tile is 1, 2, 4, 6 or 8
 // column groups (chosen from the largest n_s) that share every loaded K/V step; segment (tile,
 // kv head) walks the context [0, position of the tile's last token] in 32-token steps.  Column j may
 // only see tokens up to its own position, which matters in the last steps of a segment only.
