@@ -710,3 +710,37 @@ def test_sampling_ties_mixed_settings_and_no_window(dev):
         assert np.array_equal(kept, ref_kept) and np.array_equal(tok, ref_tok)
         if hist is None:
             assert tok[0] == 1000  # greedy: the lowest id among the tied maxima
+
+
+def test_multi_token_step_at_the_ends_of_its_range(dev):
+    # one long prompt from scratch (many tiles, ranges cut through tiles) and thousands of
+    # streams with 0, 1 or 2 new tokens
+    rng = np.random.default_rng(77)
+    cases = [([4096], [4096], 4, 1, 64),
+             (rng.integers(1, 80, 3000).tolist(), None, 8, 2, 64)]
+    for idx, (lens, nq, hq, hkv, d) in enumerate(cases):
+        if nq is None:
+            nq = np.minimum(rng.integers(0, 3, len(lens)), lens).tolist()
+        w, qo, q, k_new, v_new = _prefill_case(dev, lens, nq, hq, hkv, d, seed=300 + idx)
+        sh = binding.shape_of(w)
+        bt, lens_d, qo_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev), _i32(qo, dev)
+        kp_ref, vp_ref = _host_pools(w)
+        oracle.kv_append_multi(bits_of(k_new), bits_of(v_new), kp_ref, vp_ref, w.block_tables,
+                               w.context_lens, qo, head_dim=d)
+        binding.kv_append_multi(sh, k_new, v_new, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d)
+        torch.cuda.synchronize()
+        kp, vp = _host_pools(w)
+        assert np.array_equal(kp, kp_ref) and np.array_equal(vp, vp_ref)
+        ref, ref_lse = oracle.paged_prefill(bits_of(q), kp_ref, vp_ref, w.block_tables,
+                                            w.context_lens, qo, w.scale, num_kv_heads=hkv)
+        tq = int(qo[-1])
+        out = torch.full((tq, hq, d), float("nan"), device=dev)
+        lse = torch.full((tq, hq), float("nan"), device=dev)
+        ws = torch.empty(binding.paged_prefill_workspace_bytes(sh, tq), dtype=torch.uint8,
+                         device=dev)
+        ws.fill_(0xFF)
+        binding.paged_prefill(sh, q, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d, w.context_lens,
+                              qo, out, ws, lse=lse)
+        torch.cuda.synchronize()
+        _assert_close(out.cpu().numpy(), ref, f"range case {idx}")
+        _assert_lse(lse.cpu().numpy(), ref_lse, f"range case {idx}")
