@@ -317,6 +317,8 @@ def main() -> int:
     ap.add_argument("--rope", action="store_true",
                     help="time vox_decode_step_rope: rotary embedding + Q/K/V split fused into "
                          "the append (inputs are packed QKV rows)")
+    ap.add_argument("--no-read-ceiling", action="store_true",
+                    help="skip the 4 GiB streaming-read probe that measures the chip's read ceiling")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -442,6 +444,49 @@ def main() -> int:
     torch.cuda.synchronize()
     kern_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
     achieved = kv_bytes_layer / (kern_ms * 1e-3) / 1e9
+
+    # ---- split-K balance: every wave's own start / end clock (100 MHz) in one more launch
+    waves = args.split_waves if args.split_waves > 0 else 1024
+    clocks = torch.full((2 * waves,), -1, dtype=torch.int64, device=dev)
+    w0, o0 = sets[0], outs[0]
+    binding.kv_append(sh, w0.k_new[0], w0.v_new[0], w0.k_pool[0], w0.v_pool[0], bt, lens)
+    binding.paged_decode(sh, w0.q[0], w0.k_pool[0], w0.v_pool[0], bt, lens, o0[0], ws,
+                         context_lens_host=host_lens, wave_clock=clocks)
+    torch.cuda.synchronize()
+    ck = clocks.cpu().numpy().reshape(waves, 2)
+    ck = ck[ck[:, 0] >= 0]
+    wave_spread = None
+    if len(ck):
+        dur = (ck[:, 1] - ck[:, 0]) * 1e-2  # ticks of 10 ns -> us
+        end = (ck[:, 1] - ck[:, 0].min()) * 1e-2
+        wave_spread = {"waves": int(len(ck)), "duration_us_min": round(float(dur.min()), 1),
+                       "duration_us_median": round(float(np.median(dur)), 1),
+                       "duration_us_max": round(float(dur.max()), 1),
+                       "last_start_us": round(float((ck[:, 0].max() - ck[:, 0].min()) * 1e-2), 1),
+                       "first_end_us": round(float(end.min()), 1),
+                       "last_end_us": round(float(end.max()), 1)}
+
+    # ---- the chip's streaming-read ceiling: 4 GiB read once, no arithmetic
+    read_ceiling = None
+    if not args.no_read_ceiling:
+        probe = torch.empty(1 << 32, dtype=torch.uint8, device=dev).fill_(1)
+        sink = torch.zeros(8192, dtype=torch.int32, device=dev)
+        pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(5)]
+        binding.read_probe(probe, sink)
+        for a, b in pe:
+            a.record()
+            binding.read_probe(probe, sink)
+            b.record()
+        torch.cuda.synchronize()
+        read_ceiling = round((1 << 32) / (min(a.elapsed_time(b) for a, b in pe) * 1e-3) / 1e9, 1)
+        del probe
+    # KV bytes plus everything else one layer's step has to move: queries, outputs, block
+    # table reads, appended rows, partial records (written and read back)
+    s_, hq_, hkv_, d_ = base.num_streams, base.num_q_heads, base.num_kv_heads, base.head_dim
+    nb = int(((base.context_lens.astype(np.int64) + 15) // 16).sum())
+    other_bytes = (s_ * hq_ * d_ * 2 + s_ * hq_ * d_ * 4 + nb * 4 * hkv_ + s_ * hkv_ * d_ * 4 +
+                   2 * (waves + s_ * hkv_) * (hq_ // hkv_) * (d_ + 2) * 4)
     roofline = {
         "bound": "hbm",
         "kernel": "decode_valu_kernel" if path == binding.PATH_VALU else "decode_mfma_kernel",
@@ -452,6 +497,9 @@ def main() -> int:
         "kernel_ms": round(kern_ms, 4),
         "bytes_per_launch": kv_bytes_layer,
         "traffic": MEASURED_TRAFFIC.get(args.workload) if path != binding.PATH_VALU else None,
+        "read_ceiling_gbps": read_ceiling,
+        "frac_of_read_ceiling": round(achieved / read_ceiling, 4) if read_ceiling else None,
+        "other_algorithmic_bytes_per_launch": other_bytes,
     }
 
     # ---- CPU baseline: the oracle as it stands on a bounded sample of streams
@@ -483,10 +531,15 @@ def main() -> int:
         while passes == 0 or (secs < args.cpu_seconds and passes < 64):
             secs += run(n)  # whole sample again: the oracle is fast on many-core hosts
             passes += 1
+        threads = oracle.num_threads()
+        oracle.set_num_threads(1)  # the same oracle on one core, on the probe's streams
+        single = probe_tok * per_tok / max(run(probe_n), 1e-6) / 1e9
+        oracle.set_num_threads(0)
         cpu = {
             "value": round(passes * toks * per_tok / secs / 1e9, 4),
             "unit": "GB/s",
-            "cores": oracle.num_threads(),
+            "cores": threads,
+            "single_thread_value": round(single, 4),
             "kind": "oracle",
             "sample": f"fp64 oracle decode of streams [0,{n}) of {base.num_streams} "
                       f"({toks} tokens, layer 0), {passes} passes in {secs:.2f} s",
@@ -525,6 +578,7 @@ def main() -> int:
         },
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "stream_steps_per_s": round(base.num_streams / (ms_per_step * 1e-3), 1),
+        "wave_spread": wave_spread,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -146,13 +146,25 @@ int vox_paged_decode(const vox_shape_t* shape, const void* q, const void* k_pool
  * Measurement aid: vox_paged_decode that also records two caller-created hipEvent_t on
  * hip_stream, one immediately before and one immediately after the split-K attention kernel
  * (the launch that reads the KV cache), so its duration can be read with
- * hipEventElapsedTime.  Either event may be NULL.
+ * hipEventElapsedTime.  Either event may be NULL.  wave_clock, when not NULL, is a device
+ * array of 2 * W uint64 (W = split_waves, 1024 by default): wave w of the attention kernel
+ * stores the chip's constant-rate clock (100 MHz) at its start and end in entries 2w, 2w+1;
+ * entries of waves without work are left untouched.
  */
 int vox_paged_decode_profiled(const vox_shape_t* shape, const void* q, const void* k_pool,
                               const void* v_pool, const int32_t* block_tables,
                               const int32_t* context_lens, const int32_t* context_lens_host,
                               float* out, float* lse, void* workspace, size_t workspace_bytes,
-                              void* hip_stream, void* event_before, void* event_after);
+                              void* hip_stream, void* event_before, void* event_after,
+                              uint64_t* wave_clock);
+
+/*
+ * Measurement aid: reads `bytes` (a multiple of 16) of device memory at buf once, 16 bytes per
+ * lane with the same streaming loads the attention kernel uses, and writes one word per
+ * workgroup to sink (device, at least 8192 * 4 bytes): the streaming-read rate this chip
+ * reaches with no arithmetic at all.
+ */
+int vox_read_probe(const void* buf, size_t bytes, void* sink, void* hip_stream);
 
 /*
  * Whole decode step over `num_layers` backbone layers that share block_tables

@@ -37,6 +37,8 @@ def _load():
         lib.vox_oracle_sample_weight.argtypes = [f]
         lib.vox_oracle_sample_weight.restype = ctypes.c_uint64
         lib.vox_oracle_num_threads.restype = i
+        lib.vox_oracle_set_num_threads.argtypes = [i]
+        lib.vox_oracle_set_num_threads.restype = None
         _lib = lib
     return _lib
 
@@ -63,6 +65,11 @@ def _check(rc, what):
 
 def num_threads() -> int:
     return int(_load().vox_oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads the C oracle may use from now on (0: all processors)."""
+    _load().vox_oracle_set_num_threads(int(n))
 
 
 def kv_append(k_new, v_new, k_pool, v_pool, block_tables, context_lens, *, head_dim, block_size=16):

@@ -324,6 +324,15 @@ int vox_oracle_rope_append(int S, int Hq, int Hkv, int D, int B, int P, int max_
   return ORACLE_OK;
 }
 
+/* Number of OpenMP threads later calls may use (n < 1: the runtime's default). */
+void vox_oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+  omp_set_num_threads(n < 1 ? omp_get_num_procs() : n);
+#else
+  (void)n;
+#endif
+}
+
 int vox_oracle_num_threads(void) {
   int n = 1;
 #ifdef _OPENMP

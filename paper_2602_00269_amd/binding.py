@@ -64,7 +64,7 @@ def load() -> ctypes.CDLL:
     lib.vox_paged_decode_workspace_bytes.restype = ctypes.c_size_t
     lib.vox_paged_decode.argtypes = [sp] + [vp] * 9 + [ctypes.c_size_t, vp]
     lib.vox_paged_decode.restype = ctypes.c_int
-    lib.vox_paged_decode_profiled.argtypes = [sp] + [vp] * 9 + [ctypes.c_size_t, vp, vp, vp]
+    lib.vox_paged_decode_profiled.argtypes = [sp] + [vp] * 9 + [ctypes.c_size_t, vp, vp, vp, vp]
     lib.vox_paged_decode_profiled.restype = ctypes.c_int
     lib.vox_decode_step.argtypes = [sp, i32] + [vp] * 10 + [ctypes.c_size_t, vp]
     lib.vox_decode_step.restype = ctypes.c_int
@@ -84,6 +84,8 @@ def load() -> ctypes.CDLL:
     lib.vox_sample.restype = ctypes.c_int
     lib.vox_sample_weights.argtypes = [i32, i32, vp, vp, vp, i32, vp, vp, vp]
     lib.vox_sample_weights.restype = ctypes.c_int
+    lib.vox_read_probe.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.vox_read_probe.restype = ctypes.c_int
     lib.vox_strerror.argtypes = [ctypes.c_int]
     lib.vox_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -168,9 +170,10 @@ def alloc_workspace(shape, device="cuda", nbytes: Optional[int] = None) -> torch
 
 
 def paged_decode(shape, q, k_pool, v_pool, block_tables, context_lens, out, workspace, lse=None,
-                 context_lens_host=None, stream=None, events=None):
+                 context_lens_host=None, stream=None, events=None, wave_clock=None):
     """``events``: optional pair of recorded-once ``torch.cuda.Event(enable_timing=True)``;
-    the library re-records them around the attention kernel."""
+    the library re-records them around the attention kernel.  ``wave_clock``: optional int64
+    tensor [2 * waves] receiving every wave's start and end clock (100 MHz)."""
     bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
     keep, host = _host_lens(context_lens_host)
     ev0 = ev1 = None
@@ -181,7 +184,8 @@ def paged_decode(shape, q, k_pool, v_pool, block_tables, context_lens, out, work
         _dev(v_pool, bf, "v_pool"), _dev(block_tables, i32, "block_tables"),
         _dev(context_lens, i32, "context_lens"), host, _dev(out, f32, "out"),
         _dev(lse, f32, "lse", optional=True), _dev(workspace, torch.uint8, "workspace"),
-        workspace.numel(), _stream(stream), ev0, ev1)
+        workspace.numel(), _stream(stream), ev0, ev1,
+        _dev(wave_clock, torch.int64, "wave_clock", optional=True))
     del keep
     _check(rc, "vox_paged_decode")
 
@@ -373,3 +377,10 @@ def sample_weights(logits, params, d_out, w_out, history=None, stream=None):
                                    _dev(d_out, torch.float32, "d_out"),
                                    _dev(w_out, torch.int64, "w_out"), _stream(stream))
     _check(rc, "vox_sample_weights")
+
+
+def read_probe(buf, sink, stream=None):
+    """Stream ``buf`` (uint8 tensor, length a multiple of 16) once; ``sink``: int32 tensor [8192]."""
+    rc = load().vox_read_probe(_dev(buf, torch.uint8, "buf"), buf.numel(),
+                               _dev(sink, torch.int32, "sink"), _stream(stream))
+    _check(rc, "vox_read_probe")

@@ -28,6 +28,13 @@ int validate(const vox_shape_t* s) {
   return VOX_OK;
 }
 
+// Number of equal ranges the step axis is cut into: by default one per wave the decode
+// kernel keeps resident on the whole chip, so the launch is a single balanced round.
+int split_waves(const vox_shape_t* s) {
+  int w = s->split_waves ? s->split_waves : kDesignWaveSlots;
+  return (w + kWavesPerGroup - 1) / kWavesPerGroup * kWavesPerGroup;
+}
+
 Params make_params(const vox_shape_t* s) {
   Params p;
   p.S = s->num_streams;
@@ -38,16 +45,13 @@ Params make_params(const vox_shape_t* s) {
   p.P = s->num_blocks;
   p.max_nb = s->max_blocks_per_stream;
   p.scale_log2 = s->scale * 1.44269504088896340736f;
-  p.n_steps = p.per_wave = -1;
+  p.n_steps = -1;
+  p.lay = layout_of(0, 1, false);
+  p.waves = split_waves(s);
+  p.pool_counter = nullptr;
   p.ranges_off = 0;
+  p.wave_clock = nullptr;
   return p;
-}
-
-// Number of equal ranges the step axis is cut into: by default one per wave the decode
-// kernel keeps resident on the whole chip, so the launch is a single balanced round.
-int split_waves(const vox_shape_t* s) {
-  int w = s->split_waves ? s->split_waves : kDesignWaveSlots;
-  return (w + kWavesPerGroup - 1) / kWavesPerGroup * kWavesPerGroup;
 }
 
 // Upper bound of the number of global steps when only the shape is known.
@@ -57,11 +61,12 @@ int64_t steps_bound(const vox_shape_t* s) {
 
 Workspace map_workspace(const vox_shape_t* s, int64_t desc_capacity) {
   const int g = s->num_q_heads / s->num_kv_heads;
-  const size_t slots = (size_t)split_waves(s) + (size_t)s->num_streams * s->num_kv_heads;
+  const size_t slots = (size_t)split_waves(s) + (size_t)pool_ranges_bound(steps_bound(s)) +
+                       (size_t)s->num_streams * s->num_kv_heads;
   Workspace w;
   size_t off = 0;
   w.header = off;
-  off = align_up(off + 64 * sizeof(int32_t), 256);
+  off = align_up(off + kHeaderWords * sizeof(int32_t), 256);
   w.step_prefix = off;
   off = align_up(off + ((size_t)s->num_streams + 1) * sizeof(int32_t), 256);
   w.partial_ml = off;
@@ -111,8 +116,16 @@ int make_plan(const vox_shape_t* s, const int32_t* lens_host, size_t workspace_b
 void set_step_hints(Params* p, const Plan& plan) {
   if (!plan.exact) return;
   p->n_steps = (int32_t)plan.max_steps;
-  const int64_t q = (plan.max_steps + plan.waves - 1) / plan.waves;
-  p->per_wave = (int32_t)(q > 1 ? q : 1);
+  p->lay = layout_of(plan.max_steps, plan.waves, p->pool_counter != nullptr);
+}
+
+// The pool counter of layer l of a step (zeroed by the plan kernel).
+int32_t* pool_counter(const Plan& plan, char* ws, int layer) {
+#ifdef VOX_NO_POOL  // measurement builds: equal ranges only
+  return nullptr;
+#else
+  return (int32_t*)(ws + plan.ws.header) + kHdrPoolCounters + layer;
+#endif
 }
 
 int enqueue_plan(const Params& p, const Plan& plan, char* ws, const int32_t* bt,
@@ -217,14 +230,15 @@ int vox_paged_decode(const vox_shape_t* shape, const void* q, const void* k_pool
                      float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
   return vox_paged_decode_profiled(shape, q, k_pool, v_pool, block_tables, context_lens,
                                    context_lens_host, out, lse, workspace, workspace_bytes,
-                                   hip_stream, nullptr, nullptr);
+                                   hip_stream, nullptr, nullptr, nullptr);
 }
 
 int vox_paged_decode_profiled(const vox_shape_t* shape, const void* q, const void* k_pool,
                               const void* v_pool, const int32_t* block_tables,
                               const int32_t* context_lens, const int32_t* context_lens_host,
                               float* out, float* lse, void* workspace, size_t workspace_bytes,
-                              void* hip_stream, void* event_before, void* event_after) {
+                              void* hip_stream, void* event_before, void* event_after,
+                              uint64_t* wave_clock) {
   if (int rc = validate(shape)) return rc;
   if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out || !workspace)
     return VOX_ERR_NULL;
@@ -232,9 +246,11 @@ int vox_paged_decode_profiled(const vox_shape_t* shape, const void* q, const voi
   Plan plan;
   if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
   Params p = make_params(shape);
-  set_step_hints(&p, plan);
-  hipStream_t st = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
+  p.pool_counter = pool_counter(plan, ws, 0);
+  set_step_hints(&p, plan);
+  p.wave_clock = (unsigned long long*)wave_clock;
+  hipStream_t st = (hipStream_t)hip_stream;
   if (int rc = enqueue_plan(p, plan, ws, block_tables, context_lens, st)) return rc;
   const WsPtrs w = ws_ptrs(plan, ws);
   if (int rc = enqueue_attention(shape, p, plan, w, q, k_pool, v_pool, st,
@@ -251,7 +267,7 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
                     const int32_t* context_lens_host, float* const* out, void* workspace,
                     size_t workspace_bytes, void* hip_stream) {
   if (int rc = validate(shape)) return rc;
-  if (num_layers <= 0) return VOX_ERR_ARG;
+  if (num_layers <= 0 || num_layers > kMaxLayers) return VOX_ERR_ARG;
   if (!q || !k_new || !v_new || !k_pool || !v_pool || !block_tables || !context_lens || !out ||
       !workspace)
     return VOX_ERR_NULL;
@@ -262,9 +278,10 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
   Plan plan;
   if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
   Params p = make_params(shape);
+  char* ws = (char*)workspace;
+  p.pool_counter = pool_counter(plan, ws, 0);  // the plan zeroes every layer's counter
   set_step_hints(&p, plan);
   hipStream_t st = (hipStream_t)hip_stream;
-  char* ws = (char*)workspace;
   const WsPtrs w = ws_ptrs(plan, ws);
   // Launch chain: [plan + append(0)] attention(0) [merge(0) + append(1)] attention(1) ...
   // merge(L-1).  Each bracket is one launch of two independent roles.
@@ -273,6 +290,7 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
                          plain_append(k_new[0], v_new[0], k_pool[0], v_pool[0]), st) != hipSuccess)
     return VOX_ERR_HIP;
   for (int l = 0; l < num_layers; ++l) {
+    p.pool_counter = pool_counter(plan, ws, l);
     if (int rc = enqueue_attention(shape, p, plan, w, q[l], k_pool[l], v_pool[l], st)) return rc;
     hipError_t e =
         l + 1 < num_layers
@@ -285,6 +303,13 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
     if (e != hipSuccess) return VOX_ERR_HIP;
   }
   return VOX_OK;
+}
+
+int vox_read_probe(const void* buf, size_t bytes, void* sink, void* hip_stream) {
+  if (!buf || !sink) return VOX_ERR_NULL;
+  if (bytes == 0 || bytes % 16 || (uintptr_t)buf % 16) return VOX_ERR_ARG;
+  return launch_read_probe(buf, bytes, sink, (hipStream_t)hip_stream) == hipSuccess ? VOX_OK
+                                                                                   : VOX_ERR_HIP;
 }
 
 int vox_rope_append(const vox_shape_t* shape, const void* qkv, const float* rope_cos,
@@ -310,7 +335,7 @@ int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const voi
                          const int32_t* context_lens_host, float* const* out, void* workspace,
                          size_t workspace_bytes, void* hip_stream) {
   if (int rc = validate(shape)) return rc;
-  if (num_layers <= 0) return VOX_ERR_ARG;
+  if (num_layers <= 0 || num_layers > kMaxLayers) return VOX_ERR_ARG;
   if (!qkv || !rope_cos || !rope_sin || !q_rot || !k_pool || !v_pool || !block_tables ||
       !context_lens || !out || !workspace)
     return VOX_ERR_NULL;
@@ -321,9 +346,10 @@ int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const voi
   Plan plan;
   if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
   Params p = make_params(shape);
+  char* ws = (char*)workspace;
+  p.pool_counter = pool_counter(plan, ws, 0);  // the plan zeroes every layer's counter
   set_step_hints(&p, plan);
   hipStream_t st = (hipStream_t)hip_stream;
-  char* ws = (char*)workspace;
   const WsPtrs w = ws_ptrs(plan, ws);
   // [plan + rope/append(0)] attention(0) [merge(0) + rope/append(1)] attention(1) ... merge(L-1)
   const auto layer = [&](int l) {
@@ -334,6 +360,7 @@ int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const voi
                          st) != hipSuccess)
     return VOX_ERR_HIP;
   for (int l = 0; l < num_layers; ++l) {
+    p.pool_counter = pool_counter(plan, ws, l);
     if (int rc = enqueue_attention(shape, p, plan, w, q_rot[l], k_pool[l], v_pool[l], st))
       return rc;
     hipError_t e =

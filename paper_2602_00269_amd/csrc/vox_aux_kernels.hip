@@ -222,14 +222,18 @@ __device__ inline void plan_role(const Params& p, int group, const int32_t* __re
 
   const int64_t n_all = (int64_t)prefix[S] * p.Hkv;
   const int64_t N = min(n_all, desc_capacity);
-  const int Q = (int)max((int64_t)1, (N + waves - 1) / waves);
+  const StepLayout lay = layout_of(N, waves, p.pool_counter != nullptr);
   if (group == 0) {
     for (int s = tid; s <= S; s += kPlanThreads) step_prefix[s] = prefix[s];
+    for (int l = tid; l < kMaxLayers; l += kPlanThreads) header[kHdrPoolCounters + l] = 0;
     if (tid == 0) {
       header[kHdrSteps] = (int)N;
-      header[kHdrPerWave] = Q;
+      header[kHdrPerWave] = lay.Q;
       header[kHdrWaves] = waves;
       header[kHdrOverflow] = n_all > desc_capacity;
+      header[kHdrMain] = (int)lay.n_main;
+      header[kHdrUsed] = lay.U;
+      header[kHdrPool] = lay.R;
     }
   }
 
@@ -255,8 +259,8 @@ __device__ inline void plan_role(const Params& p, int group, const int32_t* __re
   const int idb = (2 * st + 1 < nb) ? row[2 * st + 1] : ida;
   const int ntok = min(kStepTokens, L - kStepTokens * st);
   int meta = ntok;
-  if (st == 0 || x % Q == 0) meta |= kMetaFirst;
-  if (st == n - 1 || x % Q == Q - 1 || x == N - 1) meta |= kMetaLast;
+  if (st == 0 || step_opens_range(lay, x)) meta |= kMetaFirst;
+  if (st == n - 1 || step_closes_range(lay, x)) meta |= kMetaLast;
   if (st == n - 1) meta |= kMetaTail;
   desc[x] = make_int4(ida * p.Hkv + h, idb * p.Hkv + h, meta, s * p.Hkv + h);
 }
@@ -282,8 +286,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
-// Merge: one wave per (stream, q head).  The runs of segment sigma lie in the ranges
-// w0 = P/Q .. w1 = (P+n-1)/Q (P = first global step of the segment); run j is slot w0+j+sigma.
+// Merge: one wave per (stream, q head).  The runs of segment sigma lie in the ranges r0 .. r1 of
+// its first and last global step; run j is slot r0 + j + sigma.
 // Lanes hold the runs' (max, sum) records; the global max and the rescaled sum are wave
 // reductions; the accumulators are then combined with each lane owning D/64 output dims.
 template <int D>
@@ -297,17 +301,17 @@ __device__ inline void merge_role(const Params& p, int group, const int32_t* __r
   const int s = w / p.Hq, i = w % p.Hq;
   const int h = i / p.G, g = i % p.G;
   const int sigma = s * p.Hkv + h;
-  const int Q = p.n_steps >= 0 ? p.per_wave : header[kHdrPerWave];
-  const int64_t N = p.n_steps >= 0 ? p.n_steps : header[kHdrSteps];
+  const StepLayout lay = p.n_steps >= 0 ? p.lay : layout_from_header(header);
+  const int64_t N = lay.N;
   const int nseg = step_prefix[s + 1] - step_prefix[s];
   const int64_t first = (int64_t)step_prefix[s] * p.Hkv + (int64_t)h * nseg;
   int n = 0;          // number of runs
   int64_t slot0 = 0;  // slot of run 0
   if (nseg > 0 && first < N) {
     const int64_t last = min(N, first + nseg) - 1;
-    const int64_t w0 = first / Q, w1 = last / Q;
-    n = (int)(w1 - w0 + 1);
-    slot0 = w0 + sigma;
+    const int64_t r0 = range_of_step(lay, first), r1 = range_of_step(lay, last);
+    n = (int)(r1 - r0 + 1);
+    slot0 = r0 + sigma;
   }
   merge_runs<D>(pml, pacc, slot0, n, p.G, g, lane, out + ((size_t)s * p.Hq + i) * D,
                 lse ? lse + (size_t)s * p.Hq + i : nullptr);
@@ -334,6 +338,20 @@ __global__ __launch_bounds__(256) void merge_append_kernel(
     merge_role<D>(p, blockIdx.x, header, step_prefix, pml, pacc, out, nullptr);
   else
     any_append_role<D>(p, blockIdx.x - merge_grps, a, bt, lens);
+}
+
+// Streaming-read probe: every thread walks the buffer with a grid stride, 16 bytes per load.
+__global__ __launch_bounds__(256) void read_probe_kernel(const au32x4* __restrict__ buf,
+                                                         size_t vecs,
+                                                         uint32_t* __restrict__ sink) {
+  au32x4 acc = {0, 0, 0, 0};
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < vecs; i += stride)
+    acc ^= __builtin_nontemporal_load(buf + i);
+  uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x ^= __shfl_xor(x, o);
+  if ((threadIdx.x & (kWave - 1)) == 0) atomicXor(&sink[blockIdx.x], x);
 }
 
 }  // namespace
@@ -422,6 +440,12 @@ hipError_t launch_merge_append(const Params& p, const int32_t* header, const int
     hipLaunchKernelGGL(merge_append_kernel<64>, dim3(mg + host_append_groups(p, a)), dim3(256), 0,
                        st, p, (int)mg, header, step_prefix, partial_ml, partial_acc, out, a, bt,
                        lens);
+  return hipGetLastError();
+}
+
+hipError_t launch_read_probe(const void* buf, size_t bytes, void* sink, hipStream_t st) {
+  hipLaunchKernelGGL(read_probe_kernel, dim3(8192), dim3(256), 0, st, (const au32x4*)buf,
+                     bytes / 16, (uint32_t*)sink);
   return hipGetLastError();
 }
 

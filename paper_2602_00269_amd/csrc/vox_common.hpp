@@ -43,6 +43,70 @@ constexpr int kHdrSteps = 0;     // N
 constexpr int kHdrPerWave = 1;   // Q
 constexpr int kHdrWaves = 2;     // W
 constexpr int kHdrOverflow = 3;  // set when N exceeded the descriptor capacity
+constexpr int kHdrMain = 4;      // n_main, U, R of the layout (see StepLayout)
+constexpr int kHdrUsed = 5;
+constexpr int kHdrPool = 6;
+constexpr int kHdrPoolCounters = 64;  // one pool counter per layer of a step follows the header
+constexpr int kMaxLayers = 4096;
+constexpr int kHeaderWords = kHdrPoolCounters + kMaxLayers;
+
+// Layout of the global step axis of the decode step.  The first n_main steps are cut into W
+// equal ranges of Q steps, one per wave.  The rest (one eighth, when every wave has enough
+// work) is a pool of short ranges of P steps that waves take from a shared counter as they
+// finish their own range: the waves of some parts of the chip stream measurably slower than
+// others, and the pool lets the fast ones take up the slack.  U <= W static ranges hold steps
+// (Q is rounded up); range r < U is static range r, range U + j is pool range j; partial
+// records of range r and segment sigma go to slot r + sigma.
+constexpr int kPoolRangeSteps = 16;
+constexpr int kPoolShare = 8;
+constexpr int kPoolMinStepsPerWave = 96;
+
+struct StepLayout {
+  int64_t N, n_main;
+  int32_t Q, W, U, P, R;
+};
+
+__host__ __device__ inline StepLayout layout_of(int64_t N, int W, bool pool) {
+  StepLayout l;
+  l.N = N;
+  l.W = W;
+  l.P = kPoolRangeSteps;
+  int64_t pool_steps = 0;
+  if (pool && N >= (int64_t)kPoolMinStepsPerWave * W)
+    pool_steps = N / kPoolShare / kPoolRangeSteps * kPoolRangeSteps;
+  l.n_main = N - pool_steps;
+  const int64_t q = (l.n_main + W - 1) / W;
+  l.Q = (int32_t)(q > 1 ? q : 1);
+  l.U = (int32_t)((l.n_main + l.Q - 1) / l.Q);
+  l.R = (int32_t)(pool_steps / kPoolRangeSteps);
+  return l;
+}
+__host__ __device__ inline int64_t range_of_step(const StepLayout& l, int64_t x) {
+  return x < l.n_main ? x / l.Q : l.U + (x - l.n_main) / l.P;
+}
+__host__ __device__ inline bool step_opens_range(const StepLayout& l, int64_t x) {
+  return x < l.n_main ? x % l.Q == 0 : (x - l.n_main) % l.P == 0;
+}
+__host__ __device__ inline bool step_closes_range(const StepLayout& l, int64_t x) {
+  if (x == l.N - 1 || x == l.n_main - 1) return true;
+  return x < l.n_main ? x % l.Q == l.Q - 1 : (x - l.n_main) % l.P == l.P - 1;
+}
+// The layout as the plan kernel left it in the header.
+__device__ inline StepLayout layout_from_header(const int32_t* header) {
+  StepLayout l;
+  l.N = header[kHdrSteps];
+  l.n_main = header[kHdrMain];
+  l.Q = header[kHdrPerWave];
+  l.W = header[kHdrWaves];
+  l.U = header[kHdrUsed];
+  l.P = kPoolRangeSteps;
+  l.R = header[kHdrPool];
+  return l;
+}
+// Upper bound of the number of pool ranges when only a bound of the step count is known.
+__host__ __device__ inline int64_t pool_ranges_bound(int64_t steps_bound) {
+  return steps_bound / kPoolShare / kPoolRangeSteps + 1;
+}
 
 // Workspace map (byte offsets from the 256-byte aligned workspace base).
 struct Workspace {
@@ -64,12 +128,20 @@ struct PrefillWorkspace {
 struct Params {
   int32_t S, Hq, Hkv, G, D, P, max_nb;
   float scale_log2;  // scale * log2(e): scores are kept in log2 units
-  // N and Q when the host knows the lengths (else -1 and the kernels read the plan's header):
-  // saves every wave one dependent round trip to memory before its first descriptor load
-  int32_t n_steps, per_wave;
+  // The layout of the step axis when the host knows the lengths (n_steps >= 0); else n_steps is
+  // -1 and the kernels read the layout the plan kernel left in the header.  The hint saves
+  // every wave a dependent round trip to memory before its first descriptor load.
+  int32_t n_steps;
+  StepLayout lay;
+  int32_t waves;  // W: static ranges of the step axis
+  // this launch's pool counter (zero when the launch starts), or null: equal ranges only
+  int32_t* pool_counter;
   // When > 0: wave w owns steps [r[w], r[w+1]) with r = header + ranges_off (int32 words), a
   // table the plan wrote, instead of the equal ranges [w*Q, (w+1)*Q)
   int32_t ranges_off;
+  // Measurement aid: when not null, wave w stores the chip's constant-rate clock at its start
+  // and end in wave_clock[2w], wave_clock[2w+1]
+  unsigned long long* wave_clock;
 };
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -118,6 +190,7 @@ hipError_t launch_plan(const Params& p, const int32_t* bt, const int32_t* lens, 
 PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, int64_t total_q,
                                        int64_t slots, int64_t desc_capacity, int waves);
 int prefill_column_groups(const Params& p, int max_new_tokens);
+hipError_t launch_read_probe(const void* buf, size_t bytes, void* sink, hipStream_t st);
 size_t prefill_desc_bytes();
 hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_new,
                                   const void* v_new, void* k_pool, void* v_pool,

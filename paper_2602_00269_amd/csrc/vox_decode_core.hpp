@@ -1,9 +1,9 @@
 // The split-K decode kernel skeleton shared by the MFMA and VALU arithmetic.
 //
-// A wave owns the global steps [w*Q, min(N, (w+1)*Q)) (or a range from the plan's table) and
-// walks them as one flat software
-// pipeline: the K/V loads of step i + NBUF are issued while step i is computed, across segment
-// boundaries, so the load queue never drains inside a wave.  Step descriptors are wave-uniform:
+// A wave owns the global steps [w*Q, (w+1)*Q) of the static part of the step axis (or a range
+// from the plan's table), then takes short ranges from a shared pool until it is used up.  It
+// walks a range as one flat software pipeline: the K/V loads of step i + NBUF are issued while
+// step i is computed, across segment boundaries, so the load queue never drains inside a range.  Step descriptors are wave-uniform:
 // they come in through scalar loads a few steps ahead and live in scalar registers.  When a run
 // of a segment ends inside the range its partial record is stored and the accumulators are
 // reset; the query rows of the next run are fetched one step ahead.
@@ -108,43 +108,29 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
   constexpr int LA = NBUF + 1;  // descriptor look-ahead in steps
   const int lane = threadIdx.x & (kWave - 1);
   const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6));
-  int64_t x0;
-  int nsteps;
+  // The wave's first range: from the plan's table, or static range w of the layout.
+  StepLayout lay = layout_of(0, 1, false);  // no pool unless the static layout says so
+  int64_t x0 = 0;
+  int nsteps = 0;
   if (p.ranges_off > 0) {  // ranges of unequal length, balanced by the plan
     const int32_t* r = header + p.ranges_off;
     x0 = r[w];
     nsteps = r[w + 1] - r[w];
     if (nsteps <= 0) return;
   } else {
-    const int N = p.n_steps >= 0 ? p.n_steps : header[kHdrSteps];
-    const int Q = p.n_steps >= 0 ? p.per_wave : header[kHdrPerWave];
-    x0 = (int64_t)w * Q;
-    if (x0 >= N) return;
-    nsteps = (int)min((int64_t)Q, (int64_t)N - x0);
+    lay = p.n_steps >= 0 ? p.lay : layout_from_header(header);
+    x0 = (int64_t)w * lay.Q;
+    if (x0 < lay.n_main) nsteps = (int)min((int64_t)lay.Q, lay.n_main - x0);
+    if (nsteps <= 0 && lay.R == 0) return;
   }
-
-  // Descriptors are wave-uniform: they are fetched with scalar loads LA steps ahead and live in
-  // scalar registers.  dq[k] is the descriptor of step i + k.
-  const Desc* dbase = desc + x0;
-  Desc dq[LA + 1];
-#pragma unroll
-  for (int k = 0; k <= LA; ++k) dq[k] = dbase[min(k, nsteps - 1)];
-
+  int range = w;  // index of the range being walked: static range w, then pool ranges U + j
+  const unsigned long long t_start = p.wave_clock ? wall_clock64() : 0;
   __shared__ float stash_mem[kWavesPerGroup][Math::kStashFloats];
   PartialStash stash(stash_mem[threadIdx.x >> 6], Math::kStashFloats, Math::columns(p), p.D, lane);
   Math math(lane, p);
   typename Math::State st;
   typename Math::Q qnext;
   typename Math::Regs ring[NBUF];
-  math.load_q(qnext, st, q, dq[0]);
-  math.reset(st);
-#pragma unroll
-  for (int b = 0; b < NBUF; ++b) {
-    const bool more = b < nsteps;
-    math.template issue<true>(ring[b], k_pool, v_pool, more ? Math::ga(dq[b]) : 0,
-                              more ? Math::gb(dq[b]) : 0);
-  }
-
   // One step of the pipeline.  In the steady-state loop every step refills its ring slot
   // unconditionally: a load issued under a run-time condition makes the compiler's wait-count
   // bookkeeping assume it was not issued and wait for every younger load, which serialises
@@ -172,9 +158,9 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
       if (stash.cap > 0) {                                                                 \
         float* rec = stash.next(pml, pacc);                                                \
         math.finish(st, rec, rec + stash.gd);                                              \
-        stash.commit(w + sigma, math.used_columns(dcur));                                  \
+        stash.commit(range + sigma, math.used_columns(dcur));                              \
       } else { /* record larger than the LDS buffer: straight to global memory */          \
-        const size_t slot = (size_t)(w + sigma);                                           \
+        const size_t slot = (size_t)(range + sigma);                                       \
         math.finish(st, pacc + slot * stash.gd,                                            \
                     reinterpret_cast<float*>(pml + slot * Math::columns(p)));              \
       }                                                                                    \
@@ -183,16 +169,49 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
     dq[LA] = dbase[min(i + 1 + LA, nsteps - 1)];                                           \
   }
 
-  int i0 = 0;
-  for (; i0 + NBUF <= nsteps; i0 += NBUF) {  // whole groups of NBUF steps, no conditions
+  for (;;) {
+    if (nsteps > 0) {
+      // Descriptors are wave-uniform: they are fetched with scalar loads LA steps ahead and
+      // live in scalar registers.  dq[k] is the descriptor of step i + k.
+      const Desc* dbase = desc + x0;
+      Desc dq[LA + 1];
 #pragma unroll
-    for (int b = 0; b < NBUF; ++b) VOX_STEP(i0 + b, b, true)
+      for (int k = 0; k <= LA; ++k) dq[k] = dbase[min(k, nsteps - 1)];
+
+      math.load_q(qnext, st, q, dq[0]);
+      math.reset(st);
+#pragma unroll
+      for (int b = 0; b < NBUF; ++b) {
+        const bool more = b < nsteps;
+        math.template issue<true>(ring[b], k_pool, v_pool, more ? Math::ga(dq[b]) : 0,
+                                  more ? Math::gb(dq[b]) : 0);
+      }
+
+      int i0 = 0;
+      for (; i0 + NBUF <= nsteps; i0 += NBUF) {  // whole groups of NBUF steps, no conditions
+#pragma unroll
+        for (int b = 0; b < NBUF; ++b) VOX_STEP(i0 + b, b, true)
+      }
+#pragma unroll
+      for (int b = 0; b < NBUF - 1; ++b)  // fewer than NBUF steps remain; their data is in flight
+        if (i0 + b < nsteps) VOX_STEP(i0 + b, b, false)
+    }
+    // the next range comes from the pool, if there is one and it is not used up
+    if (lay.R == 0) break;
+    int j = 0;
+    if (lane == 0) j = atomicAdd(p.pool_counter, 1);
+    j = __builtin_amdgcn_readfirstlane(j);
+    if (j >= lay.R) break;
+    range = lay.U + j;
+    x0 = lay.n_main + (int64_t)j * lay.P;
+    nsteps = (int)min((int64_t)lay.P, lay.N - x0);
   }
-#pragma unroll
-  for (int b = 0; b < NBUF - 1; ++b)  // fewer than NBUF steps remain; their data is in flight
-    if (i0 + b < nsteps) VOX_STEP(i0 + b, b, false)
 #undef VOX_STEP
   stash.flush(pml, pacc);
+  if (p.wave_clock && lane == 0) {
+    p.wave_clock[2 * (size_t)w] = t_start;
+    p.wave_clock[2 * (size_t)w + 1] = wall_clock64();
+  }
 }
 
 }  // namespace vox

@@ -699,7 +699,7 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
                        seg_runs);
     const unsigned grid = (unsigned)((waves + kWavesPerGroup - 1) / kWavesPerGroup);
     Params pk = p;  // every wave reads its range from the table the plan wrote
-    pk.n_steps = pk.per_wave = -1;
+    pk.n_steps = -1;
     pk.ranges_off = (int32_t)((m.ranges - m.header) / sizeof(int32_t));
     if (ev_before) (void)hipEventRecord(ev_before, st);
     if (p.D == 128) {
