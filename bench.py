@@ -32,7 +32,7 @@ METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 # scaled by what the same counter reads for a plain 1 GiB device copy); the runs are summarised
 # in profiles/*_<workload>*.txt.  Workloads without a counter run report null.
 MEASURED_TRAFFIC = {
-    "cfg3": 2353628525, "cfg4": 2727037161, "cfg5": 1100764377,
+    "cfg3": 2356091427, "cfg4": 2730082938, "cfg5": 1103183884,
     "chunk15": 2461071895, "chunk25": 4908707842, "chunk28": 2440519574, "admit": 3032587044,
     "prefill": 512283406, "sample_small": 53909659, "sample_large": 330291029,
 }

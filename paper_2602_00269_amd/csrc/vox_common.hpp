@@ -81,15 +81,20 @@ __host__ __device__ inline StepLayout layout_of(int64_t N, int W, bool pool) {
   l.R = (int32_t)(pool_steps / kPoolRangeSteps);
   return l;
 }
+// Step numbers fit 31 bits (the entry points refuse more steps), so the divisions are 32-bit.
 __host__ __device__ inline int64_t range_of_step(const StepLayout& l, int64_t x) {
-  return x < l.n_main ? x / l.Q : l.U + (x - l.n_main) / l.P;
+  const uint32_t u = (uint32_t)x, m = (uint32_t)l.n_main;
+  return u < m ? u / (uint32_t)l.Q : l.U + (u - m) / (uint32_t)kPoolRangeSteps;
 }
 __host__ __device__ inline bool step_opens_range(const StepLayout& l, int64_t x) {
-  return x < l.n_main ? x % l.Q == 0 : (x - l.n_main) % l.P == 0;
+  const uint32_t u = (uint32_t)x, m = (uint32_t)l.n_main;
+  return u < m ? u % (uint32_t)l.Q == 0 : (u - m) % (uint32_t)kPoolRangeSteps == 0;
 }
 __host__ __device__ inline bool step_closes_range(const StepLayout& l, int64_t x) {
   if (x == l.N - 1 || x == l.n_main - 1) return true;
-  return x < l.n_main ? x % l.Q == l.Q - 1 : (x - l.n_main) % l.P == l.P - 1;
+  const uint32_t u = (uint32_t)x, m = (uint32_t)l.n_main;
+  return u < m ? u % (uint32_t)l.Q == (uint32_t)l.Q - 1
+               : (u - m) % (uint32_t)kPoolRangeSteps == (uint32_t)kPoolRangeSteps - 1;
 }
 // The layout as the plan kernel left it in the header.
 __device__ inline StepLayout layout_from_header(const int32_t* header) {
