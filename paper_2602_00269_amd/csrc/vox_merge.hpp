@@ -26,6 +26,15 @@ __device__ inline void merge_runs(const float2* __restrict__ pml, const float* _
                                   int64_t slot0, int n, int cols, int col, int lane,
                                   float* __restrict__ out, float* __restrict__ lse) {
   constexpr int DPL = D / kWave;  // dims per lane
+  constexpr int kEarly = 2;       // most segments have one or two runs: their accumulators are
+                                  // requested together with the (max, sum) records, not after them
+  float early[kEarly][DPL];
+#pragma unroll
+  for (int j = 0; j < kEarly; ++j) {
+    const float* src = pacc + ((size_t)(slot0 + (j < n ? j : 0)) * cols + col) * D + lane * DPL;
+#pragma unroll
+    for (int k = 0; k < DPL; ++k) early[j][k] = j < n ? src[k] : 0.f;
+  }
   float m_run = -INFINITY, l_run = 0.f;
   float acc[DPL];
 #pragma unroll
@@ -41,16 +50,20 @@ __device__ inline void merge_runs(const float2* __restrict__ pml, const float* _
 #pragma unroll
     for (int k = 0; k < DPL; ++k) acc[k] *= alpha;
     const int cnt = min(kWave, n - c0);
-    for (int j = 0; j < cnt; ++j) {
+    int j = 0;
+    if (c0 == 0) {
+#pragma unroll
+      for (; j < kEarly; ++j) {
+        const float wj = __shfl(wgt, j);  // zero for j >= n
+#pragma unroll
+        for (int k = 0; k < DPL; ++k) acc[k] += wj * early[j][k];
+      }
+    }
+    for (; j < cnt; ++j) {
       const float wj = __shfl(wgt, j);
       const float* src = pacc + ((size_t)(slot0 + c0 + j) * cols + col) * D + lane * DPL;
-      if (DPL == 2) {
-        const float2 a = *reinterpret_cast<const float2*>(src);
-        acc[0] += wj * a.x;
-        acc[DPL - 1] += wj * a.y;
-      } else {
-        acc[0] += wj * src[0];
-      }
+#pragma unroll
+      for (int k = 0; k < DPL; ++k) acc[k] += wj * src[k];
     }
     m_run = m_new;
   }
