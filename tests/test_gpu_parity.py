@@ -744,3 +744,33 @@ def test_multi_token_step_at_the_ends_of_its_range(dev):
         torch.cuda.synchronize()
         _assert_close(out.cpu().numpy(), ref, f"range case {idx}")
         _assert_lse(lse.cpu().numpy(), ref_lse, f"range case {idx}")
+
+
+# ---------------------------------------------------------------------------------------
+# Measurement aids
+
+def test_wave_clocks_and_read_probe(dev):
+    w = synth.make_custom([3000] * 160, 24, 8, 128, seed=400, device=dev)  # pool ranges active
+    sh = binding.shape_of(w)
+    bt, lens = _i32(w.block_tables, dev), _i32(w.context_lens, dev)
+    out = torch.zeros((w.num_streams, w.num_q_heads, w.head_dim), device=dev)
+    ws = binding.alloc_workspace(sh, dev)
+    clocks = torch.full((2048,), -1, dtype=torch.int64, device=dev)
+    binding.paged_decode(sh, w.q[0], w.k_pool[0], w.v_pool[0], bt, lens, out, ws,
+                         context_lens_host=w.context_lens, wave_clock=clocks)
+    torch.cuda.synchronize()
+    ck = clocks.cpu().numpy().reshape(1024, 2)
+    assert (ck[:, 0] >= 0).all() and (ck[:, 1] > ck[:, 0]).all()  # every wave had work
+    dur_us = (ck[:, 1] - ck[:, 0]) / 100.0
+    assert 10.0 < np.median(dur_us) < 5000.0
+    ref, _ = _oracle_decode(w, streams=(0, 4))
+    _assert_close(out.cpu().numpy()[:4], ref, "clocked decode")
+    # the probe reads every byte once: the xor of all 16-byte words of a known pattern
+    n = 1 << 26
+    buf = torch.arange(n // 4, dtype=torch.int32, device=dev).view(torch.uint8)
+    sink = torch.zeros(8192, dtype=torch.int32, device=dev)
+    binding.read_probe(buf, sink)
+    torch.cuda.synchronize()
+    got = int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)))
+    want = int(np.bitwise_xor.reduce(np.arange(n // 4, dtype=np.uint32)))
+    assert got == want
