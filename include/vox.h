@@ -77,9 +77,9 @@ typedef struct {
   int32_t max_blocks_per_stream; /* row stride of block_tables */
   float scale;                   /* softmax scale applied to the fp32 dot product */
   int32_t decode_path;           /* VOX_PATH_* */
-  int32_t split_waves;           /* split-K: number of equal ranges (one per wave) the context
-                                    steps of all streams are cut into; 0 = one per wave the
-                                    chip keeps resident (1024), the balanced single round */
+  int32_t split_waves;           /* split-K: number of waves the context steps of all streams
+                                    are dealt to; 0 = one per wave the chip keeps resident
+                                    (1024), the balanced single round */
 } vox_shape_t;
 
 /*
@@ -133,8 +133,9 @@ size_t vox_paged_decode_workspace_bytes(const vox_shape_t* shape);
  *   out               : [S][Hq][D] fp32
  *   lse               : [S][Hq] fp32 or NULL
  * Split-K: the 32-token steps of all (stream, kv head) pairs are laid on one
- * axis and cut into equal ranges, one per wave; each run of a pair inside a
- * range leaves a partial softmax state in the workspace and a merge kernel
+ * axis and cut into ranges: equal ones, one per wave, plus (for long axes) a
+ * pool of short ones that waves take as they finish; each run of a pair inside
+ * a range leaves a partial softmax state in the workspace and a merge kernel
  * combines them.
  */
 int vox_paged_decode(const vox_shape_t* shape, const void* q, const void* k_pool,

@@ -28,8 +28,8 @@ int validate(const vox_shape_t* s) {
   return VOX_OK;
 }
 
-// Number of equal ranges the step axis is cut into: by default one per wave the decode
-// kernel keeps resident on the whole chip, so the launch is a single balanced round.
+// Number of waves the step axis is dealt to: by default one per wave the decode kernel keeps
+// resident on the whole chip, so the launch is a single balanced round.
 int split_waves(const vox_shape_t* s) {
   int w = s->split_waves ? s->split_waves : kDesignWaveSlots;
   return (w + kWavesPerGroup - 1) / kWavesPerGroup * kWavesPerGroup;
@@ -111,8 +111,8 @@ int make_plan(const vox_shape_t* s, const int32_t* lens_host, size_t workspace_b
   return VOX_OK;
 }
 
-// With exact host-side knowledge of the step count, N and Q travel as kernel arguments (the
-// plan kernel derives the same two numbers from the device lengths).
+// With exact host-side knowledge of the step count, the layout of the step axis travels as a
+// kernel argument (the plan kernel derives the same layout from the device lengths).
 void set_step_hints(Params* p, const Plan& plan) {
   if (!plan.exact) return;
   p->n_steps = (int32_t)plan.max_steps;

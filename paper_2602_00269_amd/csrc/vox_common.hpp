@@ -4,13 +4,14 @@
 // Split-K decomposition.  The context of stream s is walked in steps of 32 tokens (two KV
 // blocks); n_s = ceil(ceil(L_s / 16) / 2).  Segment sigma = s * Hkv + h owns n_s steps.  All
 // segments are laid end to end on one axis of N = Hkv * sum_s n_s global steps, and that axis
-// is cut into W equal ranges of Q = ceil(N / W) steps, one per wave.  A wave therefore reads the
-// same number of KV bytes as every other wave whatever the length mix, and a range may cover
-// the tail of one segment, several whole short segments and the head of another.  Every
-// maximal run of one segment inside one range yields one partial record (max, sum,
-// accumulator); runs are numbered along the axis, so the record of the run of segment sigma in
-// range w is slot w + sigma.  The merge kernel recomputes which ranges a segment crosses from
-// the prefix sums alone.
+// is cut into ranges (StepLayout below): W equal ones, one per wave, and for long axes a pool
+// of short ones that waves take as they finish.  A wave therefore starts with the same number
+// of KV bytes as every other wave whatever the length mix, and a range may cover the tail of
+// one segment, several whole short segments and the head of another.  Every maximal run of one
+// segment inside one range yields one partial record (max, sum, accumulator); ranges and runs
+// are numbered along the axis, so the record of the run of segment sigma in range r is slot
+// r + sigma.  The merge kernel recomputes which ranges a segment crosses from the prefix sums
+// and the layout alone.
 #pragma once
 
 #include <hip/hip_runtime.h>
