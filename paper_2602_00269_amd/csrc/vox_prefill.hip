@@ -52,7 +52,9 @@ __device__ inline float round_bf16(float a) { return (float)(__bf16)a; }
 
 // QL: the query rows live in LDS (each lane's own copy, read back by the same lane, so no
 // synchronisation is involved) instead of registers: room for more column groups per tile.
-template <int D, int NBUF, int NCG, bool QL = false>
+// REUSE: K/V loads are ordinary cacheable loads instead of streaming ones, for calls whose
+// tiles walk the same context several times (prompts): later tiles then hit the caches.
+template <int D, int NBUF, int NCG, bool QL = false, bool REUSE = false>
 struct MqMath {
   typedef MqDesc Desc;
   __device__ static int ga(const Desc& d) { return d.a.x; }
@@ -148,13 +150,13 @@ struct MqMath {
     const uint16_t* va = v_pool + (size_t)ga_ * (kBlock * D) + v_off;
     const uint16_t* vb = v_pool + (size_t)gb_ * (kBlock * D) + v_off;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) r.k[0][kk] = kv_load<STREAM>(ka + kk * 512);
+    for (int kk = 0; kk < KK; ++kk) r.k[0][kk] = kv_load<STREAM && !REUSE>(ka + kk * 512);
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) r.k[1][kk] = kv_load<STREAM>(kb + kk * 512);
+    for (int kk = 0; kk < KK; ++kk) r.k[1][kk] = kv_load<STREAM && !REUSE>(kb + kk * 512);
 #pragma unroll
-    for (int j = 0; j < KK; ++j) r.v[0][j] = kv_load<STREAM>(va + j * 128);
+    for (int j = 0; j < KK; ++j) r.v[0][j] = kv_load<STREAM && !REUSE>(va + j * 128);
 #pragma unroll
-    for (int j = 0; j < KK; ++j) r.v[1][j] = kv_load<STREAM>(vb + j * 128);
+    for (int j = 0; j < KK; ++j) r.v[1][j] = kv_load<STREAM && !REUSE>(vb + j * 128);
   }
 
   __device__ void reset(State& s) const {
@@ -655,11 +657,11 @@ int prefill_column_groups(const Params& p, int max_new_tokens) {
   return ncg;
 }
 
-template <int D, int NBUF, int NCG, bool QL = false>
+template <int D, int NBUF, int NCG, bool QL = false, bool REUSE = false>
 static void launch_mq(const Params& pk, unsigned grid, const void* q, const void* k_pool,
                       const void* v_pool, const int32_t* header, const MqDesc* desc, float2* pml,
                       float* pacc, hipStream_t st) {
-  hipLaunchKernelGGL((decode_kernel<MqMath<D, NBUF, NCG, QL>>), dim3(grid), dim3(256), 0, st, pk,
+  hipLaunchKernelGGL((decode_kernel<MqMath<D, NBUF, NCG, QL, REUSE>>), dim3(grid), dim3(256), 0, st, pk,
                      (const uint16_t*)q, (const uint16_t*)k_pool, (const uint16_t*)v_pool, header,
                      desc, pml, pacc);
 }
@@ -670,6 +672,8 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
                           float* lse, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
   const int tq = (kCols / p.G) * ncg;  // query tokens per tile
+  // most of the work re-reads contexts (several tiles per stream): keep K/V in the caches
+  const bool reuse = tiles >= 4 * (int64_t)p.S;
   int32_t* header = (int32_t*)(ws + m.header);
   int32_t* pt = (int32_t*)(ws + m.pt);
   int32_t* ps = (int32_t*)(ws + m.ps);
@@ -705,6 +709,9 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
     if (p.D == 128) {
       if (ncg == 6)
         launch_mq<128, 2, 6, true>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
+      else if (ncg == 4 && reuse)
+        launch_mq<128, 2, 4, false, true>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc,
+                                          st);
       else if (ncg == 4)
         launch_mq<128, 2, 4>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
       else if (ncg == 2)
@@ -712,7 +719,10 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
       else
         launch_mq<128, 3, 1>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
     } else {
-      if (ncg == 8)
+      if (ncg == 8 && reuse)
+        launch_mq<64, 2, 8, false, true>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc,
+                                         st);
+      else if (ncg == 8)
         launch_mq<64, 2, 8>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
       else if (ncg == 4)
         launch_mq<64, 2, 4>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
