@@ -32,9 +32,9 @@ METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 # scaled by what the same counter reads for a plain 1 GiB device copy); the runs are summarised
 # in profiles/*_<workload>*.txt.  Workloads without a counter run report null.
 MEASURED_TRAFFIC = {
-    "cfg3": 2356091427, "cfg4": 2730082938, "cfg5": 1103183884,
-    "chunk15": 2461071895, "chunk25": 4908707842, "chunk28": 2440519574, "admit": 3032587044,
-    "prefill": 512283406, "sample_small": 53909659, "sample_large": 330291029,
+    "cfg3": 2356073726, "cfg4": 2730018149, "cfg5": 1103168749,
+    "chunk15": 2445974104, "chunk25": 2580873658, "chunk28": 2428835636, "admit": 3018157471,
+    "prefill": 475259559, "sample_small": 53909659, "sample_large": 330291029,
 }
 
 
