@@ -45,6 +45,10 @@ Params make_params(const vox_shape_t* s) {
   p.P = s->num_blocks;
   p.max_nb = s->max_blocks_per_stream;
   p.scale_log2 = s->scale * 1.44269504088896340736f;
+  // A scale of zero (all scores equal) is replaced by one so small that every product with a
+  // dot product still vanishes next to 1 in the exponent: the kernels may then rely on
+  // scale * (+-inf) being an infinity, never NaN.
+  if (p.scale_log2 == 0.f) p.scale_log2 = 0x1p-100f;
   p.n_steps = -1;
   p.lay = layout_of(0, 1, false);
   p.waves = split_waves(s);
@@ -381,8 +385,13 @@ size_t vox_paged_prefill_workspace_bytes(const vox_shape_t* shape, int32_t total
   const int64_t slots = split_waves(shape) + tiles * shape->num_kv_heads;
   // the widest records any call with this many rows may use: a smaller largest chunk can pick a
   // wider tile than the largest possible one does
-  int ncg = prefill_column_groups(p, total_q);
-  if (p.D == 128 && total_q >= 5 * (16 / p.G) - (16 / p.G - 1) && ncg < 6) ncg = 6;
+  int ncg = 1;
+  const int tq = 16 / p.G;
+  for (int want = 1; want <= 32 && (want - 1) * tq < total_q; ++want) {
+    const int rows = want * tq < total_q ? want * tq : total_q;
+    const int c = prefill_column_groups(p, rows);
+    if (c > ncg) ncg = c;
+  }
   return map_prefill_workspace(p, ncg, tiles, total_q, slots, steps, split_waves(shape)).total;
 }
 

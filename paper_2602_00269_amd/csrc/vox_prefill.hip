@@ -9,6 +9,8 @@
 // only see tokens up to its own position, which matters in the last steps of a segment only.
 // Probabilities are split hi + lo as in the decode step, but as two output MFMAs per tile
 // instead of duplicated columns.
+#include <cfloat>
+
 #include "vox_decode_core.hpp"
 #include "vox_merge.hpp"
 
@@ -49,6 +51,21 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, v);
 }
 __device__ inline float round_bf16(float a) { return (float)(__bf16)a; }
+
+// max(x of this lane, x of lane ^ 16) and the same for lane ^ 32, through the lane-swap
+// instructions of gfx950 instead of a trip through LDS: after swapping the odd rows of 16
+// lanes of one copy with the even rows of the other (or the upper 32 lanes with the lower 32),
+// the two copies hold x of this lane's row and of its partner row, in one order or the other.
+__device__ inline float max_across_16(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float max_across_32(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
 // QL: the query rows live in LDS (each lane's own copy, read back by the same lane, so no
 // synchronisation is involved) instead of registers: room for more column groups per tile.
@@ -172,6 +189,12 @@ struct MqMath {
   __device__ void compute(State& s, Regs& r, const Desc& d) const {
     const int ntok = d.a.z & kMetaTokMask;
     const int cm0 = d.b.z;
+    // scores stay raw dot products until the exponent, exp2(raw * scale - max): the scale (times
+    // log2 e, never zero) is applied by the same fused multiply-add that subtracts the maximum.
+    // A hidden token gets the raw value whose product with the scale is -inf.
+    const float scale = p.scale_log2;
+    const bool positive = scale > 0.f;
+    const float hidden = positive ? -INFINITY : INFINITY;
     if (ntok < kStepTokens) {
       // slots past the tile's last token may hold any bits: clear their V values (every
       // column's probability there is zero, and 0 * NaN = NaN)
@@ -205,9 +228,9 @@ struct MqMath {
           sb = mfma32(r.k[1][kk], qv, sb);
         }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          t[b][e] = sa[e] * p.scale_log2;
-          t[b][4 + e] = sb[e] * p.scale_log2;
+        for (int e = 0; e < 4; ++e) {  // raw dot products: the scale enters with the exponent
+          t[b][e] = sa[e];
+          t[b][4 + e] = sb[e];
         }
       }
       if (cm0 + cg0 * tq < kStepTokens) {
@@ -218,20 +241,31 @@ struct MqMath {
           const int va = lim - 4 * c, vb = lim - kBlock - 4 * c;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            if (e >= va) t[b][e] = -INFINITY;
-            if (e >= vb) t[b][4 + e] = -INFINITY;
+            if (e >= va) t[b][e] = hidden;
+            if (e >= vb) t[b][4 + e] = hidden;
           }
         }
       }
+      // the largest scaled score of the lane is the scale times its largest or, under a
+      // negative scale, smallest raw one
       float mx[CB];
+      if (positive) {
 #pragma unroll
-      for (int b = 0; b < CB; ++b)
-        mx[b] = fmaxf(fmaxf(fmaxf(t[b][0], t[b][1]), fmaxf(t[b][2], t[b][3])),
-                      fmaxf(fmaxf(t[b][4], t[b][5]), fmaxf(t[b][6], t[b][7])));
+        for (int b = 0; b < CB; ++b)
+          mx[b] = fmaxf(fmaxf(fmaxf(t[b][0], t[b][1]), fmaxf(t[b][2], t[b][3])),
+                        fmaxf(fmaxf(t[b][4], t[b][5]), fmaxf(t[b][6], t[b][7])));
+      } else {
 #pragma unroll
-      for (int b = 0; b < CB; ++b) mx[b] = fmaxf(mx[b], __shfl_xor(mx[b], 16));
+        for (int b = 0; b < CB; ++b)
+          mx[b] = fminf(fminf(fminf(t[b][0], t[b][1]), fminf(t[b][2], t[b][3])),
+                        fminf(fminf(t[b][4], t[b][5]), fminf(t[b][6], t[b][7])));
+      }
 #pragma unroll
-      for (int b = 0; b < CB; ++b) mx[b] = fmaxf(mx[b], __shfl_xor(mx[b], 32));
+      for (int b = 0; b < CB; ++b) mx[b] *= scale;
+#pragma unroll
+      for (int b = 0; b < CB; ++b) mx[b] = max_across_16(mx[b]);
+#pragma unroll
+      for (int b = 0; b < CB; ++b) mx[b] = max_across_32(mx[b]);
       float alpha[CB];
       uint32_t ph[CB][4], pl[CB][4];
       bool rescale = false;
@@ -240,20 +274,25 @@ struct MqMath {
         const int cg = cg0 + b;
         const float m_new = fmaxf(s.m[cg], mx[b]);
         // a column may have seen no token yet (its run starts past its causal limit): keep
-        // the exponent arguments finite, everything it contributes is zero
-        const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+        // the exponent arguments from being inf - inf, everything it contributes is zero
+        const float m_ref = fmaxf(m_new, -FLT_MAX);
         alpha[b] = __builtin_amdgcn_exp2f(s.m[cg] - m_ref);
         rescale |= alpha[b] != 1.f;
         s.m[cg] = m_new;
         float psum = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(t[b][e] - m_ref);
-          const float p1 = __builtin_amdgcn_exp2f(t[b][e + 1] - m_ref);
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(t[b][e], scale, -m_ref));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(t[b][e + 1], scale, -m_ref));
           psum += p0 + p1;
-          const float h0 = round_bf16(p0), h1 = round_bf16(p1);
-          ph[b][e >> 1] = pack_bf16(h0, h1);
-          pl[b][e >> 1] = pack_bf16(p0 - h0, p1 - h1);
+          // hi = the upper 16 bits (truncation), lo = the exact remainder, truncated again:
+          // hi + lo carries 16 significant bits of p
+          const uint32_t b0 = __float_as_uint(p0), b1 = __float_as_uint(p1);
+          const float l0 = p0 - __uint_as_float(b0 & 0xFFFF0000u);
+          const float l1 = p1 - __uint_as_float(b1 & 0xFFFF0000u);
+          ph[b][e >> 1] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
+          pl[b][e >> 1] =
+              __builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u);
         }
         s.l[cg] = s.l[cg] * alpha[b] + psum;
       }
