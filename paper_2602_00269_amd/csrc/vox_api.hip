@@ -125,11 +125,7 @@ void set_step_hints(Params* p, const Plan& plan) {
 
 // The pool counter of layer l of a step (zeroed by the plan kernel).
 int32_t* pool_counter(const Plan& plan, char* ws, int layer) {
-#ifdef VOX_NO_POOL  // measurement builds: equal ranges only
-  return nullptr;
-#else
   return (int32_t*)(ws + plan.ws.header) + kHdrPoolCounters + layer;
-#endif
 }
 
 int enqueue_plan(const Params& p, const Plan& plan, char* ws, const int32_t* bt,
@@ -154,11 +150,12 @@ WsPtrs ws_ptrs(const Plan& plan, char* ws) {
                 (float*)(ws + plan.ws.partial_acc)};
 }
 
-// The split-K attention launch alone (the merge follows separately).
+// Append roles: rows that arrive as separate K and V tensors ...
 AppendArgs plain_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool) {
   return AppendArgs{(const uint16_t*)k_new, (const uint16_t*)v_new, (uint16_t*)k_pool,
                     (uint16_t*)v_pool, nullptr, nullptr, nullptr, nullptr};
 }
+// ... or as fused q|k|v rows that are rotated and split on the way (q goes to q_out).
 AppendArgs rope_append(const void* qkv, const float* rope_cos, const float* rope_sin, void* q_out,
                        void* k_pool, void* v_pool) {
   return AppendArgs{nullptr, nullptr, (uint16_t*)k_pool, (uint16_t*)v_pool, (const uint16_t*)qkv,
@@ -170,6 +167,7 @@ bool rope_table_ok(const vox_shape_t* s, int32_t rope_positions) {
   return rope_positions >= s->max_blocks_per_stream * kBlock;
 }
 
+// The split-K attention launch alone (the merge follows separately).
 int enqueue_attention(const vox_shape_t* s, const Params& p, const Plan& plan, const WsPtrs& w,
                       const void* q, const void* k_pool, const void* v_pool, hipStream_t st,
                       hipEvent_t ev_before = nullptr, hipEvent_t ev_after = nullptr) {

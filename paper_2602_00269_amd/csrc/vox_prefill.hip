@@ -18,12 +18,10 @@ namespace vox {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kCols = 16;   // MFMA columns of one column group
-constexpr int kBatch = 2;   // column groups whose stages are interleaved in one step  // MFMA columns = record columns of the multi-token step
+constexpr int kBatch = 2;   // column groups whose stages are interleaved in one step
 
 // Step descriptor of the multi-token step (32 bytes, wave-uniform).
 //   a: granule of block A, granule of block B, meta (valid tokens | first | last), segment
@@ -41,16 +39,6 @@ __device__ inline f32x4 mfma32(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
-__device__ inline f32x4 mfma16(u32x2 a, u32x2 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a),
-                                                   __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
-}
-__device__ inline uint32_t pack_bf16(float a, float b) {
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  bf16x2 v = {(__bf16)a, (__bf16)b};
-  return __builtin_bit_cast(uint32_t, v);
-}
-__device__ inline float round_bf16(float a) { return (float)(__bf16)a; }
 
 // max(x of this lane, x of lane ^ 16) and the same for lane ^ 32, through the lane-swap
 // instructions of gfx950 instead of a trip through LDS: after swapping the odd rows of 16
