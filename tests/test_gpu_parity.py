@@ -746,6 +746,61 @@ def test_sampling_ties_mixed_settings_and_no_window(dev):
             assert tok[0] == 1000  # greedy: the lowest id among the tied maxima
 
 
+@pytest.mark.parametrize("kind", synth.MULTI_NAMES)
+def test_multi_token_bench_workloads_match_oracle_on_sampled_streams(dev, kind):
+    # the workloads bench.py times, at full size and in its launch configuration: the append is
+    # compared bit for bit on whole pools, the attention on every row of sampled streams (the
+    # longest, the shortest, the one with most new tokens and a few seeded ones)
+    m = synth.make_multi_workload(kind, device=dev)
+    w, qo = m.base, m.q_offsets
+    sh = binding.shape_of(w)
+    bt, lens_d, qo_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev), _i32(qo, dev)
+    kp_ref, vp_ref = _host_pools(w)
+    oracle.kv_append_multi(bits_of(m.k_new), bits_of(m.v_new), kp_ref, vp_ref, w.block_tables,
+                           w.context_lens, qo, head_dim=w.head_dim)
+    binding.kv_append_multi(sh, m.k_new, m.v_new, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d)
+    tq = m.total_q
+    out = torch.full((tq, w.num_q_heads, w.head_dim), float("nan"), device=dev)
+    lse = torch.full((tq, w.num_q_heads), float("nan"), device=dev)
+    ws = torch.empty(binding.paged_prefill_workspace_bytes(sh, tq), dtype=torch.uint8, device=dev)
+    binding.paged_prefill(sh, m.q, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d, w.context_lens, qo,
+                          out, ws, lse=lse)
+    torch.cuda.synchronize()
+    kp, vp = _host_pools(w)
+    assert np.array_equal(kp, kp_ref) and np.array_equal(vp, vp_ref)
+    del kp, vp
+    got, got_lse = out.cpu().numpy(), lse.cpu().numpy()
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(5)
+    n = m.new_tokens
+    pick = {int(np.argmax(w.context_lens)), int(np.argmin(w.context_lens)), int(np.argmax(n)),
+            *rng.choice(w.num_streams, 4, replace=False).tolist()}
+    pick = sorted(i for i in pick if n[i] > 0)
+    rows = np.concatenate([np.arange(qo[i], qo[i + 1]) for i in pick])
+    sub_qo = np.zeros(len(pick) + 1, dtype=np.int32)
+    sub_qo[1:] = np.cumsum(n[pick])
+    ref, ref_lse = oracle.paged_prefill(bits_of(m.q)[rows], kp_ref, vp_ref, w.block_tables[pick],
+                                        w.context_lens[pick], sub_qo, w.scale,
+                                        num_kv_heads=w.num_kv_heads)
+    _assert_close(got[rows], ref, f"{kind} streams {pick}")
+    _assert_lse(got_lse[rows], ref_lse, f"{kind} streams {pick}")
+
+
+@pytest.mark.parametrize("workload", ["sample_small", "sample_large"])
+def test_sampling_bench_workloads_are_bit_exact(dev, workload):
+    # the two sampling workloads bench.py times, at full size, every stream against the oracle
+    s, v, preset = {"sample_small": (1024, 6564, "cosyvoice"),
+                    "sample_large": (256, 156940, "orpheus")}[workload]
+    temperature, top_p, top_k, penalty = synth.SAMPLING_PRESETS[preset]
+    logits = synth.make_logits(s, v, seed=0x5EED0200, device=dev)
+    hist = synth.make_history(s, v, 64, seed=0x5EED0210)
+    u = synth.make_uniforms(s, seed=0x5EED0211)
+    tok, kept, ref_tok, ref_kept = _sample_both(dev, logits, temperature, top_p, penalty, top_k,
+                                                u, hist)
+    assert np.array_equal(kept, ref_kept)
+    assert np.array_equal(tok, ref_tok)
+
+
 def test_multi_token_step_at_the_ends_of_its_range(dev):
     # one long prompt from scratch (many tiles, ranges cut through tiles) and thousands of
     # streams with 0, 1 or 2 new tokens
