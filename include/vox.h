@@ -160,10 +160,11 @@ int vox_paged_decode_profiled(const vox_shape_t* shape, const void* q, const voi
                               uint64_t* wave_clock);
 
 /*
- * Measurement aid: reads `bytes` (a multiple of 16) of device memory at buf once, 16 bytes per
- * lane with the same streaming loads the attention kernel uses, and writes one word per
- * workgroup to sink (device, at least 8192 * 4 bytes): the streaming-read rate this chip
- * reaches with no arithmetic at all.
+ * Measurement aid: reads `bytes` (a multiple of 16) of device memory at buf once with the
+ * attention kernel's memory pipeline and none of its arithmetic (one wave per SIMD, contiguous
+ * shares, 16 KB steps of 16-byte streaming loads, three steps in flight per wave), and xors
+ * one word per workgroup into sink (device, at least 8192 * 4 bytes, zeroed by the caller):
+ * the streaming-read rate this chip reaches when nothing else is in the way.
  */
 int vox_read_probe(const void* buf, size_t bytes, void* sink, void* hip_stream);
 

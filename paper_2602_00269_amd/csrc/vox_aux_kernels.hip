@@ -340,18 +340,60 @@ __global__ __launch_bounds__(256) void merge_append_kernel(
     any_append_role<D>(p, blockIdx.x - merge_grps, a, bt, lens);
 }
 
-// Streaming-read probe: every thread walks the buffer with a grid stride, 16 bytes per load.
-__global__ __launch_bounds__(256) void read_probe_kernel(const au32x4* __restrict__ buf,
-                                                         size_t vecs,
-                                                         uint32_t* __restrict__ sink) {
+// Streaming-read probe with the attention kernel's memory pipeline and none of its arithmetic:
+// one wave per SIMD of the chip, each walks a contiguous share of the buffer in 16 KB steps
+// (16 loads of 16 bytes per lane, every load instruction one contiguous KB) through a ring of
+// three steps in flight, and only xors what arrives.  The buffer's tail that is no whole step
+// is read by a plain strided loop.
+constexpr int kProbeStepVecs = 1024;  // 16-byte vectors per step
+constexpr int kProbeRing = 3;
+constexpr int kProbeGroups = kDesignWaveSlots / kWavesPerGroup;
+
+__global__ __launch_bounds__(256, 1) void read_probe_kernel(const au32x4* __restrict__ buf,
+                                                            size_t vecs,
+                                                            uint32_t* __restrict__ sink) {
+  constexpr int kLoads = kProbeStepVecs / kWave;
+  const int lane = threadIdx.x & (kWave - 1);
+  const size_t w = (size_t)blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
+  const size_t waves = (size_t)gridDim.x * kWavesPerGroup;
+  const size_t steps = vecs / kProbeStepVecs;
+  const size_t per = (steps + waves - 1) / waves;
+  const size_t s0 = min(steps, w * per), s1 = min(steps, s0 + per);
+  const long long n = (long long)(s1 - s0);
+  const au32x4* base = buf + s0 * kProbeStepVecs + lane;
   au32x4 acc = {0, 0, 0, 0};
+  au32x4 ring[kProbeRing][kLoads];
+  // refills past the share's end re-read its first step (in range, cache resident) and are
+  // dropped, so that the steady loop carries no condition around its loads
+#define VOX_PROBE_FILL(B, I)                                                          \
+  {                                                                                   \
+    const au32x4* src = base + ((I) < n ? (size_t)(I) : 0) * kProbeStepVecs;           \
+    _Pragma("unroll") for (int j = 0; j < kLoads; ++j) ring[B][j] =                    \
+        __builtin_nontemporal_load(src + j * kWave);                                  \
+  }
+  if (n > 0) {
+#pragma unroll
+    for (int b = 0; b < kProbeRing; ++b) VOX_PROBE_FILL(b, b)
+    for (long long i0 = 0; i0 < n; i0 += kProbeRing) {
+#pragma unroll
+      for (int b = 0; b < kProbeRing; ++b) {
+        if (i0 + b < n) {
+#pragma unroll
+          for (int j = 0; j < kLoads; ++j) acc ^= ring[b][j];
+        }
+        VOX_PROBE_FILL(b, i0 + b + kProbeRing)
+      }
+    }
+  }
+#undef VOX_PROBE_FILL
   const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < vecs; i += stride)
+  for (size_t i = steps * kProbeStepVecs + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < vecs;
+       i += stride)
     acc ^= __builtin_nontemporal_load(buf + i);
   uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) x ^= __shfl_xor(x, o);
-  if ((threadIdx.x & (kWave - 1)) == 0) atomicXor(&sink[blockIdx.x], x);
+  if (lane == 0) atomicXor(&sink[blockIdx.x], x);
 }
 
 }  // namespace
@@ -444,7 +486,7 @@ hipError_t launch_merge_append(const Params& p, const int32_t* header, const int
 }
 
 hipError_t launch_read_probe(const void* buf, size_t bytes, void* sink, hipStream_t st) {
-  hipLaunchKernelGGL(read_probe_kernel, dim3(8192), dim3(256), 0, st, (const au32x4*)buf,
+  hipLaunchKernelGGL(read_probe_kernel, dim3(kProbeGroups), dim3(256), 0, st, (const au32x4*)buf,
                      bytes / 16, (uint32_t*)sink);
   return hipGetLastError();
 }
