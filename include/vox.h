@@ -41,6 +41,10 @@
  * for the default stream) and returns: no synchronisation, no host copies.
  * Contents of device-resident block_tables / context_lens are trusted (block
  * ids outside [0,P) or L_s > max_blocks_per_stream*B are undefined behaviour).
+ * Row tensors (q, k_new, v_new, qkv, q_out), the pools, the rotary tables and
+ * the fp32 outputs are read and written 16 bytes at a time: their base
+ * addresses must be multiples of 16 (VOX_ERR_ARG otherwise); int32 / int64 /
+ * float arrays of per-stream scalars need only their natural alignment.
  *
  * Every function returns VOX_OK (0) or a negative VOX_ERR_* code; the host-side
  * checks (null pointers, shape rules, workspace size) run before any launch.
@@ -60,7 +64,7 @@ extern "C" {
 #define VOX_ERR_SHAPE (-2)     /* S<=0, S>8192, Hq%Hkv!=0, G>8, D not in {64,128}, B!=16, P<=0, ... */
 #define VOX_ERR_WORKSPACE (-3) /* workspace too small for the steps of this call */
 #define VOX_ERR_HIP (-4)       /* a launch failed; hipGetLastError() still holds the cause */
-#define VOX_ERR_ARG (-5)       /* a scalar argument is out of range */
+#define VOX_ERR_ARG (-5)       /* a scalar argument is out of range, or a misaligned tensor */
 
 /* Which decode kernel family runs; both give results within the same tolerance. */
 #define VOX_PATH_AUTO 0 /* the library's choice (MFMA) */

@@ -28,6 +28,13 @@ int validate(const vox_shape_t* s) {
   return VOX_OK;
 }
 
+// Rows, pools and outputs are accessed with 16-byte vector loads and stores.
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+template <class... T>
+bool all_aligned16(const T*... ptrs) {
+  return (aligned16(ptrs) && ...);
+}
+
 // Number of waves the step axis is dealt to: by default one per wave the decode kernel keeps
 // resident on the whole chip, so the launch is a single balanced round.
 int split_waves(const vox_shape_t* s) {
@@ -201,6 +208,7 @@ int vox_kv_append(const vox_shape_t* shape, const void* k_new, const void* v_new
   if (int rc = validate(shape)) return rc;
   if (!k_new || !v_new || !k_pool || !v_pool || !block_tables || !context_lens)
     return VOX_ERR_NULL;
+  if (!all_aligned16(k_new, v_new, k_pool, v_pool)) return VOX_ERR_ARG;
   const Params p = make_params(shape);
   return launch_append(p, plain_append(k_new, v_new, k_pool, v_pool), block_tables, context_lens,
                        (hipStream_t)hip_stream) == hipSuccess
@@ -214,6 +222,7 @@ int vox_kv_gather(const vox_shape_t* shape, const void* k_pool, const void* v_po
   if (int rc = validate(shape)) return rc;
   if (!k_pool || !v_pool || !block_tables || !context_lens || !row_offsets || !k_out || !v_out)
     return VOX_ERR_NULL;
+  if (!all_aligned16(k_pool, v_pool, k_out, v_out)) return VOX_ERR_ARG;
   const Params p = make_params(shape);
   return launch_kv_gather(p, k_pool, v_pool, block_tables, context_lens, row_offsets, k_out,
                           v_out, (hipStream_t)hip_stream) == hipSuccess
@@ -244,7 +253,7 @@ int vox_paged_decode_profiled(const vox_shape_t* shape, const void* q, const voi
   if (int rc = validate(shape)) return rc;
   if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out || !workspace)
     return VOX_ERR_NULL;
-  if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
+  if ((uintptr_t)workspace % 256 || !all_aligned16(q, k_pool, v_pool, out)) return VOX_ERR_ARG;
   Plan plan;
   if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
   Params p = make_params(shape);
@@ -277,6 +286,8 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
     if (!q[l] || !k_new[l] || !v_new[l] || !k_pool[l] || !v_pool[l] || !out[l])
       return VOX_ERR_NULL;
   if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
+  for (int l = 0; l < num_layers; ++l)
+    if (!all_aligned16(q[l], k_new[l], v_new[l], k_pool[l], v_pool[l], out[l])) return VOX_ERR_ARG;
   Plan plan;
   if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
   Params p = make_params(shape);
@@ -323,6 +334,7 @@ int vox_rope_append(const vox_shape_t* shape, const void* qkv, const float* rope
       !context_lens)
     return VOX_ERR_NULL;
   if (!rope_table_ok(shape, rope_positions)) return VOX_ERR_ARG;
+  if (!all_aligned16(qkv, rope_cos, rope_sin, q_out, k_pool, v_pool)) return VOX_ERR_ARG;
   const Params p = make_params(shape);
   return launch_append(p, rope_append(qkv, rope_cos, rope_sin, q_out, k_pool, v_pool),
                        block_tables, context_lens, (hipStream_t)hip_stream) == hipSuccess
@@ -344,7 +356,9 @@ int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const voi
   for (int l = 0; l < num_layers; ++l)
     if (!qkv[l] || !q_rot[l] || !k_pool[l] || !v_pool[l] || !out[l]) return VOX_ERR_NULL;
   if (!rope_table_ok(shape, rope_positions)) return VOX_ERR_ARG;
-  if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
+  if ((uintptr_t)workspace % 256 || !all_aligned16(rope_cos, rope_sin)) return VOX_ERR_ARG;
+  for (int l = 0; l < num_layers; ++l)
+    if (!all_aligned16(qkv[l], q_rot[l], k_pool[l], v_pool[l], out[l])) return VOX_ERR_ARG;
   Plan plan;
   if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
   Params p = make_params(shape);
@@ -402,6 +416,7 @@ int vox_kv_append_multi(const vox_shape_t* shape, const void* k_new, const void*
   if (total_q == 0) return VOX_OK;  // no rows: the row arrays may be empty (NULL)
   if (!k_new || !v_new || !k_pool || !v_pool || !block_tables || !context_lens || !q_offsets)
     return VOX_ERR_NULL;
+  if (!all_aligned16(k_new, v_new, k_pool, v_pool)) return VOX_ERR_ARG;
   const Params p = make_params(shape);
   return launch_kv_append_multi(p, total_q, k_new, v_new, k_pool, v_pool, block_tables,
                                 context_lens, q_offsets, (hipStream_t)hip_stream) == hipSuccess
@@ -433,7 +448,7 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
   if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !q_offsets || !out ||
       !workspace)
     return VOX_ERR_NULL;
-  if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
+  if ((uintptr_t)workspace % 256 || !all_aligned16(q, k_pool, v_pool, out)) return VOX_ERR_ARG;
   const Params p = make_params(shape);
   // exact tile and step counts from the host copies (the scheduler that admits a prompt
   // knows its length)
@@ -479,7 +494,7 @@ const char* vox_strerror(int code) {
     case VOX_ERR_SHAPE: return "unsupported shape (need Hq % Hkv == 0, Hq/Hkv <= 8, head_dim 64 or 128, block_size 16, 0 < streams <= 8192, positive sizes)";
     case VOX_ERR_WORKSPACE: return "workspace too small (see vox_paged_decode_workspace_bytes)";
     case VOX_ERR_HIP: return "a HIP launch failed (see hipGetLastError)";
-    case VOX_ERR_ARG: return "a scalar argument is out of range";
+    case VOX_ERR_ARG: return "a scalar argument is out of range, or a tensor is not 16-byte aligned";
     default: return "unknown vox error code";
   }
 }

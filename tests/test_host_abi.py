@@ -83,6 +83,17 @@ def test_null_pointers_and_bad_scalars(lib):
     # misaligned workspace
     assert lib.vox_paged_decode(ctypes.byref(sh), one, one, one, one, one, None, one, None,
                                 ctypes.c_void_p(257), 1 << 20, None) == -5
+    # tensors are accessed 16 bytes at a time: a base address that is no multiple of 16 is refused
+    odd = ctypes.c_void_p(264)
+    assert lib.vox_kv_append(ctypes.byref(sh), odd, one, one, one, one, one, None) == -5
+    assert lib.vox_kv_append(ctypes.byref(sh), one, one, one, odd, one, one, None) == -5
+    assert lib.vox_paged_decode(ctypes.byref(sh), odd, one, one, one, one, None, one, None, one,
+                                1 << 20, None) == -5
+    assert lib.vox_paged_decode(ctypes.byref(sh), one, one, one, one, one, None, odd, None, one,
+                                1 << 20, None) == -5
+    assert lib.vox_kv_gather(ctypes.byref(sh), one, one, one, one, one, odd, one, None) == -5
+    assert lib.vox_kv_append_multi(ctypes.byref(sh), one, odd, one, one, one, one, one, 3,
+                                   None) == -5
 
 
 def test_multi_token_calls_validate_on_the_host(lib):
