@@ -62,6 +62,8 @@ Params make_params(const vox_shape_t* s) {
   p.pool_counter = nullptr;
   p.ranges_off = 0;
   p.wave_clock = nullptr;
+  p.out = nullptr;
+  p.lse = nullptr;
   return p;
 }
 

@@ -37,6 +37,9 @@ constexpr int kDesignWaveSlots = 256 * kWavesPerGroup;  // 256 CUs x 1 workgroup
 constexpr int kMetaFirst = 1 << 8;
 constexpr int kMetaLast = 1 << 9;
 constexpr int kMetaTail = 1 << 10;  // last step of its stream: holds the block appended to
+// multi-token step, on a segment's last step: the whole segment is this one run, its rows go
+// straight to the output
+constexpr int kMetaWhole = 1 << 11;
 constexpr int kMetaTokMask = 63;
 
 // header words
@@ -126,7 +129,7 @@ struct Workspace {
 
 // Workspace map of the multi-token (prefill / chunk) step.
 struct PrefillWorkspace {
-  size_t header, ranges, pt, ps, tile_first, tile_steps, tile_info, seg_runs, row_tile,
+  size_t header, ranges, pt, ps, tile_first, tile_steps, tile_info, split_list,
       partial_ml, partial_acc, desc, total;
 };
 
@@ -148,6 +151,10 @@ struct Params {
   // Measurement aid: when not null, wave w stores the chip's constant-rate clock at its start
   // and end in wave_clock[2w], wave_clock[2w+1]
   unsigned long long* wave_clock;
+  // Multi-token step: where runs that are whole segments write their finished rows
+  // ([rows][Hq][D] fp32 and, if not null, [rows][Hq] log-sum-exp)
+  float* out;
+  float* lse;
 };
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -18,7 +18,8 @@
 //   used_columns(desc): leading record columns that carry query rows (the rest is not stored);
 //   finish(State&, float* acc, float* ml): writes the run's [columns][D] accumulators to acc
 //   and its [columns] (max, sum) pairs to ml (an LDS record, or global memory when a record
-//   does not fit the LDS buffer).
+//   does not fit the LDS buffer); kDirect: a step may carry kMetaWhole (its run is the whole
+//   segment), then finish_rows(State&, desc) writes the finished rows instead of a record.
 #pragma once
 
 #include "vox_common.hpp"
@@ -155,7 +156,11 @@ __global__ __launch_bounds__(256, Math::kMinWavesPerSimd) void decode_kernel(
                                 more ? Math::gb(dq[NBUF]) : 0);                            \
     }                                                                                      \
     if (meta & kMetaLast) {                                                                \
-      if (stash.cap > 0) {                                                                 \
+      bool whole = false; /* the run is its whole segment: finished rows, no partial record */ \
+      if constexpr (Math::kDirect) whole = (meta & kMetaWhole) != 0;                       \
+      if (whole) {                                                                         \
+        if constexpr (Math::kDirect) math.finish_rows(st, dcur);                           \
+      } else if (stash.cap > 0) {                                                          \
         float* rec = stash.next(pml, pacc);                                                \
         math.finish(st, rec, rec + stash.gd);                                              \
         stash.commit(range + sigma, math.used_columns(dcur));                              \

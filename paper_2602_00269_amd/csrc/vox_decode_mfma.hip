@@ -61,6 +61,7 @@ struct MfmaMath {
   __device__ static int columns(const Params& p) { return p.G; }
 
   static constexpr int kBuffers = NBUF;
+  static constexpr bool kDirect = false;  // every run leaves a partial record for the merge
   static constexpr int kStashFloats = 4096;  // 16 KB per wave: several decode records
   static constexpr int kMinWavesPerSimd = 1;
   static constexpr int KK = D / 32;  // score MFMAs per block = V loads per block

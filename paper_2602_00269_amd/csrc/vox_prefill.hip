@@ -35,6 +35,15 @@ struct TileInfo {
   int32_t stream, q_row0, nq, pos0;
 };
 
+// A segment that was cut into several runs, for the merge: entry w of the list belongs to the
+// segment whose first step lies in range w and that runs on past it (at most one per range);
+// nruns == 0: no such segment.
+struct SplitSegment {
+  int32_t slot0, nruns;  // its partial records: slots slot0 .. slot0 + nruns - 1
+  int32_t q_row0, nq;    // query rows of its tile
+  int32_t h, pad0, pad1, pad2;
+};
+
 __device__ inline f32x4 mfma32(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -69,6 +78,8 @@ struct MqMath {
   __device__ static int columns(const Params&) { return kCols * NCG; }
 
   static constexpr int kBuffers = NBUF;
+  // a run that is its whole segment writes finished rows instead of a partial record
+  static constexpr bool kDirect = true;
   // 39 KB per wave (all four waves: 156 of the CU's 160 KB): 4, 2, 1 records at head_dim 128
   // with 1, 2, 4 column groups; 9, 4, 2, 1 at head_dim 64 with 1, 2, 4, 8.  With the query rows
   // in LDS there is no room for records: they go straight to global memory.
@@ -334,6 +345,31 @@ struct MqMath {
         *reinterpret_cast<float2*>(ml + 2 * (cg * kCols + n)) = make_float2(s.m[cg], l);
     }
   }
+
+  // Rows of a run that was its whole segment, normalised: out = acc / sum and the log-sum-exp
+  // (max + log2 sum) ln 2, what the merge of a single partial record would give.
+  // Straight from the accumulators, as the step that ends the run: no trip through LDS.
+  __device__ void finish_rows(State& s, const Desc& d) const {
+#pragma unroll
+    for (int cg = 0; cg < NCG; ++cg) {
+      float l = s.l[cg];
+      l += __shfl_xor(l, 16);
+      l += __shfl_xor(l, 32);
+      const int tok = cg * tq + jcol;
+      if (jcol >= tq || tok >= d.b.y) continue;
+      const float inv = l > 0.f ? 1.f / l : 0.f;
+      const size_t row = (size_t)(d.b.x + tok) * p.Hq + d.b.w * p.G + gcol;
+      float* mine = p.out + row * D + 8 * c;
+#pragma unroll
+      for (int j = 0; j < KK; ++j) {
+        const f32x4 e = s.acc[cg][2 * j] * inv, o = s.acc[cg][2 * j + 1] * inv;
+        *reinterpret_cast<f32x4*>(mine + 32 * j) = f32x4{e[0], o[0], e[1], o[1]};
+        *reinterpret_cast<f32x4*>(mine + 32 * j + 4) = f32x4{e[2], o[2], e[3], o[3]};
+      }
+      if (p.lse && c == 0)
+        p.lse[row] = l > 0.f ? (s.m[cg] + log2f(l)) * 0.69314718055994530942f : -INFINITY;
+    }
+  }
 };
 
 // ---------------------------------------------------------------------------------------
@@ -408,8 +444,7 @@ __global__ __launch_bounds__(256) void mq_tiles_kernel(
     Params p, int tq, const int32_t* __restrict__ lens, const int32_t* __restrict__ qo,
     const int32_t* __restrict__ header, const int32_t* __restrict__ pt,
     const int32_t* __restrict__ ps, int32_t* __restrict__ tile_first,
-    int32_t* __restrict__ tile_steps, TileInfo* __restrict__ tile_info,
-    int32_t* __restrict__ row_tile) {
+    int32_t* __restrict__ tile_steps, TileInfo* __restrict__ tile_info) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   const int total = pt[p.S];
   if (t >= total) return;
@@ -433,7 +468,6 @@ __global__ __launch_bounds__(256) void mq_tiles_kernel(
   info.nq = min(tq, n - tau * tq);
   info.pos0 = L - n + tau * tq;
   tile_info[t] = info;
-  for (int j = 0; j < info.nq; ++j) row_tile[info.q_row0 + j] = t;
   if (t == total - 1) tile_first[total] = ps[p.S] * p.Hkv;
 }
 
@@ -454,10 +488,12 @@ __device__ inline int64_t segment_first(const int32_t* tile_first, const int32_t
 __global__ __launch_bounds__(256) void mq_ranges_kernel(
     Params p, int waves, int run_cost, const int32_t* __restrict__ header,
     const int32_t* __restrict__ pt, const int32_t* __restrict__ tile_first,
-    const int32_t* __restrict__ tile_steps, int32_t* __restrict__ ranges) {
+    const int32_t* __restrict__ tile_steps, int32_t* __restrict__ ranges,
+    SplitSegment* __restrict__ split) {
   const int w = blockIdx.x * blockDim.x + threadIdx.x;
   const int launched = (waves + kWavesPerGroup - 1) / kWavesPerGroup * kWavesPerGroup;
   if (w > launched) return;  // waves past `waves` exist only to fill a workgroup: empty ranges
+  if (w < waves) split[w].nruns = 0;  // the expand kernel fills in the cut segments
   const int N = header[kHdrSteps];
   const int segments = pt[p.S] * p.Hkv;
   const int64_t total = (int64_t)N + (int64_t)run_cost * segments;
@@ -500,7 +536,7 @@ __global__ __launch_bounds__(256) void mq_expand_kernel(
     const int32_t* __restrict__ pt, const int32_t* __restrict__ tile_first,
     const int32_t* __restrict__ tile_steps, const TileInfo* __restrict__ tile_info,
     const int32_t* __restrict__ ranges, int waves, MqDesc* __restrict__ desc,
-    int2* __restrict__ seg_runs) {
+    SplitSegment* __restrict__ split) {
   const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int N = header[kHdrSteps];
   if (x >= N) return;
@@ -525,49 +561,60 @@ __global__ __launch_bounds__(256) void mq_expand_kernel(
   const int w = owner_wave(ranges, waves, x);
   if (st == 0 || x == ranges[w]) meta |= kMetaFirst;
   if (st == f - 1 || x == ranges[w + 1] - 1) meta |= kMetaLast;
+  // the segment's last step in the range that also holds its first: one run, no partial record
+  if (st == f - 1 && x - st >= ranges[w]) meta |= kMetaWhole;
   MqDesc d;
   d.a = make_int4(ida * p.Hkv + h, idb * p.Hkv + h, meta, t * p.Hkv + h);
   d.b = make_int4(info.q_row0, info.nq, info.pos0 + 1 - kStepTokens * st, h);
   desc[x] = d;
   if (st == 0) {  // the segment's runs: waves w .. owner of its last step, slots w + sigma ..
     const int w1 = owner_wave(ranges, waves, min((int64_t)N, x + f) - 1);
-    seg_runs[t * p.Hkv + h] = make_int2(w + t * p.Hkv + h, w1 - w + 1);
+    // a segment cut into several runs is the last one that starts in range w: entry w
+    if (w1 > w) {
+      SplitSegment e;
+      e.slot0 = w + t * p.Hkv + h;
+      e.nruns = w1 - w + 1;
+      e.q_row0 = info.q_row0;
+      e.nq = info.nq;
+      e.h = h;
+      e.pad0 = e.pad1 = e.pad2 = 0;
+      split[w] = e;
+    }
   }
 }
 
 // ---------------------------------------------------------------------------------------
-// Merge: one wave per (query row, q head).
+// Merge of the segments that were cut into several runs (the others wrote their rows
+// themselves): workgroup (w, y) takes entry w of the list, its four waves columns 4y .. 4y+3
+// of the segment's records, one (query row, q head) each.
 template <int D>
 __global__ __launch_bounds__(256) void mq_merge_kernel(
-    Params p, int total_q, int ncg, const int2* __restrict__ seg_runs,
-    const TileInfo* __restrict__ tile_info, const int32_t* __restrict__ row_tile,
-    const float2* __restrict__ pml, const float* __restrict__ pacc, float* __restrict__ out,
-    float* __restrict__ lse) {
+    Params p, int ncg, const SplitSegment* __restrict__ split, const float2* __restrict__ pml,
+    const float* __restrict__ pacc, float* __restrict__ out, float* __restrict__ lse) {
+  const SplitSegment e = split[blockIdx.x];
+  if (e.nruns == 0) return;
   const int lane = threadIdx.x & (kWave - 1);
-  const int w = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
-  if (w >= total_q * p.Hq) return;
-  const int row = w / p.Hq, i = w % p.Hq;
-  const int h = i / p.G, g = i % p.G;
-  const int t = row_tile[row];
-  const int q_row0 = tile_info[t].q_row0;
-  const int2 runs = seg_runs[t * p.Hkv + h];  // first slot, number of runs (every tile has steps)
-  const int tqg = kCols / p.G, j = row - q_row0;  // column group j / tqg, column inside it
-  const int col = (j / tqg) * kCols + (j % tqg) * p.G + g;
-  merge_runs<D>(pml, pacc, runs.x, runs.y, kCols * ncg, col, lane, out + (size_t)w * D,
+  const int col = blockIdx.y * kWavesPerGroup + (threadIdx.x >> 6);
+  const int tqg = kCols / p.G;  // tokens per column group
+  const int nn = col & (kCols - 1), j = nn / p.G, g = nn - j * p.G;
+  const int tok = (col / kCols) * tqg + j;
+  if (j >= tqg || tok >= e.nq) return;  // a column without a query row
+  const size_t w = (size_t)(e.q_row0 + tok) * p.Hq + e.h * p.G + g;
+  merge_runs<D>(pml, pacc, e.slot0, e.nruns, kCols * ncg, col, lane, out + w * D,
                 lse ? lse + w : nullptr);
 }
 
 // ---------------------------------------------------------------------------------------
-// Multi-token append: one wave per (new row, kv head).
+// Multi-token append: one wave per new row, all kv heads of it (the search for the row's stream
+// and the table entry are paid once per row, and every lane has bytes to move).
 template <int D>
 __global__ __launch_bounds__(256) void kv_append_multi_kernel(
     Params p, int total_q, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
     uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool, const int32_t* __restrict__ bt,
     const int32_t* __restrict__ lens, const int32_t* __restrict__ qo) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int w = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
-  if (w >= total_q * p.Hkv) return;
-  const int row = w / p.Hkv, h = w % p.Hkv;
+  const int row = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
+  if (row >= total_q) return;
   // largest s with qo[s] <= row, found by the whole wave: 64 probes per round trip to memory
   int a = 0, b = p.S;
   while (b - a > 1) {
@@ -584,36 +631,45 @@ __global__ __launch_bounds__(256) void kv_append_multi_kernel(
   if (pos < 0) return;
   const int64_t blk = bt[(int64_t)s * p.max_nb + (pos >> 4)];
   const int t = pos & (kBlock - 1);
-  const size_t g = granule_offset(blk, h, p.Hkv, D);
-  const uint16_t* krow = k_new + (size_t)w * D;
-  const uint16_t* vrow = v_new + (size_t)w * D;
-  if (lane < D / 8)
-    *reinterpret_cast<u32x4*>(k_pool + g + k_elem(t, lane * 8)) =
-        *reinterpret_cast<const u32x4*>(krow + lane * 8);
+  const uint16_t* krow = k_new + (size_t)row * p.Hkv * D;  // [Hkv][D] of this row
+  const uint16_t* vrow = v_new + (size_t)row * p.Hkv * D;
+  // K: 16 bytes per lane, D/8 lanes per head, 512/D heads per pass
+  constexpr int kLanesK = D / 8, kHeadsK = kWave / kLanesK;
+  for (int h0 = 0; h0 < p.Hkv; h0 += kHeadsK) {
+    const int h = h0 + lane / kLanesK, d = (lane % kLanesK) * 8;
+    if (h < p.Hkv)
+      *reinterpret_cast<u32x4*>(k_pool + granule_offset(blk, h, p.Hkv, D) + k_elem(t, d)) =
+          *reinterpret_cast<const u32x4*>(krow + h * D + d);
+  }
   // V keeps four tokens of a dim together.  The row at the start of a quad whose other three
   // tokens are new as well writes the whole quad, 16 bytes (two dims) per lane, from the four
   // rows; the other three rows of such a quad skip V.  Quads that also hold older tokens, or
   // end past the stream's last token, are written one 2-byte element at a time, so bytes of
-  // tokens that are not being appended are never touched.
+  // tokens that are not being appended are never touched.  D/2 lanes per head either way.
   const int j = row - qo[s];             // index among the stream's new tokens
   const int q0 = j - (t & 3);            // index of the quad's first token (may be < 0)
   const bool full_quad = q0 >= 0 && q0 + 3 < n;
-  if (full_quad) {
-    if ((t & 3) == 0 && lane < D / 2) {
-      const size_t stride = (size_t)p.Hkv * D;  // next new row of the same kv head
+  if (full_quad && (t & 3) != 0) return;
+  constexpr int kLanesV = D / 2, kHeadsV = kWave / kLanesV;
+  const size_t stride = (size_t)p.Hkv * D;  // next new row of the same kv head
+  for (int h0 = 0; h0 < p.Hkv; h0 += kHeadsV) {
+    const int h = h0 + lane / kLanesV, d = (lane % kLanesV) * 2;
+    if (h >= p.Hkv) continue;
+    const uint16_t* src = vrow + h * D + d;
+    uint16_t* dst = v_pool + granule_offset(blk, h, p.Hkv, D);
+    if (full_quad) {
       uint32_t x[4];
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
-        x[k] = *reinterpret_cast<const uint32_t*>(vrow + k * stride + 2 * lane);
-      // dims 2*lane and 2*lane+1, tokens t..t+3 each: eight consecutive elements
+      for (int k = 0; k < 4; ++k) x[k] = *reinterpret_cast<const uint32_t*>(src + k * stride);
+      // dims d and d + 1, tokens t..t+3 each: eight consecutive elements
       const u32x4 out = {(x[0] & 0xFFFFu) | (x[1] << 16), (x[2] & 0xFFFFu) | (x[3] << 16),
                          (x[0] >> 16) | (x[1] & 0xFFFF0000u), (x[2] >> 16) | (x[3] & 0xFFFF0000u)};
-      *reinterpret_cast<u32x4*>(v_pool + g + v_elem(t, 2 * lane, D)) = out;
+      *reinterpret_cast<u32x4*>(dst + v_elem(t, d, D)) = out;
+    } else {
+      const uint32_t two = *reinterpret_cast<const uint32_t*>(src);
+      dst[v_elem(t, d, D)] = (uint16_t)(two & 0xFFFFu);
+      dst[v_elem(t, d + 1, D)] = (uint16_t)(two >> 16);
     }
-  } else if (lane < D / 2) {
-    const uint32_t two = *reinterpret_cast<const uint32_t*>(vrow + 2 * lane);
-    v_pool[g + v_elem(t, 2 * lane, D)] = (uint16_t)(two & 0xFFFFu);
-    v_pool[g + v_elem(t, 2 * lane + 1, D)] = (uint16_t)(two >> 16);
   }
 }
 
@@ -638,8 +694,7 @@ PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, 
   w.tile_first = take(((size_t)tiles + 1) * sizeof(int32_t));
   w.tile_steps = take((size_t)tiles * sizeof(int32_t));
   w.tile_info = take((size_t)tiles * sizeof(TileInfo));
-  w.seg_runs = take((size_t)tiles * p.Hkv * sizeof(int2));
-  w.row_tile = take((size_t)total_q * sizeof(int32_t));
+  w.split_list = take(((size_t)waves + kWavesPerGroup + 1) * sizeof(SplitSegment));
   w.partial_ml = take((size_t)slots * kCols * ncg * sizeof(float2));
   w.partial_acc = take((size_t)slots * kCols * ncg * p.D * sizeof(float));
   w.desc = take((size_t)desc_capacity * sizeof(MqDesc));
@@ -654,8 +709,7 @@ hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_ne
                                   const int32_t* bt, const int32_t* lens, const int32_t* qo,
                                   hipStream_t st) {
   if (total_q <= 0) return hipSuccess;
-  const unsigned grid =
-      (unsigned)(((int64_t)total_q * p.Hkv + kWavesPerGroup - 1) / kWavesPerGroup);
+  const unsigned grid = (unsigned)(((int64_t)total_q + kWavesPerGroup - 1) / kWavesPerGroup);
   if (p.D == 128)
     hipLaunchKernelGGL(kv_append_multi_kernel<128>, dim3(grid), dim3(256), 0, st, p, total_q,
                        (const uint16_t*)k_new, (const uint16_t*)v_new, (uint16_t*)k_pool,
@@ -707,11 +761,10 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
   int32_t* tile_first = (int32_t*)(ws + m.tile_first);
   int32_t* tile_steps = (int32_t*)(ws + m.tile_steps);
   TileInfo* tile_info = (TileInfo*)(ws + m.tile_info);
-  int32_t* row_tile = (int32_t*)(ws + m.row_tile);
+  SplitSegment* split = (SplitSegment*)(ws + m.split_list);
   float2* pml = (float2*)(ws + m.partial_ml);
   float* pacc = (float*)(ws + m.partial_acc);
   MqDesc* desc = (MqDesc*)(ws + m.desc);
-  int2* seg_runs = (int2*)(ws + m.seg_runs);
   int32_t* ranges = (int32_t*)(ws + m.ranges);
   // measured: a run boundary (query rows of the next run, record of the finished one) costs
   // about as much as four to six steps of a wave
@@ -721,17 +774,18 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
                      desc_capacity, header, pt, ps);
   if (tiles > 0) {
     hipLaunchKernelGGL(mq_tiles_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, st,
-                       p, tq, lens, qo, header, pt, ps, tile_first, tile_steps, tile_info,
-                       row_tile);
+                       p, tq, lens, qo, header, pt, ps, tile_first, tile_steps, tile_info);
     hipLaunchKernelGGL(mq_ranges_kernel, dim3((unsigned)((waves + kWavesPerGroup) / 256 + 1)), dim3(256), 0,
-                       st, p, waves, run_cost, header, pt, tile_first, tile_steps, ranges);
+                       st, p, waves, run_cost, header, pt, tile_first, tile_steps, ranges, split);
     hipLaunchKernelGGL(mq_expand_kernel, dim3((unsigned)((steps + 255) / 256)), dim3(256), 0, st,
                        p, bt, header, pt, tile_first, tile_steps, tile_info, ranges, waves, desc,
-                       seg_runs);
+                       split);
     const unsigned grid = (unsigned)((waves + kWavesPerGroup - 1) / kWavesPerGroup);
     Params pk = p;  // every wave reads its range from the table the plan wrote
     pk.n_steps = -1;
     pk.ranges_off = (int32_t)((m.ranges - m.header) / sizeof(int32_t));
+    pk.out = out;
+    pk.lse = lse;
     if (ev_before) (void)hipEventRecord(ev_before, st);
     if (p.D == 128) {
       if (ncg == 6)
@@ -759,14 +813,14 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
         launch_mq<64, 2, 1>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
     }
     if (ev_after) (void)hipEventRecord(ev_after, st);
-    const unsigned mg =
-        (unsigned)(((int64_t)total_q * p.Hq + kWavesPerGroup - 1) / kWavesPerGroup);
+    // every range start cuts at most one segment: `waves` bounds the list
+    const dim3 mg((unsigned)waves, (unsigned)(kCols * ncg / kWavesPerGroup));
     if (p.D == 128)
-      hipLaunchKernelGGL(mq_merge_kernel<128>, dim3(mg), dim3(256), 0, st, p, total_q, ncg,
-                         seg_runs, tile_info, row_tile, pml, pacc, out, lse);
+      hipLaunchKernelGGL(mq_merge_kernel<128>, mg, dim3(256), 0, st, p, ncg, split, pml, pacc, out,
+                         lse);
     else
-      hipLaunchKernelGGL(mq_merge_kernel<64>, dim3(mg), dim3(256), 0, st, p, total_q, ncg,
-                         seg_runs, tile_info, row_tile, pml, pacc, out, lse);
+      hipLaunchKernelGGL(mq_merge_kernel<64>, mg, dim3(256), 0, st, p, ncg, split, pml, pacc, out,
+                         lse);
   }
   return hipGetLastError();
 }
