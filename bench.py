@@ -33,8 +33,8 @@ METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 # in profiles/*_<workload>*.txt.  Workloads without a counter run report null.
 MEASURED_TRAFFIC = {
     "cfg3": 2356073726, "cfg4": 2730018149, "cfg5": 1103168749,
-    "chunk15": 2446218008, "chunk25": 2580836075, "chunk28": 2428704494, "admit": 3018084980,
-    "prefill": 475740393, "sample_small": 53909659, "sample_large": 330291029,
+    "chunk15": 2444113393, "chunk25": 2568395584, "chunk28": 2414441910, "admit": 2989020947,
+    "prefill": 468359012, "sample_small": 53909659, "sample_large": 330291029,
 }
 
 
