@@ -406,7 +406,7 @@ size_t vox_paged_prefill_workspace_bytes(const vox_shape_t* shape, int32_t total
     const int c = prefill_column_groups(p, rows);
     if (c > ncg) ncg = c;
   }
-  return map_prefill_workspace(p, ncg, tiles, total_q, slots, steps, split_waves(shape)).total;
+  return map_prefill_workspace(p, ncg, tiles, slots, steps, split_waves(shape)).total;
 }
 
 int vox_kv_append_multi(const vox_shape_t* shape, const void* k_new, const void* v_new,
@@ -475,13 +475,12 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
     tiles += nt;
   }
   steps *= p.Hkv;
-  const int64_t total_q = q_offsets_host[p.S];
   if (steps > INT32_MAX || tiles * p.Hkv > INT32_MAX / 2) return VOX_ERR_SHAPE;
   const int waves = split_waves(shape);
   const int64_t slots = waves + tiles * p.Hkv;
-  const PrefillWorkspace m = map_prefill_workspace(p, ncg, tiles, total_q, slots, steps, waves);
+  const PrefillWorkspace m = map_prefill_workspace(p, ncg, tiles, slots, steps, waves);
   if (m.total > workspace_bytes) return VOX_ERR_WORKSPACE;
-  return launch_prefill(p, m, (char*)workspace, ncg, tiles, steps, steps, waves, (int)total_q, q,
+  return launch_prefill(p, m, (char*)workspace, ncg, tiles, steps, steps, waves, q,
                         k_pool, v_pool, block_tables, context_lens, q_offsets, out, lse,
                         (hipStream_t)hip_stream, (hipEvent_t)event_before,
                         (hipEvent_t)event_after) == hipSuccess

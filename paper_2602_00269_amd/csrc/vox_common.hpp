@@ -200,8 +200,8 @@ hipError_t launch_kv_gather(const Params& p, const void* k_pool, const void* v_p
 hipError_t launch_plan(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
                        int64_t desc_capacity, int64_t max_steps, int32_t* header,
                        int32_t* step_prefix, int4* desc, hipStream_t st);
-PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, int64_t total_q,
-                                       int64_t slots, int64_t desc_capacity, int waves);
+PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, int64_t slots,
+                                       int64_t desc_capacity, int waves);
 int prefill_column_groups(const Params& p, int max_new_tokens);
 hipError_t launch_read_probe(const void* buf, size_t bytes, void* sink, hipStream_t st);
 size_t prefill_desc_bytes();
@@ -211,7 +211,7 @@ hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_ne
                                   hipStream_t st);
 hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, int ncg,
                           int64_t tiles, int64_t steps, int64_t desc_capacity, int waves,
-                          int total_q, const void* q, const void* k_pool, const void* v_pool,
+                          const void* q, const void* k_pool, const void* v_pool,
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
                           float* lse, hipStream_t st, hipEvent_t ev_before,
                           hipEvent_t ev_after);

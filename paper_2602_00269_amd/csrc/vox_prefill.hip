@@ -442,9 +442,9 @@ __global__ __launch_bounds__(kScanThreads) void mq_scan_kernel(
 
 __global__ __launch_bounds__(256) void mq_tiles_kernel(
     Params p, int tq, const int32_t* __restrict__ lens, const int32_t* __restrict__ qo,
-    const int32_t* __restrict__ header, const int32_t* __restrict__ pt,
-    const int32_t* __restrict__ ps, int32_t* __restrict__ tile_first,
-    int32_t* __restrict__ tile_steps, TileInfo* __restrict__ tile_info) {
+    const int32_t* __restrict__ pt, const int32_t* __restrict__ ps,
+    int32_t* __restrict__ tile_first, int32_t* __restrict__ tile_steps,
+    TileInfo* __restrict__ tile_info) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   const int total = pt[p.S];
   if (t >= total) return;
@@ -675,10 +675,10 @@ __global__ __launch_bounds__(256) void kv_append_multi_kernel(
 
 }  // namespace
 
-// Workspace map of the multi-token step (byte offsets), for `tiles` tiles at most, `total_q`
-// query rows, `slots` partial records and `desc_capacity` step descriptors.
-PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, int64_t total_q,
-                                       int64_t slots, int64_t desc_capacity, int waves) {
+// Workspace map of the multi-token step (byte offsets), for `tiles` tiles at most, `slots`
+// partial records, `desc_capacity` step descriptors and `waves` ranges.
+PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, int64_t slots,
+                                       int64_t desc_capacity, int waves) {
   PrefillWorkspace w;
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -749,7 +749,7 @@ static void launch_mq(const Params& pk, unsigned grid, const void* q, const void
 
 hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, int ncg,
                           int64_t tiles, int64_t steps, int64_t desc_capacity, int waves,
-                          int total_q, const void* q, const void* k_pool, const void* v_pool,
+                          const void* q, const void* k_pool, const void* v_pool,
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
                           float* lse, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
   const int tq = (kCols / p.G) * ncg;  // query tokens per tile
@@ -774,7 +774,7 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
                      desc_capacity, header, pt, ps);
   if (tiles > 0) {
     hipLaunchKernelGGL(mq_tiles_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, st,
-                       p, tq, lens, qo, header, pt, ps, tile_first, tile_steps, tile_info);
+                       p, tq, lens, qo, pt, ps, tile_first, tile_steps, tile_info);
     hipLaunchKernelGGL(mq_ranges_kernel, dim3((unsigned)((waves + kWavesPerGroup) / 256 + 1)), dim3(256), 0,
                        st, p, waves, run_cost, header, pt, tile_first, tile_steps, ranges, split);
     hipLaunchKernelGGL(mq_expand_kernel, dim3((unsigned)((steps + 255) / 256)), dim3(256), 0, st,
