@@ -533,6 +533,60 @@ def test_zero_negative_and_tiny_scales(dev, scale):
         _assert_close(out_d.cpu().numpy(), ref[qo[1:] - 1], f"decode scale {scale} D {d}")
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_decode_and_multi_token(dev, seed):
+    # seeded random shapes, length mixes, chunk mixes and range counts: the decode step and the
+    # multi-token step against the oracle
+    rng = np.random.default_rng(9000 + seed)
+    d = int(rng.choice([64, 128]))
+    hkv = int(rng.choice([1, 2, 4, 8]))
+    g = int(rng.integers(1, 9))
+    s = int(rng.integers(1, 40))
+    top = int(rng.choice([40, 300, 2500]))
+    lens = rng.integers(0, top, size=s)
+    lens[rng.integers(0, s)] = max(1, top - 1)
+    kind = int(rng.integers(0, 3))
+    if kind == 0:  # chunks of one size, where the stream is long enough
+        nq = np.minimum(lens, int(rng.integers(1, 40)))
+    elif kind == 1:  # anything from nothing to the whole context
+        nq = (lens * rng.random(s)).astype(np.int64)
+    else:  # mostly single tokens, a few whole prompts
+        nq = np.minimum(lens, 1)
+        pick = rng.random(s) < 0.2
+        nq[pick] = lens[pick]
+    w, qo, q, k_new, v_new = _prefill_case(dev, lens, nq, g * hkv, hkv, d, seed=9100 + seed)
+    sh = binding.shape_of(w)
+    sh.split_waves = int(rng.choice([0, 4, 64, 2000]))
+    bt, lens_d, qo_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev), _i32(qo, dev)
+    what = f"seed {seed}: D {d} Hkv {hkv} G {g} S {s} kind {kind} waves {sh.split_waves}"
+    kp_ref, vp_ref = _host_pools(w)
+    oracle.kv_append_multi(bits_of(k_new), bits_of(v_new), kp_ref, vp_ref, w.block_tables,
+                           w.context_lens, qo, head_dim=d)
+    binding.kv_append_multi(sh, k_new, v_new, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d)
+    torch.cuda.synchronize()
+    kp, vp = _host_pools(w)
+    assert np.array_equal(kp, kp_ref) and np.array_equal(vp, vp_ref), what
+    tq = int(qo[-1])
+    if tq > 0:
+        ref, ref_lse = oracle.paged_prefill(bits_of(q), kp_ref, vp_ref, w.block_tables,
+                                            w.context_lens, qo, w.scale, num_kv_heads=hkv)
+        out = torch.full((tq, g * hkv, d), float("nan"), device=dev)
+        lse = torch.full((tq, g * hkv), float("nan"), device=dev)
+        ws = torch.empty(binding.paged_prefill_workspace_bytes(sh, tq), dtype=torch.uint8,
+                         device=dev)
+        ws.fill_(0xA5)
+        binding.paged_prefill(sh, q, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d, w.context_lens,
+                              qo, out, ws, lse=lse)
+        torch.cuda.synchronize()
+        _assert_close(out.cpu().numpy(), ref, what)
+        _assert_lse(lse.cpu().numpy(), ref_lse, what)
+    # the decode step over the same caches (w.q holds one query row per stream)
+    out_d, lse_d = _decode(w, dev)
+    ref_d, ref_lse_d = _oracle_decode(w)
+    _assert_close(out_d, ref_d, what + " decode")
+    _assert_lse(lse_d, ref_lse_d, what + " decode")
+
+
 def test_multi_token_step_with_no_rows_is_a_no_op(dev):
     w = synth.make_custom([40, 7], 8, 2, 64, seed=95, device=dev)
     sh = binding.shape_of(w)
