@@ -36,6 +36,7 @@ constexpr int kKeyBits = 31 + kIdBits;
 constexpr int kLevels = 5;
 constexpr int kBins = 2048;
 constexpr int kCandidates = 4096;
+constexpr int kQuadMinVocab = 16384;  // below this a thread has too few tokens for quads to pay
 
 __device__ constexpr int kWidth[kLevels] = {11, 10, 10, 9, 9};
 __device__ constexpr int kShift[kLevels] = {38, 28, 18, 9, 0};
@@ -69,39 +70,75 @@ struct StreamCtx {
   int V;
   float r, invT, m;
 };
+// QUAD: the row is read four consecutive tokens per lane and load (its length is a multiple of
+// four and its start 16-byte aligned: the host decides, one kernel per way of reading)
+template <bool QUAD>
+struct StreamCtxT : StreamCtx {
+  static constexpr bool kQuad = QUAD;
+};
 
-// penalised, tempered logit of token v whose raw logit is z
-__device__ inline float tempered(const StreamCtx& c, int v, float z) {
+// penalised, tempered logit of token v whose raw logit is z; `word` is word v / 32 of the
+// window bitmap (zero when there is no window)
+__device__ inline float tempered(const StreamCtx& c, int v, float z, uint32_t word) {
 #pragma clang fp contract(off)
   float zp = z;
-  if (c.seen && ((c.seen[v >> 5] >> (v & 31)) & 1u)) zp = zp > 0.0f ? zp / c.r : zp * c.r;
+  if ((word >> (v & 31)) & 1u) zp = zp > 0.0f ? zp / c.r : zp * c.r;
   return zp * c.invT;
 }
 
-__device__ inline uint64_t key_of(const StreamCtx& c, int v, float z, float* d_out) {
+__device__ inline uint64_t key_of(const StreamCtx& c, int v, float z, uint32_t word,
+                                  float* d_out) {
 #pragma clang fp contract(off)
-  const float d = c.m - tempered(c, v, z);
+  const float d = c.m - tempered(c, v, z, word);
   *d_out = d;
   const uint64_t dkey = __builtin_bit_cast(uint32_t, d) & 0x7FFFFFFFu;
   return (dkey << kIdBits) | (uint32_t)v;
 }
 
-// Calls f(v, z[v]) for every token of the stream, this thread's share; the logits of kAhead
+// Calls f(v, z[v], bitmap word of v) for every token of the stream, this thread's share, in
+// no particular order (nothing the callers compute depends on it); the logits of several
 // tokens are loaded before any of them is used, so the loads overlap (more of them for light
-// bodies, fewer where the body needs the registers).
-template <int kAhead = 4, class F>
-__device__ inline void for_each_token(const StreamCtx& c, F f) {
-  for (int v0 = threadIdx.x; v0 < c.V; v0 += kThreads * kAhead) {
-    float z[kAhead];
+// bodies, fewer where the body needs the registers).  Rows read in quads: twice the tokens in
+// flight with half the loads, and the four tokens share one look-up of the bitmap.
+template <int kAhead = 4, class Ctx, class F>
+__device__ inline void for_each_token(const Ctx& c, F f) {
+  if constexpr (Ctx::kQuad) {
+    const float4* z4 = reinterpret_cast<const float4*>(c.z);
+    const int quads = c.V >> 2;
+    constexpr int kQuadsAhead = kAhead >= 2 ? kAhead / 2 : 1;
+    for (int q0 = threadIdx.x; q0 < quads; q0 += kThreads * kQuadsAhead) {
+      float4 z[kQuadsAhead];
 #pragma unroll
-    for (int e = 0; e < kAhead; ++e) {
-      const int v = v0 + e * kThreads;
-      z[e] = v < c.V ? c.z[v] : 0.0f;
+      for (int e = 0; e < kQuadsAhead; ++e) {
+        const int q = q0 + e * kThreads;
+        z[e] = q < quads ? z4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int e = 0; e < kQuadsAhead; ++e) {
+        const int q = q0 + e * kThreads;
+        if (q < quads) {
+          const int v = 4 * q;
+          const uint32_t word = c.seen ? c.seen[v >> 5] : 0u;
+          f(v, z[e].x, word);
+          f(v + 1, z[e].y, word);
+          f(v + 2, z[e].z, word);
+          f(v + 3, z[e].w, word);
+        }
+      }
     }
+  } else {
+    for (int v0 = threadIdx.x; v0 < c.V; v0 += kThreads * kAhead) {
+      float z[kAhead];
 #pragma unroll
-    for (int e = 0; e < kAhead; ++e) {
-      const int v = v0 + e * kThreads;
-      if (v < c.V) f(v, z[e]);
+      for (int e = 0; e < kAhead; ++e) {
+        const int v = v0 + e * kThreads;
+        z[e] = v < c.V ? c.z[v] : 0.0f;
+      }
+#pragma unroll
+      for (int e = 0; e < kAhead; ++e) {
+        const int v = v0 + e * kThreads;
+        if (v < c.V) f(v, z[e], c.seen ? c.seen[v >> 5] : 0u);
+      }
     }
   }
 }
@@ -185,7 +222,8 @@ __device__ inline void clear_hist(Lds& s) {
 }
 
 // Position where the running count / weight first reaches thr (1 <= thr <= total).
-__device__ Located locate(Lds& s, const StreamCtx& c, bool by_mass, unsigned long long thr) {
+template <class Ctx>
+__device__ Located locate(Lds& s, const Ctx& c, bool by_mass, unsigned long long thr) {
   uint64_t prefix = 0;  // the digits chosen so far, right-aligned
   int prefix_bits = 0;
   unsigned long long before_cnt = 0, before_mass = 0, bucket_mass = 0;
@@ -210,9 +248,9 @@ __device__ Located locate(Lds& s, const StreamCtx& c, bool by_mass, unsigned lon
           atomicAdd(&s.mass[b], (unsigned long long)weight_of(d_of_key(comp)));
         }
       } else {
-        for_each_token(c, [&](int v, float z) {
+        for_each_token(c, [&](int v, float z, uint32_t word) {
           float d;
-          const uint64_t comp = key_of(c, v, z, &d);
+          const uint64_t comp = key_of(c, v, z, word, &d);
           if ((comp >> (kKeyBits - prefix_bits)) != prefix) return;
           const uint32_t b = (uint32_t)(comp >> shift) & digit_mask;
           atomicAdd(&s.cnt[b], 1u);
@@ -234,9 +272,9 @@ __device__ Located locate(Lds& s, const StreamCtx& c, bool by_mass, unsigned lon
       // copy the bucket's keys to LDS; later digits are read from there
       if (threadIdx.x == 0) s.n_cand = 0;
       __syncthreads();
-      for_each_token(c, [&](int v, float z) {
+      for_each_token(c, [&](int v, float z, uint32_t word) {
         float d;
-        const uint64_t comp = key_of(c, v, z, &d);
+        const uint64_t comp = key_of(c, v, z, word, &d);
         if ((comp >> (kKeyBits - prefix_bits)) == prefix) s.cand[atomicAdd(&s.n_cand, 1u)] = comp;
       });
       __syncthreads();
@@ -253,11 +291,12 @@ __device__ Located locate(Lds& s, const StreamCtx& c, bool by_mass, unsigned lon
 }
 
 // Per-stream set-up: the window's tokens as an LDS bitmap, 1/T, the maximum tempered logit.
-__device__ StreamCtx open_stream(Lds& s, int V, const float* __restrict__ logits,
+template <class Ctx>
+__device__ Ctx open_stream(Lds& s, int V, const float* __restrict__ logits,
                                  const vox_sampling_t& prm, const int32_t* __restrict__ history,
                                  int window, int stream) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  StreamCtx c;
+  Ctx c;
   c.z = logits + (size_t)stream * V;
   c.V = V;
   c.r = prm.repetition_penalty;
@@ -275,7 +314,8 @@ __device__ StreamCtx open_stream(Lds& s, int V, const float* __restrict__ logits
   }
   c.m = 0.0f;
   float mx = -INFINITY;
-  for_each_token<16>(c, [&](int v, float z) { mx = fmaxf(mx, tempered(c, v, z)); });
+  for_each_token<Ctx::kQuad ? 8 : 16>(
+      c, [&](int v, float z, uint32_t word) { mx = fmaxf(mx, tempered(c, v, z, word)); });
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
   if (lane == 0) s.wave_max[wv] = mx;
@@ -293,25 +333,27 @@ __global__ __launch_bounds__(kThreads) void sample_weights_kernel(
     unsigned long long* __restrict__ w_out) {
   __shared__ Lds s;
   const int stream = blockIdx.x;
-  const StreamCtx c = open_stream(s, V, logits, params[stream], history, window, stream);
-  for_each_token(c, [&](int v, float z) {
+  const auto c =
+      open_stream<StreamCtxT<false>>(s, V, logits, params[stream], history, window, stream);
+  for_each_token(c, [&](int v, float z, uint32_t word) {
     float d;
-    (void)key_of(c, v, z, &d);
+    (void)key_of(c, v, z, word, &d);
     d_out[(size_t)stream * V + v] = d;
     w_out[(size_t)stream * V + v] = weight_of(d);
   });
 }
 
 // Level-0 histogram of the radix descent (digits of the key), for the general path.
-__device__ void build_key_histogram(Lds& s, const StreamCtx& c) {
+template <class Ctx>
+__device__ void build_key_histogram(Lds& s, const Ctx& c) {
   for (int b = threadIdx.x; b < kBins; b += kThreads) {
     s.cnt0[b] = 0;
     s.mass[kBins + b] = 0;
   }
   __syncthreads();
-  for_each_token(c, [&](int v, float z) {
+  for_each_token(c, [&](int v, float z, uint32_t word) {
     float d;
-    const uint64_t comp = key_of(c, v, z, &d);
+    const uint64_t comp = key_of(c, v, z, word, &d);
     const uint32_t b = (uint32_t)(comp >> kShift[0]);
     atomicAdd(&s.cnt0[b], 1u);
     const unsigned long long w = weight_of(d);
@@ -321,7 +363,8 @@ __device__ void build_key_histogram(Lds& s, const StreamCtx& c) {
 }
 
 // General path: every cut by radix descent over the whole vocabulary.
-__device__ void sample_general(Lds& s, const StreamCtx& c, const vox_sampling_t& prm, bool greedy,
+template <class Ctx>
+__device__ void sample_general(Lds& s, const Ctx& c, const vox_sampling_t& prm, bool greedy,
                                float u, int* token, int* n_kept) {
   build_key_histogram(s, c);
   if (greedy) {
@@ -381,6 +424,7 @@ __device__ inline int first_reaching(const unsigned long long* cum, int n,
   return lo;
 }
 
+template <bool QUAD>
 __global__ __launch_bounds__(kThreads) void sample_kernel(
     int V, const float* __restrict__ logits, const vox_sampling_t* __restrict__ params,
     const int32_t* __restrict__ history, int window, const float* __restrict__ uniforms,
@@ -391,7 +435,7 @@ __global__ __launch_bounds__(kThreads) void sample_kernel(
   const vox_sampling_t prm = params[stream];
   const bool greedy = !(prm.temperature > 0.0f);
   const float u = uniforms[stream];
-  const StreamCtx c = open_stream(s, V, logits, prm, history, window, stream);
+  const auto c = open_stream<StreamCtxT<QUAD>>(s, V, logits, prm, history, window, stream);
   // One pass over the logits: tokens within kNearRange of the maximum go into the bucket
   // histogram and into the candidate list, all others only add to the thread's weight total
   // (and, when a top-k cut is wanted, to the bucket counts out to kCountRange, since the k-th
@@ -406,9 +450,9 @@ __global__ __launch_bounds__(kThreads) void sample_kernel(
   if (tid == 0) s.n_cand = 0;
   __syncthreads();
   unsigned long long far_mass = 0;
-  for_each_token(c, [&](int v, float z) {
+  for_each_token(c, [&](int v, float z, uint32_t word) {
     float d;
-    const uint64_t comp = key_of(c, v, z, &d);
+    const uint64_t comp = key_of(c, v, z, word, &d);
     const unsigned long long w = weight_of(d);
     if (d < kNearRange) {
       const int b = bucket_of(d);
@@ -454,9 +498,9 @@ __global__ __launch_bounds__(kThreads) void sample_kernel(
   if (fast && last_bucket >= kNearBuckets) {
     // the k-th token lies beyond the near range: one more pass adds the tokens between the
     // near range and its bucket to the candidates
-    for_each_token(c, [&](int v, float z) {
+    for_each_token(c, [&](int v, float z, uint32_t word) {
       float d;
-      const uint64_t comp = key_of(c, v, z, &d);
+      const uint64_t comp = key_of(c, v, z, word, &d);
       if (d >= kNearRange && d < kCountRange && bucket_of(d) <= last_bucket)
         s.cand[atomicAdd(&s.n_cand, 1u)] = comp;
     });
@@ -566,9 +610,16 @@ extern "C" int vox_sample(int32_t num_streams, int32_t vocab, const float* logit
   if (num_streams <= 0 || vocab <= 0 || vocab > vox::kMaxVocab || window < 0)
     return VOX_ERR_SHAPE;
   if (!logits || !params || !uniforms || !tokens || (window > 0 && !history)) return VOX_ERR_NULL;
-  hipLaunchKernelGGL(vox::sample_kernel, dim3((unsigned)num_streams), dim3(vox::kThreads), 0,
-                     (hipStream_t)hip_stream, vocab, logits, params, history, window, uniforms,
-                     tokens, kept);
+  // large vocabularies whose rows start 16-byte aligned are read four tokens per lane and load
+  const bool quad = vocab >= vox::kQuadMinVocab && vocab % 4 == 0 && ((uintptr_t)logits & 15) == 0;
+  if (quad)
+    hipLaunchKernelGGL(vox::sample_kernel<true>, dim3((unsigned)num_streams),
+                       dim3(vox::kThreads), 0, (hipStream_t)hip_stream, vocab, logits, params,
+                       history, window, uniforms, tokens, kept);
+  else
+    hipLaunchKernelGGL(vox::sample_kernel<false>, dim3((unsigned)num_streams),
+                       dim3(vox::kThreads), 0, (hipStream_t)hip_stream, vocab, logits, params,
+                       history, window, uniforms, tokens, kept);
   return hipGetLastError() == hipSuccess ? VOX_OK : VOX_ERR_HIP;
 }
 

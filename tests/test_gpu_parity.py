@@ -767,6 +767,24 @@ def test_sampled_tokens_are_bit_exact(dev, case):
             assert np.array_equal(tok, ref_tok), what
 
 
+def test_sampling_reads_rows_whatever_their_alignment(dev):
+    # large vocabularies are read 16 bytes per lane when the rows allow it: the same logits at a
+    # 16-byte aligned address and 4 bytes further on must give the same tokens as the oracle
+    s, v = 6, 40000
+    base = synth.make_logits(s, v, seed=250, device=dev)
+    hist = synth.make_history(s, v, 64, seed=251)
+    u = synth.make_uniforms(s, seed=252)
+    store = torch.empty(s * v + 1, dtype=torch.float32, device=dev)
+    for off in (0, 1):
+        logits = store[off:off + s * v].view(s, v)
+        logits.copy_(base)
+        assert logits.data_ptr() % 16 == 4 * off
+        for temperature, top_p, top_k, penalty in synth.SAMPLING_PRESETS.values():
+            tok, kept, ref_tok, ref_kept = _sample_both(dev, logits, temperature, top_p, penalty,
+                                                        top_k, u, hist)
+            assert np.array_equal(kept, ref_kept) and np.array_equal(tok, ref_tok), off
+
+
 def test_sampling_weights_are_bit_exact(dev):
     s, v = 6, 50021
     logits = synth.make_logits(s, v, seed=230, device=dev, spread=3.0)
