@@ -767,6 +767,30 @@ def test_sampled_tokens_are_bit_exact(dev, case):
             assert np.array_equal(tok, ref_tok), what
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_sampling_shapes_and_settings(dev, seed):
+    # seeded random vocabularies (tiny to 2^18, multiples of four and not), spreads, windows and
+    # per-stream settings: tokens and kept counts bit for bit
+    rng = np.random.default_rng(7000 + seed)
+    s = int(rng.integers(1, 9))
+    v = int(rng.choice([rng.integers(1, 300), rng.integers(300, 20000),
+                        4 * rng.integers(4096, 65536), rng.integers(16384, 262145)]))
+    logits = synth.make_logits(s, v, seed=seed, device=dev,
+                               spread=float(rng.choice([0.0, 0.5, 2.0, 6.0])))
+    window = int(rng.choice([0, 7, 64, 500]))
+    hist = synth.make_history(s, v, window, seed=seed + 1) if window else None
+    u = synth.make_uniforms(s, seed=seed + 2)
+    temperature = rng.choice([0.0, 0.3, 0.8, 1.0, 5.0], size=s).astype(np.float32)
+    top_p = rng.choice([1.0, 0.95, 0.5, 1e-4], size=s).astype(np.float32)
+    top_k = rng.choice([0, 1, 50, 1000, v + 5], size=s).astype(np.int32)
+    penalty = np.float32(rng.choice([1.0, 1.1, 2.0]))
+    tok, kept, ref_tok, ref_kept = _sample_both(dev, logits, temperature, top_p, penalty, top_k,
+                                                u, hist)
+    what = f"seed {seed}: S {s} V {v} window {window}"
+    assert np.array_equal(kept, ref_kept), what
+    assert np.array_equal(tok, ref_tok), what
+
+
 def test_sampling_reads_rows_whatever_their_alignment(dev):
     # large vocabularies are read 16 bytes per lane when the rows allow it: the same logits at a
     # 16-byte aligned address and 4 bytes further on must give the same tokens as the oracle
