@@ -312,6 +312,42 @@ def test_multi_layer_step_matches_oracle_on_sampled_streams(dev):
             _assert_close(got[s:s + 1], ref, f"cfg5 layer{l} stream{s}")
 
 
+def test_full_28_layer_step_at_bench_size(dev):
+    # the 1024-stream, 28-layer step exactly as bench.py times it: every layer's output finite,
+    # and the first, a middle and the last layer checked against the oracle (whole pools bit for
+    # bit after the append, attention on a seeded sample of streams)
+    w = synth.make_workload(5, device=dev)
+    assert w.layers == 28
+    sh = binding.shape_of(w)
+    bt, lens = _i32(w.block_tables, dev), _i32(w.context_lens, dev)
+    outs = [torch.full((w.num_streams, w.num_q_heads, w.head_dim), float("nan"), device=dev)
+            for _ in range(w.layers)]
+    checked = (0, 13, 27)
+    before = {l: _host_pools(w, l) for l in checked}
+    args = binding.StepArgs(w.q, w.k_new, w.v_new, w.k_pool, w.v_pool, outs)
+    ws = binding.alloc_workspace(sh, dev)
+    binding.decode_step(sh, args, bt, lens, ws, context_lens_host=w.context_lens)
+    torch.cuda.synchronize()
+    for l in range(w.layers):
+        assert bool(torch.isfinite(outs[l]).all()), f"layer {l}"
+    rng = np.random.default_rng(78)
+    sample = sorted({int(np.argmax(w.context_lens)), int(np.argmin(w.context_lens)),
+                     *rng.choice(w.num_streams, size=10, replace=False).tolist()})
+    for l in checked:
+        kp_ref, vp_ref = before[l]
+        oracle.kv_append(bits_of(w.k_new[l]), bits_of(w.v_new[l]), kp_ref, vp_ref, w.block_tables,
+                         w.context_lens, head_dim=w.head_dim)
+        kp, vp = _host_pools(w, l)
+        assert np.array_equal(kp, kp_ref) and np.array_equal(vp, vp_ref), f"layer {l}"
+        del kp, vp
+        got = outs[l].cpu().numpy()
+        for s in sample:
+            ref, _ = oracle.paged_decode(bits_of(w.q[l]), kp_ref, vp_ref, w.block_tables,
+                                         w.context_lens, w.scale, num_kv_heads=w.num_kv_heads,
+                                         streams=(s, s + 1))
+            _assert_close(got[s:s + 1], ref, f"cfg5 layer{l} stream{s}")
+
+
 def test_decode_step_replays_from_a_hip_graph(dev):
     # The step only enqueues kernels with length-independent attention grids, so it can be
     # captured once and replayed with new queries / new tokens in the same buffers.  Each replay
