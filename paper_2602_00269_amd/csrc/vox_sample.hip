@@ -1,5 +1,6 @@
 // Sampling step: logits -> next token per stream (repetition penalty, temperature, top-k, top-p,
-// draw), one workgroup of 1024 threads per stream, everything besides the logits in LDS.
+// draw), one workgroup per stream (1024 threads, or 512 for vocabularies up to 32768 so that two
+// streams share a CU), everything besides the logits in LDS.
 //
 // The token is decided by exact arithmetic: every float step is a single IEEE fp32 operation
 // in a fixed order (contraction is off in this file's arithmetic helpers), softmax weights are
@@ -28,15 +29,26 @@
 namespace vox {
 namespace {
 
-constexpr int kThreads = 1024;
-constexpr int kWaves = kThreads / 64;
 constexpr int kIdBits = 18;  // vocabulary of at most 2^18 tokens
 constexpr int kMaxVocab = 1 << kIdBits;
 constexpr int kKeyBits = 31 + kIdBits;
 constexpr int kLevels = 5;
 constexpr int kBins = 2048;
-constexpr int kCandidates = 4096;
 constexpr int kQuadMinVocab = 16384;  // below this a thread has too few tokens for quads to pay
+
+// Workgroup shapes.  Results do not depend on them (the candidate limits only decide which of
+// two equivalent paths runs); what differs is how much of a CU a stream takes.
+struct AnyVocab {  // one workgroup per CU
+  static constexpr int kThreads = 1024;
+  static constexpr int kVocab = kMaxVocab;  // largest vocabulary: sizes the window bitmap
+  static constexpr int kCandidates = 4096;  // tokens of a bucket / of the near range kept in LDS
+};
+struct SmallVocab {  // 68 KB of LDS and half the threads: two workgroups per CU, whose short
+                     // dependent phases then overlap
+  static constexpr int kThreads = 512;
+  static constexpr int kVocab = 32768;
+  static constexpr int kCandidates = 2048;
+};
 
 __device__ constexpr int kWidth[kLevels] = {11, 10, 10, 9, 9};
 __device__ constexpr int kShift[kLevels] = {38, 28, 18, 9, 0};
@@ -95,13 +107,51 @@ __device__ inline uint64_t key_of(const StreamCtx& c, int v, float z, uint32_t w
   return (dkey << kIdBits) | (uint32_t)v;
 }
 
+__device__ inline float d_of_key(uint64_t comp) {
+  return __builtin_bit_cast(float, (uint32_t)(comp >> kIdBits));
+}
+
+struct Located {
+  uint64_t comp;                   // key of the token at the crossing
+  uint64_t through_cnt, through_mass;  // tokens / weight up to and including it
+};
+
+constexpr float kBucketsPerUnit = 64.0f;
+constexpr float kNearRange = 8.0f;
+constexpr int kNearBuckets = 512;  // kNearRange * kBucketsPerUnit
+constexpr float kCountRange = 32.0f;  // kBins / kBucketsPerUnit: counts are kept out to here
+
+
+__device__ inline int bucket_of(float d) { return (int)(d * kBucketsPerUnit); }  // d in [0, 32)
+
+// First index i in [0, n) with cum[i] >= thr (n if none).
+__device__ inline int first_reaching(const unsigned long long* cum, int n,
+                                     unsigned long long thr) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (cum[mid] >= thr)
+      hi = mid;
+    else
+      lo = mid + 1;
+  }
+  return lo;
+}
+
+template <class Cfg>
+struct Sampler {
+static constexpr int kThreads = Cfg::kThreads;
+static constexpr int kWaves = kThreads / 64;
+static constexpr int kCandidates = Cfg::kCandidates;
+static constexpr int kSuperset = Cfg::kCandidates;
+
 // Calls f(v, z[v], bitmap word of v) for every token of the stream, this thread's share, in
 // no particular order (nothing the callers compute depends on it); the logits of several
 // tokens are loaded before any of them is used, so the loads overlap (more of them for light
 // bodies, fewer where the body needs the registers).  Rows read in quads: twice the tokens in
 // flight with half the loads, and the four tokens share one look-up of the bitmap.
 template <int kAhead = 4, class Ctx, class F>
-__device__ inline void for_each_token(const Ctx& c, F f) {
+static __device__ inline void for_each_token(const Ctx& c, F f) {
   if constexpr (Ctx::kQuad) {
     const float4* z4 = reinterpret_cast<const float4*>(c.z);
     const int quads = c.V >> 2;
@@ -143,12 +193,8 @@ __device__ inline void for_each_token(const Ctx& c, F f) {
   }
 }
 
-__device__ inline float d_of_key(uint64_t comp) {
-  return __builtin_bit_cast(float, (uint32_t)(comp >> kIdBits));
-}
-
 struct Lds {
-  uint32_t seen[kMaxVocab / 32];
+  uint32_t seen[Cfg::kVocab / 32];
   uint32_t cnt[kBins], cnt0[kBins];
   unsigned long long mass[2 * kBins];  // [0, kBins): histogram in use; [kBins, 2 kBins): level 0
   unsigned long long cand[kCandidates];
@@ -160,20 +206,22 @@ struct Lds {
   uint32_t n_cand;
 };
 
-struct Located {
-  uint64_t comp;                   // key of the token at the crossing
-  uint64_t through_cnt, through_mass;  // tokens / weight up to and including it
-};
-
 // Finds, over bins [0, nbins), the first bin where the running count (by_mass = false) or
 // running weight reaches thr; leaves the bin and the sums before it in LDS.  All threads call.
-__device__ inline void scan_bins(Lds& s, const uint32_t* cnt, const unsigned long long* mass,
+static __device__ inline void scan_bins(Lds& s, const uint32_t* cnt, const unsigned long long* mass,
                                  int nbins, bool by_mass, unsigned long long thr) {
+  constexpr int kPerThread = kBins / kThreads;  // consecutive bins per thread
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int b0 = 2 * tid, b1 = 2 * tid + 1;
-  const unsigned long long c0 = b0 < nbins ? cnt[b0] : 0, c1 = b1 < nbins ? cnt[b1] : 0;
-  const unsigned long long m0 = b0 < nbins ? mass[b0] : 0, m1 = b1 < nbins ? mass[b1] : 0;
-  unsigned long long ic = c0 + c1, im = m0 + m1;
+  const int b0 = kPerThread * tid;
+  unsigned long long c[kPerThread], m[kPerThread], tc = 0, tm = 0;
+#pragma unroll
+  for (int e = 0; e < kPerThread; ++e) {
+    c[e] = b0 + e < nbins ? cnt[b0 + e] : 0;
+    m[e] = b0 + e < nbins ? mass[b0 + e] : 0;
+    tc += c[e];
+    tm += m[e];
+  }
+  unsigned long long ic = tc, im = tm;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
     const unsigned long long ac = __shfl_up(ic, o), am = __shfl_up(im, o);
@@ -188,32 +236,31 @@ __device__ inline void scan_bins(Lds& s, const uint32_t* cnt, const unsigned lon
   }
   if (tid == 0) s.bin = -1;
   __syncthreads();
-  unsigned long long ec = ic - (c0 + c1), em = im - (m0 + m1);  // exclusive, inside the wave
+  unsigned long long ec = ic - tc, em = im - tm;  // exclusive, inside the wave
   for (int k = 0; k < wv; ++k) {
     ec += s.wave_cnt[k];
     em += s.wave_mass[k];
   }
-  // running value before bin b0, after b0, after b1
-  const unsigned long long v0 = by_mass ? em : ec;
-  const unsigned long long v1 = v0 + (by_mass ? m0 : c0);
-  const unsigned long long v2 = v1 + (by_mass ? m1 : c1);
-  if (v0 < thr && thr <= v1) {
-    s.bin = b0;
-    s.before_cnt = ec;
-    s.before_mass = em;
-  } else if (v1 < thr && thr <= v2) {
-    s.bin = b1;
-    s.before_cnt = ec + c0;
-    s.before_mass = em + m0;
+#pragma unroll
+  for (int e = 0; e < kPerThread; ++e) {  // running value before and after bin b0 + e
+    const unsigned long long before = by_mass ? em : ec;
+    const unsigned long long after = before + (by_mass ? m[e] : c[e]);
+    if (before < thr && thr <= after) {
+      s.bin = b0 + e;
+      s.before_cnt = ec;
+      s.before_mass = em;
+    }
+    ec += c[e];
+    em += m[e];
   }
   if (tid == kThreads - 1) {
-    s.total_cnt = ec + c0 + c1;
-    s.total_mass = em + m0 + m1;
+    s.total_cnt = ec;
+    s.total_mass = em;
   }
   __syncthreads();
 }
 
-__device__ inline void clear_hist(Lds& s) {
+static __device__ inline void clear_hist(Lds& s) {
   for (int b = threadIdx.x; b < kBins; b += kThreads) {
     s.cnt[b] = 0;
     s.mass[b] = 0;
@@ -223,7 +270,7 @@ __device__ inline void clear_hist(Lds& s) {
 
 // Position where the running count / weight first reaches thr (1 <= thr <= total).
 template <class Ctx>
-__device__ Located locate(Lds& s, const Ctx& c, bool by_mass, unsigned long long thr) {
+static __device__ Located locate(Lds& s, const Ctx& c, bool by_mass, unsigned long long thr) {
   uint64_t prefix = 0;  // the digits chosen so far, right-aligned
   int prefix_bits = 0;
   unsigned long long before_cnt = 0, before_mass = 0, bucket_mass = 0;
@@ -292,7 +339,7 @@ __device__ Located locate(Lds& s, const Ctx& c, bool by_mass, unsigned long long
 
 // Per-stream set-up: the window's tokens as an LDS bitmap, 1/T, the maximum tempered logit.
 template <class Ctx>
-__device__ Ctx open_stream(Lds& s, int V, const float* __restrict__ logits,
+static __device__ Ctx open_stream(Lds& s, int V, const float* __restrict__ logits,
                                  const vox_sampling_t& prm, const int32_t* __restrict__ history,
                                  int window, int stream) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -327,10 +374,11 @@ __device__ Ctx open_stream(Lds& s, int V, const float* __restrict__ logits,
 }
 
 // Verification aid: the distance d = max - y and the integer weight of every token.
-__global__ __launch_bounds__(kThreads) void sample_weights_kernel(
-    int V, const float* __restrict__ logits, const vox_sampling_t* __restrict__ params,
-    const int32_t* __restrict__ history, int window, float* __restrict__ d_out,
-    unsigned long long* __restrict__ w_out) {
+static __device__ void weights_body(int V, const float* __restrict__ logits,
+                                    const vox_sampling_t* __restrict__ params,
+                                    const int32_t* __restrict__ history, int window,
+                                    float* __restrict__ d_out,
+                                    unsigned long long* __restrict__ w_out) {
   __shared__ Lds s;
   const int stream = blockIdx.x;
   const auto c =
@@ -345,7 +393,7 @@ __global__ __launch_bounds__(kThreads) void sample_weights_kernel(
 
 // Level-0 histogram of the radix descent (digits of the key), for the general path.
 template <class Ctx>
-__device__ void build_key_histogram(Lds& s, const Ctx& c) {
+static __device__ void build_key_histogram(Lds& s, const Ctx& c) {
   for (int b = threadIdx.x; b < kBins; b += kThreads) {
     s.cnt0[b] = 0;
     s.mass[kBins + b] = 0;
@@ -364,7 +412,7 @@ __device__ void build_key_histogram(Lds& s, const Ctx& c) {
 
 // General path: every cut by radix descent over the whole vocabulary.
 template <class Ctx>
-__device__ void sample_general(Lds& s, const Ctx& c, const vox_sampling_t& prm, bool greedy,
+static __device__ void sample_general(Lds& s, const Ctx& c, const vox_sampling_t& prm, bool greedy,
                                float u, int* token, int* n_kept) {
   build_key_histogram(s, c);
   if (greedy) {
@@ -402,30 +450,8 @@ __device__ void sample_general(Lds& s, const Ctx& c, const vox_sampling_t& prm, 
 // weight) falls inside their buckets, every later cut does too (each lies at or before the
 // previous one): the copies are sorted by key and the cuts are searches in the running sums of
 // their weights.  Otherwise the general path starts over.
-constexpr float kBucketsPerUnit = 64.0f;
-constexpr float kNearRange = 8.0f;
-constexpr int kNearBuckets = 512;  // kNearRange * kBucketsPerUnit
-constexpr float kCountRange = 32.0f;  // kBins / kBucketsPerUnit: counts are kept out to here
-constexpr int kSuperset = 4096;
-
-__device__ inline int bucket_of(float d) { return (int)(d * kBucketsPerUnit); }  // d in [0, 32)
-
-// First index i in [0, n) with cum[i] >= thr (n if none).
-__device__ inline int first_reaching(const unsigned long long* cum, int n,
-                                     unsigned long long thr) {
-  int lo = 0, hi = n;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (cum[mid] >= thr)
-      hi = mid;
-    else
-      lo = mid + 1;
-  }
-  return lo;
-}
-
 template <bool QUAD>
-__global__ __launch_bounds__(kThreads) void sample_kernel(
+static __device__ void sample_body(
     int V, const float* __restrict__ logits, const vox_sampling_t* __restrict__ params,
     const int32_t* __restrict__ history, int window, const float* __restrict__ uniforms,
     int32_t* __restrict__ tokens, int32_t* __restrict__ kept) {
@@ -600,6 +626,26 @@ __global__ __launch_bounds__(kThreads) void sample_kernel(
   }
 }
 
+};  // Sampler
+
+
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::kThreads) void sample_weights_kernel(
+    int V, const float* __restrict__ logits, const vox_sampling_t* __restrict__ params,
+    const int32_t* __restrict__ history, int window, float* __restrict__ d_out,
+    unsigned long long* __restrict__ w_out) {
+  Sampler<Cfg>::weights_body(V, logits, params, history, window, d_out, w_out);
+}
+
+template <class Cfg, bool QUAD>
+__global__ __launch_bounds__(Cfg::kThreads, 4) void sample_kernel(
+    int V, const float* __restrict__ logits, const vox_sampling_t* __restrict__ params,
+    const int32_t* __restrict__ history, int window, const float* __restrict__ uniforms,
+    int32_t* __restrict__ tokens, int32_t* __restrict__ kept) {
+  Sampler<Cfg>::template sample_body<QUAD>(V, logits, params, history, window, uniforms, tokens,
+                                           kept);
+}
+
 }  // namespace
 }  // namespace vox
 
@@ -610,16 +656,20 @@ extern "C" int vox_sample(int32_t num_streams, int32_t vocab, const float* logit
   if (num_streams <= 0 || vocab <= 0 || vocab > vox::kMaxVocab || window < 0)
     return VOX_ERR_SHAPE;
   if (!logits || !params || !uniforms || !tokens || (window > 0 && !history)) return VOX_ERR_NULL;
+  using namespace vox;
+  const dim3 grid((unsigned)num_streams);
+  hipStream_t st = (hipStream_t)hip_stream;
   // large vocabularies whose rows start 16-byte aligned are read four tokens per lane and load
-  const bool quad = vocab >= vox::kQuadMinVocab && vocab % 4 == 0 && ((uintptr_t)logits & 15) == 0;
-  if (quad)
-    hipLaunchKernelGGL(vox::sample_kernel<true>, dim3((unsigned)num_streams),
-                       dim3(vox::kThreads), 0, (hipStream_t)hip_stream, vocab, logits, params,
-                       history, window, uniforms, tokens, kept);
+  const bool quad = vocab >= kQuadMinVocab && vocab % 4 == 0 && ((uintptr_t)logits & 15) == 0;
+  if (vocab <= SmallVocab::kVocab && !quad)
+    hipLaunchKernelGGL((sample_kernel<SmallVocab, false>), grid, dim3(SmallVocab::kThreads), 0, st,
+                       vocab, logits, params, history, window, uniforms, tokens, kept);
+  else if (quad)
+    hipLaunchKernelGGL((sample_kernel<AnyVocab, true>), grid, dim3(AnyVocab::kThreads), 0, st,
+                       vocab, logits, params, history, window, uniforms, tokens, kept);
   else
-    hipLaunchKernelGGL(vox::sample_kernel<false>, dim3((unsigned)num_streams),
-                       dim3(vox::kThreads), 0, (hipStream_t)hip_stream, vocab, logits, params,
-                       history, window, uniforms, tokens, kept);
+    hipLaunchKernelGGL((sample_kernel<AnyVocab, false>), grid, dim3(AnyVocab::kThreads), 0, st,
+                       vocab, logits, params, history, window, uniforms, tokens, kept);
   return hipGetLastError() == hipSuccess ? VOX_OK : VOX_ERR_HIP;
 }
 
@@ -630,8 +680,8 @@ extern "C" int vox_sample_weights(int32_t num_streams, int32_t vocab, const floa
   if (num_streams <= 0 || vocab <= 0 || vocab > vox::kMaxVocab || window < 0)
     return VOX_ERR_SHAPE;
   if (!logits || !params || !d_out || !w_out || (window > 0 && !history)) return VOX_ERR_NULL;
-  hipLaunchKernelGGL(vox::sample_weights_kernel, dim3((unsigned)num_streams),
-                     dim3(vox::kThreads), 0, (hipStream_t)hip_stream, vocab, logits, params,
-                     history, window, d_out, (unsigned long long*)w_out);
+  hipLaunchKernelGGL(vox::sample_weights_kernel<vox::AnyVocab>, dim3((unsigned)num_streams),
+                     dim3(vox::AnyVocab::kThreads), 0, (hipStream_t)hip_stream, vocab, logits,
+                     params, history, window, d_out, (unsigned long long*)w_out);
   return hipGetLastError() == hipSuccess ? VOX_OK : VOX_ERR_HIP;
 }
