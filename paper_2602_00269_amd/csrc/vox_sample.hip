@@ -138,6 +138,8 @@ __device__ inline int first_reaching(const unsigned long long* cum, int n,
   return lo;
 }
 
+// Everything that depends on the workgroup shape, as static members of a class template (laid
+// out like a namespace: members are not indented).
 template <class Cfg>
 struct Sampler {
 static constexpr int kThreads = Cfg::kThreads;
@@ -627,7 +629,6 @@ static __device__ void sample_body(
 }
 
 };  // Sampler
-
 
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::kThreads) void sample_weights_kernel(
