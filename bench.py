@@ -34,7 +34,7 @@ METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 MEASURED_TRAFFIC = {
     "cfg3": 2356073726, "cfg4": 2730018149, "cfg5": 1103168749,
     "chunk15": 2444113393, "chunk25": 2568395584, "chunk28": 2414441910, "admit": 2989020947,
-    "prefill": 468359012, "sample_small": 45368174, "sample_large": 330291045,
+    "prefill": 468359012, "sample_small": 27864508, "sample_large": 321869659,
 }
 
 

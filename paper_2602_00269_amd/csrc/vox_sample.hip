@@ -412,37 +412,37 @@ static __device__ void build_key_histogram(Lds& s, const Ctx& c) {
   __syncthreads();
 }
 
-// General path: every cut by radix descent over the whole vocabulary.
+// General path: every cut by radix descent over the whole vocabulary.  It may be compiled as a
+// real call, so everything goes in and comes out by value: an argument passed by address would
+// make the caller keep that object in memory, and store it, on the fast path too.
+struct Picked {
+  int token, n_kept;
+};
 template <class Ctx>
-static __device__ void sample_general(Lds& s, const Ctx& c, const vox_sampling_t& prm, bool greedy,
-                               float u, int* token, int* n_kept) {
+static __device__ Picked sample_general(Lds& s, const Ctx c, const float top_p, const int top_k,
+                                        bool greedy, float u) {
   build_key_histogram(s, c);
-  if (greedy) {
-    *token = (int)(locate(s, c, false, 1).comp & (kMaxVocab - 1));
-    *n_kept = 1;
-    return;
-  }
+  if (greedy) return {(int)(locate(s, c, false, 1).comp & (kMaxVocab - 1)), 1};
   unsigned long long total;
   unsigned long long n = (unsigned long long)c.V;
-  if (prm.top_k > 0 && prm.top_k < c.V) {
-    const Located k = locate(s, c, false, (unsigned long long)prm.top_k);
-    n = (unsigned long long)prm.top_k;
+  if (top_k > 0 && top_k < c.V) {
+    const Located k = locate(s, c, false, (unsigned long long)top_k);
+    n = (unsigned long long)top_k;
     total = k.through_mass;
   } else {
     scan_bins(s, s.cnt0, s.mass + kBins, kBins, false, ~0ull);  // no crossing: totals only
     total = s.total_mass;
     __syncthreads();
   }
-  if (prm.top_p < 1.0f) {
-    unsigned long long thr = (unsigned long long)((double)prm.top_p * (double)total);
+  if (top_p < 1.0f) {
+    unsigned long long thr = (unsigned long long)((double)top_p * (double)total);
     if (thr < 1) thr = 1;
     const Located pcut = locate(s, c, true, thr);
     n = pcut.through_cnt;
     total = pcut.through_mass;
   }
   const unsigned long long target = (unsigned long long)((double)u * (double)total);
-  *token = (int)(locate(s, c, true, target + 1).comp & (kMaxVocab - 1));
-  *n_kept = (int)n;
+  return {(int)(locate(s, c, true, target + 1).comp & (kMaxVocab - 1)), (int)n};
 }
 
 // Fast path.  The cuts almost always lie among the few tokens next to the maximum.  In the same
@@ -539,7 +539,9 @@ static __device__ void sample_body(
 
   int token = 0, n_kept = 1;
   if (!fast) {
-    sample_general(s, c, prm, greedy, u, &token, &n_kept);
+    const Picked g = sample_general(s, c, prm.top_p, prm.top_k, greedy, u);
+    token = g.token;
+    n_kept = g.n_kept;
   } else {
     // keep the tokens up to the first cut's bucket (all later cuts lie among them), pad to a
     // power of two, sort by key; the histogram array is free now and takes the kept keys
