@@ -428,6 +428,68 @@ def test_many_streams_up_to_the_limit(dev):
         binding.paged_decode_workspace_bytes(sh)
 
 
+def test_pools_beyond_4_gib_address_like_small_ones(dev):
+    # 140 000 blocks of 8 heads x 4 KiB: each pool is 4.6 GB, so byte offsets of the top blocks
+    # need more than 32 bits.  The same blocks at the top of such a pool must give what they give
+    # in a small pool, bit for bit, in every entry point that forms a granule address (the rest
+    # of the big pools stays unwritten memory: nothing may read it).
+    lens, nq, hq, hkv, d = [300, 17, 1024, 0, 50, 2000], [20, 1, 7, 0, 50, 3], 24, 8, 128
+    w, qo, q, k_new, v_new = _prefill_case(dev, lens, nq, hq, hkv, d, seed=73)
+    big_blocks = 140_000
+    shift = big_blocks - w.num_blocks
+    assert big_blocks * hkv * 16 * d * 2 > (1 << 32) + (w.num_blocks * hkv * 16 * d * 2)
+    kb = torch.empty((big_blocks,) + tuple(w.k_pool[0].shape[1:]), dtype=torch.bfloat16, device=dev)
+    vb = torch.empty_like(kb)
+    kb[shift:].copy_(w.k_pool[0])
+    vb[shift:].copy_(w.v_pool[0])
+    tb = w.block_tables.copy()
+    tb[tb >= 0] += shift
+    sh = binding.shape_of(w, split_waves=64)
+    shb = binding.make_shape(w.num_streams, hq, hkv, d, big_blocks, w.max_blocks_per_stream,
+                             w.scale, split_waves=64)
+    bt, btb, lens_d, qo_d = _i32(w.block_tables, dev), _i32(tb, dev), _i32(w.context_lens, dev), _i32(qo, dev)
+
+    def same_pools(what):
+        torch.cuda.synchronize()
+        assert torch.equal(kb[shift:].view(torch.int16), w.k_pool[0].view(torch.int16)), what
+        assert torch.equal(vb[shift:].view(torch.int16), w.v_pool[0].view(torch.int16)), what
+
+    # single-token append, then decode
+    binding.kv_append(sh, w.k_new[0], w.v_new[0], w.k_pool[0], w.v_pool[0], bt, lens_d)
+    binding.kv_append(shb, w.k_new[0], w.v_new[0], kb, vb, btb, lens_d)
+    same_pools("kv_append")
+    out, _ = _decode(w, dev, waves=64)
+    ref, _ = _oracle_decode(w)
+    _assert_close(out, ref, "small pool")
+    outb = torch.full((w.num_streams, hq, d), float("nan"), device=dev)
+    binding.paged_decode(shb, w.q[0], kb, vb, btb, lens_d, outb, binding.alloc_workspace(shb, dev),
+                         context_lens_host=w.context_lens)
+    torch.cuda.synchronize()
+    assert np.array_equal(outb.cpu().numpy(), out), "paged_decode"
+    # multi-token append and attention
+    tq = int(qo[-1])
+    binding.kv_append_multi(sh, k_new, v_new, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d)
+    binding.kv_append_multi(shb, k_new, v_new, kb, vb, btb, lens_d, qo_d)
+    same_pools("kv_append_multi")
+    outs = []
+    for s, kp, vp, tab in ((sh, w.k_pool[0], w.v_pool[0], bt), (shb, kb, vb, btb)):
+        o = torch.full((tq, hq, d), float("nan"), device=dev)
+        ws = torch.empty(binding.paged_prefill_workspace_bytes(s, tq), dtype=torch.uint8, device=dev)
+        binding.paged_prefill(s, q, kp, vp, tab, lens_d, qo_d, w.context_lens, qo, o, ws)
+        torch.cuda.synchronize()
+        outs.append(o.cpu().numpy())
+    assert np.isfinite(outs[0]).all() and np.array_equal(outs[0], outs[1]), "paged_prefill"
+    # gather
+    kp_h, vp_h = _host_pools(w)
+    k_ref, v_ref, offs = oracle.kv_gather(kp_h, vp_h, w.block_tables, w.context_lens,
+                                          num_kv_heads=hkv, head_dim=d)
+    k_out = torch.zeros((int(w.context_lens.sum()), hkv, d), dtype=torch.bfloat16, device=dev)
+    v_out = torch.zeros_like(k_out)
+    binding.kv_gather(shb, kb, vb, btb, lens_d, torch.from_numpy(offs).to(dev), k_out, v_out)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(k_out), k_ref) and np.array_equal(bits_of(v_out), v_ref)
+
+
 def test_workspace_reuse_across_calls_with_different_lengths(dev):
     # the same workspace serves calls whose step counts differ; nothing of the earlier plan or
     # of its partial records may leak into the later result
