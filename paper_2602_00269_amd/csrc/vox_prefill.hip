@@ -12,7 +12,6 @@
 #include <cfloat>
 
 #include "vox_decode_core.hpp"
-#include "vox_merge.hpp"
 
 namespace vox {
 namespace {
@@ -585,23 +584,57 @@ __global__ __launch_bounds__(256) void mq_expand_kernel(
 
 // ---------------------------------------------------------------------------------------
 // Merge of the segments that were cut into several runs (the others wrote their rows
-// themselves): workgroup (w, y) takes entry w of the list, its four waves columns 4y .. 4y+3
-// of the segment's records, one (query row, q head) each.
+// themselves): workgroup (w, y) takes entry w of the list and column group y of its records;
+// each of its four waves takes four of the group's 16 columns, one (query row, q head) per 16
+// lanes, a lane D/16 consecutive dims.  Two passes over the runs' records: the largest maximum
+// (16 runs at a time across the lanes), then the weighted sums (every lane of a column reads the
+// run's (max, sum) itself; nothing moves between lanes there).
 template <int D>
 __global__ __launch_bounds__(256) void mq_merge_kernel(
     Params p, int ncg, const SplitSegment* __restrict__ split, const float2* __restrict__ pml,
     const float* __restrict__ pacc, float* __restrict__ out, float* __restrict__ lse) {
+  constexpr int DPL = D / 16;  // dims per lane
   const SplitSegment e = split[blockIdx.x];
   if (e.nruns == 0) return;
-  const int lane = threadIdx.x & (kWave - 1);
-  const int col = blockIdx.y * kWavesPerGroup + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & (kWave - 1), l16 = lane & 15;
+  const int col = blockIdx.y * kCols + (threadIdx.x >> 6) * 4 + (lane >> 4);
   const int tqg = kCols / p.G;  // tokens per column group
   const int nn = col & (kCols - 1), j = nn / p.G, g = nn - j * p.G;
-  const int tok = (col / kCols) * tqg + j;
-  if (j >= tqg || tok >= e.nq) return;  // a column without a query row
+  const int tok = blockIdx.y * tqg + j;
+  const bool real = j < tqg && tok < e.nq;  // a column with a query row
+  // columns without a row have no runs to walk (the 16 lanes of a column stay together, so
+  // the shuffles below always find their partners)
+  const int cols = kCols * ncg, n = real ? e.nruns : 0;
+  const size_t rec0 = (size_t)e.slot0 * cols + col;
+  float mx = -INFINITY, sum = 0.f;
+  f32x4 acc[DPL / 4];
+#pragma unroll
+  for (int k = 0; k < DPL / 4; ++k) acc[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int r0 = 0; r0 < n; r0 += 16) {
+    const int r = r0 + l16;
+    float m = r < n ? pml[rec0 + (size_t)r * cols].x : -INFINITY;
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    mx = fmaxf(mx, m);
+  }
+#pragma unroll 4
+  for (int r = 0; r < n; ++r) {
+    const size_t rec = rec0 + (size_t)r * cols;
+    const float2 ml = pml[rec];
+    const f32x4* src = reinterpret_cast<const f32x4*>(pacc + rec * D + l16 * DPL);
+    const float wgt = ml.x == -INFINITY ? 0.f : exp2f(ml.x - mx);
+    sum += wgt * ml.y;
+#pragma unroll
+    for (int k = 0; k < DPL / 4; ++k) acc[k] += wgt * src[k];
+  }
+  if (!real) return;
+  const float inv = sum > 0.f ? 1.f / sum : 0.f;
   const size_t w = (size_t)(e.q_row0 + tok) * p.Hq + e.h * p.G + g;
-  merge_runs<D>(pml, pacc, e.slot0, e.nruns, kCols * ncg, col, lane, out + w * D,
-                lse ? lse + w : nullptr);
+  f32x4* dst = reinterpret_cast<f32x4*>(out + w * D + l16 * DPL);
+#pragma unroll
+  for (int k = 0; k < DPL / 4; ++k) dst[k] = acc[k] * inv;
+  if (lse && l16 == 0)
+    lse[w] = sum > 0.f ? (mx + log2f(sum)) * 0.69314718055994530942f : -INFINITY;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -814,7 +847,7 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
     }
     if (ev_after) (void)hipEventRecord(ev_after, st);
     // every range start cuts at most one segment: `waves` bounds the list
-    const dim3 mg((unsigned)waves, (unsigned)(kCols * ncg / kWavesPerGroup));
+    const dim3 mg((unsigned)waves, (unsigned)ncg);
     if (p.D == 128)
       hipLaunchKernelGGL(mq_merge_kernel<128>, mg, dim3(256), 0, st, p, ncg, split, pml, pacc, out,
                          lse);
