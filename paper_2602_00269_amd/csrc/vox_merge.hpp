@@ -1,7 +1,7 @@
 // Merge of the partial (max, sum, accumulator) records of one output row: the runs of a segment
 // occupy consecutive slots; lanes hold the runs' (max, sum) records, the global max and the
 // rescaled sum are wave reductions, and the accumulators are combined with each lane owning
-// D/64 output dims.  Shared by the decode and the multi-token merge kernels.
+// D/64 output dims.  Used by the decode step's merge kernel.
 #pragma once
 
 #include "vox_common.hpp"
