@@ -33,7 +33,7 @@ METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 # in profiles/*_<workload>*.txt.  Workloads without a counter run report null.
 MEASURED_TRAFFIC = {
     "cfg3": 2356073726, "cfg4": 2730018149, "cfg5": 1103168749,
-    "chunk15": 2444163013, "chunk25": 2568399055, "chunk28": 2414360087, "admit": 2988930564,
+    "chunk15": 2444163013, "chunk25": 2568399055, "chunk28": 2414360087, "admit": 2963961819,
     "prefill": 468522237, "sample_small": 27864508, "sample_large": 321869659,
 }
 
@@ -125,7 +125,13 @@ def bench_multi(args, dev) -> int:
         ach = kv_bytes / (kern_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4)}
-    roofline.update({"kernel": "decode_kernel<MqMath>", "kernel_ms": round(kern_ms, 4),
+    # a batch with many single-token streams runs those through the decode kernel: the events
+    # then enclose both attention kernels
+    singles = int((n64 == 1).sum())
+    kernels = "decode_kernel<MqMath>"
+    if singles >= 32:
+        kernels = "decode_kernel<MfmaMath>" + (" + decode_kernel<MqMath>" if (n64 > 1).any() else "")
+    roofline.update({"kernel": kernels, "kernel_ms": round(kern_ms, 4),
                      "bytes_per_launch": kv_bytes, "flops_per_launch": flops,
                      "traffic": MEASURED_TRAFFIC.get(args.workload)})
 

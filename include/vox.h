@@ -236,6 +236,11 @@ int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const voi
  * With no query rows at all (total_q == 0) both calls return VOX_OK and touch nothing.
  * vox_paged_prefill_workspace_bytes(shape, total_q) is enough for any lengths the shape
  * admits; a smaller workspace is accepted when the actual step count fits.
+ * A batch may mix decoding streams (n_s = 1) with prompts and chunks, as during admission
+ * (Section 3.2.1): when 32 or more streams bring exactly one token those are computed by the
+ * kernels of vox_paged_decode and the others by the multi-token kernels, in the same call and
+ * with the same results; the workspace size above has room for both (with a smaller workspace
+ * every stream takes the multi-token kernels).
  */
 size_t vox_paged_prefill_workspace_bytes(const vox_shape_t* shape, int32_t total_q);
 int vox_kv_append_multi(const vox_shape_t* shape, const void* k_new, const void* v_new,
@@ -251,7 +256,8 @@ int vox_paged_prefill(const vox_shape_t* shape, const void* q, const void* k_poo
 
 /*
  * Measurement aid: vox_paged_prefill that also records two caller-created hipEvent_t on
- * hip_stream around the multi-token attention kernel (the launch that reads the KV cache).
+ * hip_stream around the multi-token attention kernel (the launch that reads the KV cache; in a
+ * mixed batch the two launches that do, decode kernel first).
  * Either event may be NULL; with no query rows at all nothing is launched or recorded.
  */
 int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const void* k_pool,

@@ -1,6 +1,9 @@
 // C-ABI entry points: host-side validation, split-K sizing and launches.
-// Nothing here allocates, synchronises or copies; every call only enqueues kernels.
+// Nothing here allocates device memory, synchronises or copies; every call only enqueues
+// kernels.
 #include <math.h>
+
+#include <vector>
 
 #include "vox_common.hpp"
 
@@ -64,6 +67,8 @@ Params make_params(const vox_shape_t* s) {
   p.wave_clock = nullptr;
   p.out = nullptr;
   p.lse = nullptr;
+  p.q_rows = nullptr;
+  p.skip_single = 0;
   return p;
 }
 
@@ -195,6 +200,16 @@ int enqueue_attention(const vox_shape_t* s, const Params& p, const Plan& plan, c
   }
   if (ev_after && hipEventRecord(ev_after, st) != hipSuccess) return VOX_ERR_HIP;
   return VOX_OK;
+}
+
+// Mixed batches of the multi-token step.  A stream that brings exactly one token is a decode
+// stream: the decode kernels (a pool of short ranges against the tail, three steps in flight,
+// records kept in LDS) serve it better than a one-row tile of the multi-token kernel, so when
+// there are enough of them they take those streams and the multi-token kernels the rest.  The
+// workspace then holds, after the multi-token part: the masked lengths, the decode workspace.
+constexpr int kMinSingleStreams = 32;
+size_t mixed_batch_base(size_t prefill_bytes, const vox_shape_t* s) {
+  return align_up(prefill_bytes, 256) + align_up((size_t)s->num_streams * sizeof(int32_t), 256);
 }
 
 }  // namespace
@@ -406,7 +421,10 @@ size_t vox_paged_prefill_workspace_bytes(const vox_shape_t* shape, int32_t total
     const int c = prefill_column_groups(p, rows);
     if (c > ncg) ncg = c;
   }
-  return map_prefill_workspace(p, ncg, tiles, slots, steps, split_waves(shape)).total;
+  // a mixed batch also runs the decode kernels on the streams that bring one token
+  return mixed_batch_base(map_prefill_workspace(p, ncg, tiles, slots, steps, split_waves(shape)).total,
+                          shape) +
+         map_workspace(shape, steps_bound(shape)).total;
 }
 
 int vox_kv_append_multi(const vox_shape_t* shape, const void* k_new, const void* v_new,
@@ -451,41 +469,93 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
       !workspace)
     return VOX_ERR_NULL;
   if ((uintptr_t)workspace % 256 || !all_aligned16(q, k_pool, v_pool, out)) return VOX_ERR_ARG;
-  const Params p = make_params(shape);
+  Params p = make_params(shape);
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
   // exact tile and step counts from the host copies (the scheduler that admits a prompt
   // knows its length)
   if (q_offsets_host[0] != 0) return VOX_ERR_ARG;
-  int64_t max_new = 0;
-  for (int s = 0; s < p.S; ++s) {
-    const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
-    if (n > max_new) max_new = n;
-  }
-  const int ncg = prefill_column_groups(p, (int)(max_new < INT32_MAX ? max_new : INT32_MAX));
-  const int tq = (16 / p.G) * ncg;
-  int64_t tiles = 0, steps = 0;
+  int singles = 0;
   for (int s = 0; s < p.S; ++s) {
     const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
     const int64_t L = context_lens_host[s];
     if (n < 0 || n > L || L > (int64_t)shape->max_blocks_per_stream * kBlock) return VOX_ERR_ARG;
-    const int64_t nt = (n + tq - 1) / tq;
-    for (int64_t tau = 0; tau < nt; ++tau) {
-      const int64_t ctx = L - n + (n < (tau + 1) * tq ? n : (tau + 1) * tq);
-      steps += (ctx + kStepTokens - 1) / kStepTokens;
-    }
-    tiles += nt;
+    singles += n == 1;
   }
-  steps *= p.Hkv;
-  if (steps > INT32_MAX || tiles * p.Hkv > INT32_MAX / 2) return VOX_ERR_SHAPE;
   const int waves = split_waves(shape);
-  const int64_t slots = waves + tiles * p.Hkv;
-  const PrefillWorkspace m = map_prefill_workspace(p, ncg, tiles, slots, steps, waves);
-  if (m.total > workspace_bytes) return VOX_ERR_WORKSPACE;
-  return launch_prefill(p, m, (char*)workspace, ncg, tiles, steps, steps, waves, q,
-                        k_pool, v_pool, block_tables, context_lens, q_offsets, out, lse,
-                        (hipStream_t)hip_stream, (hipEvent_t)event_before,
-                        (hipEvent_t)event_after) == hipSuccess
-             ? VOX_OK
-             : VOX_ERR_HIP;
+  // Two passes at most: with the single-token streams left to the decode kernels when there are
+  // enough of them and the workspace has room for both parts, else with every stream here.
+  for (int mixed = (singles >= kMinSingleStreams && shape->decode_path != VOX_PATH_VALU) ? 1 : 0;
+       mixed >= 0; --mixed) {
+    int64_t max_new = 0, tile_streams = 0;
+    for (int s = 0; s < p.S; ++s) {
+      const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
+      if (mixed && n == 1) continue;
+      if (n > max_new) max_new = n;
+      tile_streams += n > 0;
+    }
+    const int ncg = prefill_column_groups(p, (int)(max_new < INT32_MAX ? max_new : INT32_MAX));
+    const int tq = (16 / p.G) * ncg;
+    int64_t tiles = 0, steps = 0;
+    for (int s = 0; s < p.S; ++s) {
+      const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
+      if (mixed && n == 1) continue;
+      const int64_t L = context_lens_host[s];
+      const int64_t nt = (n + tq - 1) / tq;
+      for (int64_t tau = 0; tau < nt; ++tau) {
+        const int64_t ctx = L - n + (n < (tau + 1) * tq ? n : (tau + 1) * tq);
+        steps += (ctx + kStepTokens - 1) / kStepTokens;
+      }
+      tiles += nt;
+    }
+    steps *= p.Hkv;
+    if (steps > INT32_MAX || tiles * p.Hkv > INT32_MAX / 2) return VOX_ERR_SHAPE;
+    const int64_t slots = waves + tiles * p.Hkv;
+    const PrefillWorkspace m = map_prefill_workspace(p, ncg, tiles, slots, steps, waves);
+    if (!mixed) {
+      if (m.total > workspace_bytes) return VOX_ERR_WORKSPACE;
+      return launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool,
+                            block_tables, context_lens, q_offsets, out, lse, st,
+                            (hipEvent_t)event_before, (hipEvent_t)event_after) == hipSuccess
+                 ? VOX_OK
+                 : VOX_ERR_HIP;
+    }
+    // the decode part: masked lengths on both sides, its own workspace behind the multi-token one
+    const size_t lens_off = align_up(m.total, 256), dec_off = mixed_batch_base(m.total, shape);
+    if (dec_off >= workspace_bytes) continue;
+    std::vector<int32_t> single_lens((size_t)p.S);
+    for (int s = 0; s < p.S; ++s)
+      single_lens[s] = q_offsets_host[s + 1] - q_offsets_host[s] == 1 ? context_lens_host[s] : 0;
+    Plan plan;
+    if (make_plan(shape, single_lens.data(), workspace_bytes - dec_off, &plan) != VOX_OK) continue;
+    int32_t* lens_single = (int32_t*)(ws + lens_off);
+    char* dws = ws + dec_off;
+    Params pd = p;  // the decode kernels' view
+    pd.q_rows = q_offsets;
+    pd.pool_counter = pool_counter(plan, dws, 0);
+    set_step_hints(&pd, plan);
+    p.skip_single = 1;  // the multi-token plan's view
+    if (launch_single_token_lens(p.S, context_lens, q_offsets, lens_single, st) != hipSuccess)
+      return VOX_ERR_HIP;
+    if (int rc = enqueue_plan(pd, plan, dws, block_tables, lens_single, st)) return rc;
+    if (launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool, block_tables,
+                       context_lens, q_offsets, out, lse, st, nullptr, nullptr, kPrefillPlan,
+                       tile_streams) != hipSuccess)
+      return VOX_ERR_HIP;
+    const WsPtrs w = ws_ptrs(plan, dws);
+    // the events enclose both attention kernels
+    if (int rc = enqueue_attention(shape, pd, plan, w, q, k_pool, v_pool, st,
+                                   (hipEvent_t)event_before, tiles > 0 ? nullptr : (hipEvent_t)event_after))
+      return rc;
+    if (launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool, block_tables,
+                       context_lens, q_offsets, out, lse, st, nullptr, (hipEvent_t)event_after,
+                       kPrefillRun, tile_streams) != hipSuccess)
+      return VOX_ERR_HIP;
+    return launch_merge(pd, w.header, w.step_prefix, w.pml, w.pacc, out, lse, st) == hipSuccess
+               ? VOX_OK
+               : VOX_ERR_HIP;
+  }
+  return VOX_ERR_WORKSPACE;  // not reached: the pass with every stream here returns
 }
 
 const char* vox_strerror(int code) {

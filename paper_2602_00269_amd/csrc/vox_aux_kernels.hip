@@ -313,8 +313,9 @@ __device__ inline void merge_role(const Params& p, int group, const int32_t* __r
     n = (int)(r1 - r0 + 1);
     slot0 = r0 + sigma;
   }
-  merge_runs<D>(pml, pacc, slot0, n, p.G, g, lane, out + ((size_t)s * p.Hq + i) * D,
-                lse ? lse + (size_t)s * p.Hq + i : nullptr);
+  if (p.q_rows && n == 0) return;  // packed rows: a stream without a run owns no output row
+  const size_t row = (size_t)(p.q_rows ? p.q_rows[s] : s) * p.Hq + i;
+  merge_runs<D>(pml, pacc, slot0, n, p.G, g, lane, out + row * D, lse ? lse + row : nullptr);
 }
 
 template <int D>

@@ -155,6 +155,12 @@ struct Params {
   // ([rows][Hq][D] fp32 and, if not null, [rows][Hq] log-sum-exp)
   float* out;
   float* lse;
+  // Mixed batches of the multi-token step: streams that bring exactly one token go through the
+  // decode kernels, the others through the multi-token kernels.  q_rows (decode side; null in
+  // the plain decode step): stream s's query row and output row is q_rows[s] of the packed row
+  // arrays instead of s.  skip_single (multi-token plan): such streams get no tiles.
+  const int32_t* q_rows;
+  int32_t skip_single;
 };
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -209,12 +215,17 @@ hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_ne
                                   const void* v_new, void* k_pool, void* v_pool,
                                   const int32_t* bt, const int32_t* lens, const int32_t* qo,
                                   hipStream_t st);
+// launch_prefill does the plan kernels, the attention and merge kernels, or both
+constexpr int kPrefillPlan = 1, kPrefillRun = 2;
+hipError_t launch_single_token_lens(int S, const int32_t* lens, const int32_t* qo,
+                                    int32_t* lens_single, hipStream_t st);
 hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, int ncg,
                           int64_t tiles, int64_t steps, int64_t desc_capacity, int waves,
                           const void* q, const void* k_pool, const void* v_pool,
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
                           float* lse, hipStream_t st, hipEvent_t ev_before,
-                          hipEvent_t ev_after);
+                          hipEvent_t ev_after, int phases = kPrefillPlan | kPrefillRun,
+                          int64_t tile_streams = 0);
 hipError_t launch_decode_mfma(const Params& p, int waves, const void* q, const void* k_pool,
                               const void* v_pool, const int32_t* header, const int4* desc,
                               float2* partial_ml, float* partial_acc, hipStream_t st);

@@ -51,7 +51,9 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
 }
 __device__ inline float round_bf16(float a) { return (float)(__bf16)a; }
 
-template <int D, int NBUF>
+// PACKED: the streams' query rows are packed rows q_rows[s] (mixed batches of the multi-token
+// step) instead of rows s.
+template <int D, int NBUF, bool PACKED = false>
 struct MfmaMath {
   typedef int4 Desc;  // decode step descriptor, see the plan kernel
   __device__ static int ga(const Desc& d) { return d.x; }
@@ -95,7 +97,11 @@ struct MfmaMath {
 
   // Query operand of segment sigma: column n -> row sigma*G + (n mod G) for n < 2G, else zero.
   __device__ void load_q(Q& out, State&, const uint16_t* __restrict__ q, const Desc& dsc) const {
-    const int sigma = dsc.w;
+    int sigma = dsc.w;
+    if (PACKED) {  // (stream, kv head) -> (packed row, kv head)
+      const int s = sigma / p.Hkv;
+      sigma = p.q_rows[s] * p.Hkv + (sigma - s * p.Hkv);
+    }
     const bool has = n < 2 * G;
     const int row = sigma * G + (has ? (n < G ? n : n - G) : 0);
     const uint16_t* qrow = q + (size_t)row * D + c * 8;
@@ -239,12 +245,12 @@ struct MfmaMath {
   }
 };
 
-template <int D, int NBUF>
+template <int D, int NBUF, bool PACKED = false>
 hipError_t launch_one(const Params& p, int waves, const void* q, const void* k_pool,
                       const void* v_pool, const int32_t* header, const int4* desc, float2* pml,
                       float* pacc, hipStream_t st) {
   const unsigned grid = (unsigned)((waves + kWavesPerGroup - 1) / kWavesPerGroup);
-  hipLaunchKernelGGL((decode_kernel<MfmaMath<D, NBUF>>), dim3(grid), dim3(256), 0, st, p,
+  hipLaunchKernelGGL((decode_kernel<MfmaMath<D, NBUF, PACKED>>), dim3(grid), dim3(256), 0, st, p,
                      (const uint16_t*)q, (const uint16_t*)k_pool, (const uint16_t*)v_pool, header,
                      desc, pml, pacc);
   return hipGetLastError();
@@ -257,6 +263,11 @@ hipError_t launch_decode_mfma(const Params& p, int waves, const void* q, const v
                               float2* partial_ml, float* partial_acc, hipStream_t st) {
   // Ring depth: three 32-token steps (48 KiB of loads in flight per wave) at head_dim 128, two
   // at head_dim 64 where deeper rings measured no faster.
+  if (p.q_rows)
+    return p.D == 128 ? launch_one<128, 3, true>(p, waves, q, k_pool, v_pool, header, desc,
+                                                 partial_ml, partial_acc, st)
+                      : launch_one<64, 2, true>(p, waves, q, k_pool, v_pool, header, desc,
+                                                partial_ml, partial_acc, st);
   return p.D == 128 ? launch_one<128, 3>(p, waves, q, k_pool, v_pool, header, desc, partial_ml,
                                          partial_acc, st)
                     : launch_one<64, 2>(p, waves, q, k_pool, v_pool, header, desc, partial_ml,

@@ -377,6 +377,12 @@ struct MqMath {
 //           ceil(ctx_tile / 32); exclusive scans PT (tiles) and PS (steps, per kv head).
 //   tiles:  per tile its first global step, step count, TileInfo and the row -> tile map.
 //   expand: per global step its descriptor (binary search over the tiles' first steps).
+// New tokens of stream s as the plan sees them: in a mixed batch the streams that bring exactly
+// one token are left to the decode kernels.
+__device__ inline int planned_tokens(const Params& p, const int32_t* __restrict__ qo, int s) {
+  const int n = qo[s + 1] - qo[s];
+  return (p.skip_single && n == 1) ? 0 : n;
+}
 __device__ inline int tile_ctx(int L, int n, int tq, int tau) {
   return L - n + min(n, (tau + 1) * tq);  // tokens visible to the tile's last query
 }
@@ -395,7 +401,7 @@ __global__ __launch_bounds__(kScanThreads) void mq_scan_kernel(
   const int lo = min(S, tid * per), hi = min(S, lo + per);
   int tiles = 0, steps = 0;
   for (int s = lo; s < hi; ++s) {
-    const int L = lens[s], n = qo[s + 1] - qo[s];
+    const int L = lens[s], n = planned_tokens(p, qo, s);
     const int nt = (n + tq - 1) / tq;
     for (int tau = 0; tau < nt; ++tau) steps += steps_of(tile_ctx(L, n, tq, tau));
     tiles += nt;
@@ -422,7 +428,7 @@ __global__ __launch_bounds__(kScanThreads) void mq_scan_kernel(
   for (int s = lo; s < hi; ++s) {  // second walk writes the exclusive prefixes
     pt[s] = bt_;
     ps[s] = bs_;
-    const int L = lens[s], n = qo[s + 1] - qo[s];
+    const int L = lens[s], n = planned_tokens(p, qo, s);
     const int nt = (n + tq - 1) / tq;
     for (int tau = 0; tau < nt; ++tau) bs_ += steps_of(tile_ctx(L, n, tq, tau));
     bt_ += nt;
@@ -456,7 +462,7 @@ __global__ __launch_bounds__(256) void mq_tiles_kernel(
       b = mid;
   }
   const int s = a, tau = t - pt[s];
-  const int L = lens[s], n = qo[s + 1] - qo[s];
+  const int L = lens[s], n = planned_tokens(p, qo, s);
   int cum = 0;
   for (int k = 0; k < tau; ++k) cum += steps_of(tile_ctx(L, n, tq, k));
   tile_first[t] = (ps[s] + cum) * p.Hkv;
@@ -706,7 +712,23 @@ __global__ __launch_bounds__(256) void kv_append_multi_kernel(
   }
 }
 
+// Context lengths as the decode kernels of a mixed batch see them: streams with exactly one
+// new token keep theirs, all others become padded slots.
+__global__ __launch_bounds__(256) void single_token_lens_kernel(
+    int S, const int32_t* __restrict__ lens, const int32_t* __restrict__ qo,
+    int32_t* __restrict__ lens_single) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s < S) lens_single[s] = (qo[s + 1] - qo[s] == 1) ? lens[s] : 0;
+}
+
 }  // namespace
+
+hipError_t launch_single_token_lens(int S, const int32_t* lens, const int32_t* qo,
+                                    int32_t* lens_single, hipStream_t st) {
+  hipLaunchKernelGGL(single_token_lens_kernel, dim3((unsigned)((S + 255) / 256)), dim3(256), 0, st,
+                     S, lens, qo, lens_single);
+  return hipGetLastError();
+}
 
 // Workspace map of the multi-token step (byte offsets), for `tiles` tiles at most, `slots`
 // partial records, `desc_capacity` step descriptors and `waves` ranges.
@@ -784,10 +806,11 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
                           int64_t tiles, int64_t steps, int64_t desc_capacity, int waves,
                           const void* q, const void* k_pool, const void* v_pool,
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
-                          float* lse, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
+                          float* lse, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after,
+                          int phases, int64_t tile_streams) {
   const int tq = (kCols / p.G) * ncg;  // query tokens per tile
   // most of the work re-reads contexts (several tiles per stream): keep K/V in the caches
-  const bool reuse = tiles >= 4 * (int64_t)p.S;
+  const bool reuse = tiles >= 4 * (tile_streams > 0 ? tile_streams : (int64_t)p.S);
   int32_t* header = (int32_t*)(ws + m.header);
   int32_t* pt = (int32_t*)(ws + m.pt);
   int32_t* ps = (int32_t*)(ws + m.ps);
@@ -803,9 +826,10 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
   // about as much as four to six steps of a wave
   const int run_cost = 4;
 
-  hipLaunchKernelGGL(mq_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, p, tq, lens, qo, waves,
-                     desc_capacity, header, pt, ps);
-  if (tiles > 0) {
+  if (phases & kPrefillPlan)
+    hipLaunchKernelGGL(mq_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, p, tq, lens, qo, waves,
+                       desc_capacity, header, pt, ps);
+  if (tiles > 0 && (phases & kPrefillPlan)) {
     hipLaunchKernelGGL(mq_tiles_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, st,
                        p, tq, lens, qo, pt, ps, tile_first, tile_steps, tile_info);
     hipLaunchKernelGGL(mq_ranges_kernel, dim3((unsigned)((waves + kWavesPerGroup) / 256 + 1)), dim3(256), 0,
@@ -813,6 +837,8 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
     hipLaunchKernelGGL(mq_expand_kernel, dim3((unsigned)((steps + 255) / 256)), dim3(256), 0, st,
                        p, bt, header, pt, tile_first, tile_steps, tile_info, ranges, waves, desc,
                        split);
+  }
+  if (tiles > 0 && (phases & kPrefillRun)) {
     const unsigned grid = (unsigned)((waves + kWavesPerGroup - 1) / kWavesPerGroup);
     Params pk = p;  // every wave reads its range from the table the plan wrote
     pk.n_steps = -1;

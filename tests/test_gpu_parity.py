@@ -580,6 +580,41 @@ def test_multi_token_append_and_prefill_match_oracle(dev, case):
         _assert_lse(lse.cpu().numpy(), ref_lse, f"prefill case {case} waves {waves}")
 
 
+@pytest.mark.parametrize("hq,hkv,d,singles", [(24, 8, 128, 70), (14, 2, 64, 100), (8, 8, 64, 33)])
+def test_mixed_batches_of_decode_streams_and_prompts(dev, hq, hkv, d, singles):
+    # with 32 or more single-token streams in a call those go through the decode kernels and
+    # the rest through the multi-token kernels: both halves, the rows in between (n_s = 0, with
+    # and without a context) and the log-sum-exp must come out as one result
+    rng = np.random.default_rng(singles)
+    lens = list(rng.integers(1, 900, size=singles)) + [300, 64, 17, 0, 250, 1000, 40, 5]
+    nq = [1] * singles + [300, 20, 17, 0, 0, 45, 2, 5]
+    order = rng.permutation(len(lens))
+    lens, nq = [int(lens[i]) for i in order], [int(nq[i]) for i in order]
+    if singles == 100:  # nothing but single-token streams and empty slots
+        nq = [n if n <= 1 else 0 for n in nq]
+    w, qo, q, k_new, v_new = _prefill_case(dev, lens, nq, hq, hkv, d, seed=95 + singles)
+    sh = binding.shape_of(w)
+    bt, lens_d, qo_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev), _i32(qo, dev)
+    binding.kv_append_multi(sh, k_new, v_new, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d)
+    torch.cuda.synchronize()
+    kp, vp = _host_pools(w)
+    ref, ref_lse = oracle.paged_prefill(bits_of(q), kp, vp, w.block_tables, w.context_lens, qo,
+                                        w.scale, num_kv_heads=hkv)
+    tq = int(qo[-1])
+    for waves in (0, 8):
+        sh.split_waves = waves
+        out = torch.full((tq, hq, d), float("nan"), device=dev)
+        lse = torch.full((tq, hq), float("nan"), device=dev)
+        ws = torch.empty(binding.paged_prefill_workspace_bytes(sh, tq), dtype=torch.uint8,
+                         device=dev)
+        ws.fill_(0xFF)
+        binding.paged_prefill(sh, q, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d, w.context_lens,
+                              qo, out, ws, lse=lse)
+        torch.cuda.synchronize()
+        _assert_close(out.cpu().numpy(), ref, f"mixed batch waves {waves}")
+        _assert_lse(lse.cpu().numpy(), ref_lse, f"mixed batch waves {waves}")
+
+
 def test_prefill_with_one_token_per_stream_equals_decode(dev):
     lens = [33, 700, 64, 1, 255]
     w, qo, q, _, _ = _prefill_case(dev, lens, [1] * 5, 24, 8, 128, seed=90)
