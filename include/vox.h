@@ -237,10 +237,11 @@ int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const voi
  * vox_paged_prefill_workspace_bytes(shape, total_q) is enough for any lengths the shape
  * admits; a smaller workspace is accepted when the actual step count fits.
  * A batch may mix decoding streams (n_s = 1) with prompts and chunks, as during admission
- * (Section 3.2.1): when 32 or more streams bring exactly one token those are computed by the
- * kernels of vox_paged_decode and the others by the multi-token kernels, in the same call and
- * with the same results; the workspace size above has room for both (with a smaller workspace
- * every stream takes the multi-token kernels).
+ * (Section 3.2.1): when many streams bring exactly one token (32 or more, with 32 768 or more
+ * 32-token steps per kv head between them) those are computed by the kernels of
+ * vox_paged_decode and the others by the multi-token kernels, in the same call and with the
+ * same results; the workspace size above has room for both (with a smaller workspace every
+ * stream takes the multi-token kernels).
  */
 size_t vox_paged_prefill_workspace_bytes(const vox_shape_t* shape, int32_t total_q);
 int vox_kv_append_multi(const vox_shape_t* shape, const void* k_new, const void* v_new,

@@ -207,7 +207,10 @@ int enqueue_attention(const vox_shape_t* s, const Params& p, const Plan& plan, c
 // records kept in LDS) serve it better than a one-row tile of the multi-token kernel, so when
 // there are enough of them they take those streams and the multi-token kernels the rest.  The
 // workspace then holds, after the multi-token part: the masked lengths, the decode workspace.
+// The split costs four more launches (about 18 us): measured against the single kernel it pays
+// from about 32 k steps of single-token streams on (0.5 GB of K/V at head_dim 128).
 constexpr int kMinSingleStreams = 32;
+constexpr int64_t kMinSingleSteps = 32768;
 size_t mixed_batch_base(size_t prefill_bytes, const vox_shape_t* s) {
   return align_up(prefill_bytes, 256) + align_up((size_t)s->num_streams * sizeof(int32_t), 256);
 }
@@ -476,17 +479,22 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
   // knows its length)
   if (q_offsets_host[0] != 0) return VOX_ERR_ARG;
   int singles = 0;
+  int64_t single_steps = 0;
   for (int s = 0; s < p.S; ++s) {
     const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
     const int64_t L = context_lens_host[s];
     if (n < 0 || n > L || L > (int64_t)shape->max_blocks_per_stream * kBlock) return VOX_ERR_ARG;
-    singles += n == 1;
+    if (n == 1) {
+      ++singles;
+      single_steps += (L + kStepTokens - 1) / kStepTokens * p.Hkv;
+    }
   }
+  const bool split = singles >= kMinSingleStreams && single_steps >= kMinSingleSteps &&
+                     shape->decode_path != VOX_PATH_VALU;
   const int waves = split_waves(shape);
   // Two passes at most: with the single-token streams left to the decode kernels when there are
   // enough of them and the workspace has room for both parts, else with every stream here.
-  for (int mixed = (singles >= kMinSingleStreams && shape->decode_path != VOX_PATH_VALU) ? 1 : 0;
-       mixed >= 0; --mixed) {
+  for (int mixed = split ? 1 : 0; mixed >= 0; --mixed) {
     int64_t max_new = 0, tile_streams = 0;
     for (int s = 0; s < p.S; ++s) {
       const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];

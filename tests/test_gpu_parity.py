@@ -582,11 +582,15 @@ def test_multi_token_append_and_prefill_match_oracle(dev, case):
 
 @pytest.mark.parametrize("hq,hkv,d,singles", [(24, 8, 128, 70), (14, 2, 64, 100), (8, 8, 64, 33)])
 def test_mixed_batches_of_decode_streams_and_prompts(dev, hq, hkv, d, singles):
-    # with 32 or more single-token streams in a call those go through the decode kernels and
-    # the rest through the multi-token kernels: both halves, the rows in between (n_s = 0, with
+    # with many single-token streams in a call those go through the decode kernels and the
+    # rest through the multi-token kernels: both halves, the rows in between (n_s = 0, with
     # and without a context) and the log-sum-exp must come out as one result
     rng = np.random.default_rng(singles)
-    lens = list(rng.integers(1, 900, size=singles)) + [300, 64, 17, 0, 250, 1000, 40, 5]
+    # contexts long enough for the split to happen: 32 768 steps over the single-token streams
+    avg = 32 * 40000 // (singles * hkv)
+    lens = list(rng.integers(avg - avg // 4, avg + avg // 4, size=singles)) + [300, 64, 17, 0, 250, 1000, 40, 5]
+    lens[0], lens[1] = 1, 33  # short single-token streams among them
+    assert sum((L + 31) // 32 for L in lens[:singles]) * hkv >= 32768
     nq = [1] * singles + [300, 20, 17, 0, 0, 45, 2, 5]
     order = rng.permutation(len(lens))
     lens, nq = [int(lens[i]) for i in order], [int(nq[i]) for i in order]
