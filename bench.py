@@ -128,8 +128,9 @@ def bench_multi(args, dev) -> int:
     # a batch with many single-token streams runs those through the decode kernel: the events
     # then enclose both attention kernels
     singles = int((n64 == 1).sum())
+    single_steps = int(((lens64[n64 == 1] + 31) // 32).sum()) * base.num_kv_heads
     kernels = "decode_kernel<MqMath>"
-    if singles >= 32:
+    if singles >= 32 and single_steps >= 32768:  # the library's rule for splitting a batch
         kernels = "decode_kernel<MfmaMath>" + (" + decode_kernel<MqMath>" if (n64 > 1).any() else "")
     roofline.update({"kernel": kernels, "kernel_ms": round(kern_ms, 4),
                      "bytes_per_launch": kv_bytes, "flops_per_launch": flops,
