@@ -207,7 +207,7 @@ int enqueue_attention(const vox_shape_t* s, const Params& p, const Plan& plan, c
 // records kept in LDS) serve it better than a one-row tile of the multi-token kernel, so when
 // there are enough of them they take those streams and the multi-token kernels the rest.  The
 // workspace then holds, after the multi-token part: the masked lengths, the decode workspace.
-// The split costs four more launches (about 18 us): measured against the single kernel it pays
+// The split costs three more launches (about 15 us): measured against the single kernel it pays
 // from about 32 k steps of single-token streams on (0.5 GB of K/V at head_dim 128).
 constexpr int kMinSingleStreams = 32;
 constexpr int64_t kMinSingleSteps = 32768;
@@ -543,13 +543,12 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
     pd.pool_counter = pool_counter(plan, dws, 0);
     set_step_hints(&pd, plan);
     p.skip_single = 1;  // the multi-token plan's view
-    if (launch_single_token_lens(p.S, context_lens, q_offsets, lens_single, st) != hipSuccess)
-      return VOX_ERR_HIP;
-    if (int rc = enqueue_plan(pd, plan, dws, block_tables, lens_single, st)) return rc;
+    // the multi-token plan's first kernel also writes the masked lengths
     if (launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool, block_tables,
                        context_lens, q_offsets, out, lse, st, nullptr, nullptr, kPrefillPlan,
-                       tile_streams) != hipSuccess)
+                       tile_streams, lens_single) != hipSuccess)
       return VOX_ERR_HIP;
+    if (int rc = enqueue_plan(pd, plan, dws, block_tables, lens_single, st)) return rc;
     const WsPtrs w = ws_ptrs(plan, dws);
     // the events enclose both attention kernels
     if (int rc = enqueue_attention(shape, pd, plan, w, q, k_pool, v_pool, st,

@@ -393,7 +393,7 @@ constexpr int kScanThreads = 256;
 __global__ __launch_bounds__(kScanThreads) void mq_scan_kernel(
     Params p, int tq, const int32_t* __restrict__ lens, const int32_t* __restrict__ qo, int waves,
     int64_t desc_capacity, int32_t* __restrict__ header, int32_t* __restrict__ pt,
-    int32_t* __restrict__ ps) {
+    int32_t* __restrict__ ps, int32_t* __restrict__ lens_single) {
   __shared__ int wave_tiles[kScanThreads / kWave], wave_steps[kScanThreads / kWave];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
   const int S = p.S;
@@ -432,6 +432,9 @@ __global__ __launch_bounds__(kScanThreads) void mq_scan_kernel(
     const int nt = (n + tq - 1) / tq;
     for (int tau = 0; tau < nt; ++tau) bs_ += steps_of(tile_ctx(L, n, tq, tau));
     bt_ += nt;
+    // mixed batch: the lengths as the decode kernels see them (streams with exactly one new
+    // token keep theirs, all others become padded slots)
+    if (lens_single) lens_single[s] = (qo[s + 1] - qo[s] == 1) ? L : 0;
   }
   if (tid == kScanThreads - 1) {
     pt[S] = bt_;
@@ -712,23 +715,7 @@ __global__ __launch_bounds__(256) void kv_append_multi_kernel(
   }
 }
 
-// Context lengths as the decode kernels of a mixed batch see them: streams with exactly one
-// new token keep theirs, all others become padded slots.
-__global__ __launch_bounds__(256) void single_token_lens_kernel(
-    int S, const int32_t* __restrict__ lens, const int32_t* __restrict__ qo,
-    int32_t* __restrict__ lens_single) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s < S) lens_single[s] = (qo[s + 1] - qo[s] == 1) ? lens[s] : 0;
-}
-
 }  // namespace
-
-hipError_t launch_single_token_lens(int S, const int32_t* lens, const int32_t* qo,
-                                    int32_t* lens_single, hipStream_t st) {
-  hipLaunchKernelGGL(single_token_lens_kernel, dim3((unsigned)((S + 255) / 256)), dim3(256), 0, st,
-                     S, lens, qo, lens_single);
-  return hipGetLastError();
-}
 
 // Workspace map of the multi-token step (byte offsets), for `tiles` tiles at most, `slots`
 // partial records, `desc_capacity` step descriptors and `waves` ranges.
@@ -807,7 +794,7 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
                           const void* q, const void* k_pool, const void* v_pool,
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
                           float* lse, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after,
-                          int phases, int64_t tile_streams) {
+                          int phases, int64_t tile_streams, int32_t* lens_single) {
   const int tq = (kCols / p.G) * ncg;  // query tokens per tile
   // most of the work re-reads contexts (several tiles per stream): keep K/V in the caches
   const bool reuse = tiles >= 4 * (tile_streams > 0 ? tile_streams : (int64_t)p.S);
@@ -828,7 +815,7 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
 
   if (phases & kPrefillPlan)
     hipLaunchKernelGGL(mq_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, p, tq, lens, qo, waves,
-                       desc_capacity, header, pt, ps);
+                       desc_capacity, header, pt, ps, lens_single);
   if (tiles > 0 && (phases & kPrefillPlan)) {
     hipLaunchKernelGGL(mq_tiles_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, st,
                        p, tq, lens, qo, pt, ps, tile_first, tile_steps, tile_info);
