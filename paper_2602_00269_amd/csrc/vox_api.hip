@@ -551,8 +551,9 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
     if (int rc = enqueue_plan(pd, plan, dws, block_tables, lens_single, st)) return rc;
     const WsPtrs w = ws_ptrs(plan, dws);
     // the events enclose both attention kernels
+    hipEvent_t after_decode = tiles > 0 ? nullptr : (hipEvent_t)event_after;
     if (int rc = enqueue_attention(shape, pd, plan, w, q, k_pool, v_pool, st,
-                                   (hipEvent_t)event_before, tiles > 0 ? nullptr : (hipEvent_t)event_after))
+                                   (hipEvent_t)event_before, after_decode))
       return rc;
     if (launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool, block_tables,
                        context_lens, q_offsets, out, lse, st, nullptr, (hipEvent_t)event_after,
