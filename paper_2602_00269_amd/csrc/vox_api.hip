@@ -504,12 +504,14 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
     }
     const int ncg = prefill_column_groups(p, (int)(max_new < INT32_MAX ? max_new : INT32_MAX));
     const int tq = (16 / p.G) * ncg;
-    int64_t tiles = 0, steps = 0;
+    int64_t tiles = 0, steps = 0, max_tile_steps = 1;
     for (int s = 0; s < p.S; ++s) {
       const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
       if (mixed && n == 1) continue;
       const int64_t L = context_lens_host[s];
       const int64_t nt = (n + tq - 1) / tq;
+      if (n > 0 && (L + kStepTokens - 1) / kStepTokens * p.Hkv > max_tile_steps)
+        max_tile_steps = (L + kStepTokens - 1) / kStepTokens * p.Hkv;
       for (int64_t tau = 0; tau < nt; ++tau) {
         const int64_t ctx = L - n + (n < (tau + 1) * tq ? n : (tau + 1) * tq);
         steps += (ctx + kStepTokens - 1) / kStepTokens;
@@ -524,7 +526,8 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
       if (m.total > workspace_bytes) return VOX_ERR_WORKSPACE;
       return launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool,
                             block_tables, context_lens, q_offsets, out, lse, st,
-                            (hipEvent_t)event_before, (hipEvent_t)event_after) == hipSuccess
+                            (hipEvent_t)event_before, (hipEvent_t)event_after,
+                            kPrefillPlan | kPrefillRun, 0, nullptr, max_tile_steps) == hipSuccess
                  ? VOX_OK
                  : VOX_ERR_HIP;
     }
@@ -546,7 +549,7 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
     // the multi-token plan's first kernel also writes the masked lengths
     if (launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool, block_tables,
                        context_lens, q_offsets, out, lse, st, nullptr, nullptr, kPrefillPlan,
-                       tile_streams, lens_single) != hipSuccess)
+                       tile_streams, lens_single, max_tile_steps) != hipSuccess)
       return VOX_ERR_HIP;
     if (int rc = enqueue_plan(pd, plan, dws, block_tables, lens_single, st)) return rc;
     const WsPtrs w = ws_ptrs(plan, dws);
@@ -557,7 +560,7 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
       return rc;
     if (launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool, block_tables,
                        context_lens, q_offsets, out, lse, st, nullptr, (hipEvent_t)event_after,
-                       kPrefillRun, tile_streams) != hipSuccess)
+                       kPrefillRun, tile_streams, nullptr, max_tile_steps) != hipSuccess)
       return VOX_ERR_HIP;
     return launch_merge(pd, w.header, w.step_prefix, w.pml, w.pacc, out, lse, st) == hipSuccess
                ? VOX_OK

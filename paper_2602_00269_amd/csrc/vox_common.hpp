@@ -217,13 +217,15 @@ hipError_t launch_kv_append_multi(const Params& p, int total_q, const void* k_ne
                                   hipStream_t st);
 // launch_prefill does the plan kernels, the attention and merge kernels, or both
 constexpr int kPrefillPlan = 1, kPrefillRun = 2;
+// tile_streams: streams that have tiles (0: all); lens_single: where the plan leaves the masked
+// lengths of a mixed batch (or null); max_tile_steps: most steps of any tile, all kv heads
 hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, int ncg,
                           int64_t tiles, int64_t steps, int64_t desc_capacity, int waves,
                           const void* q, const void* k_pool, const void* v_pool,
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
                           float* lse, hipStream_t st, hipEvent_t ev_before,
-                          hipEvent_t ev_after, int phases = kPrefillPlan | kPrefillRun,
-                          int64_t tile_streams = 0, int32_t* lens_single = nullptr);
+                          hipEvent_t ev_after, int phases, int64_t tile_streams,
+                          int32_t* lens_single, int64_t max_tile_steps);
 hipError_t launch_decode_mfma(const Params& p, int waves, const void* q, const void* k_pool,
                               const void* v_pool, const int32_t* header, const int4* desc,
                               float2* partial_ml, float* partial_acc, hipStream_t st);

@@ -376,7 +376,7 @@ struct MqMath {
 //   scan:   per stream tiles_s = ceil(n_s / TQ) and steps_s = sum over its tiles of
 //           ceil(ctx_tile / 32); exclusive scans PT (tiles) and PS (steps, per kv head).
 //   tiles:  per tile its first global step, step count, TileInfo and the row -> tile map.
-//   expand: per global step its descriptor (binary search over the tiles' first steps).
+//   expand: per tile the descriptors of its steps.
 // New tokens of stream s as the plan sees them: in a mixed batch the streams that bring exactly
 // one token are left to the decode kernels.
 __device__ inline int planned_tokens(const Params& p, const int32_t* __restrict__ qo, int s) {
@@ -525,68 +525,83 @@ __global__ __launch_bounds__(256) void mq_ranges_kernel(
   ranges[w] = (int)min((int64_t)N, first + min(steps, max((int64_t)0, into)));
 }
 
-// Largest w with ranges[w] <= x: the wave that owns step x (empty ranges share their start
-// with the next one, so the last of equal starts is the owner).
-__device__ inline int owner_wave(const int32_t* ranges, int waves, int64_t x) {
-  int a = 0, b = waves;
-  while (b - a > 1) {
-    const int mid = (a + b) >> 1;
+// The wave that owns step x is the largest w with ranges[w] <= x (empty ranges share their
+// start with the next one, so the last of equal starts is the owner).
+// Largest w in [lo, hi] with ranges[w] <= x, given ranges[lo] <= x.
+__device__ inline int owner_between(const int32_t* ranges, int lo, int hi, int64_t x) {
+  while (hi > lo) {
+    const int mid = (lo + hi + 1) >> 1;
     if (ranges[mid] <= x)
-      a = mid;
+      lo = mid;
     else
-      b = mid;
+      hi = mid - 1;
   }
-  return a;
+  return lo;
 }
 
+// Workgroup (t, y) writes the descriptors of steps 256 y .. 256 y + 255 of tile t (all its kv
+// heads, laid end to end): what a step needs of its tile is read once, and the owners of the
+// tile's first and last step, found by each wave with 64 probes per round trip, bound every
+// step's own search to the few ranges the tile spans.
 __global__ __launch_bounds__(256) void mq_expand_kernel(
     Params p, const int32_t* __restrict__ bt, const int32_t* __restrict__ header,
-    const int32_t* __restrict__ pt, const int32_t* __restrict__ tile_first,
-    const int32_t* __restrict__ tile_steps, const TileInfo* __restrict__ tile_info,
-    const int32_t* __restrict__ ranges, int waves, MqDesc* __restrict__ desc,
-    SplitSegment* __restrict__ split) {
-  const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int32_t* __restrict__ tile_first, const int32_t* __restrict__ tile_steps,
+    const TileInfo* __restrict__ tile_info, const int32_t* __restrict__ ranges, int waves,
+    MqDesc* __restrict__ desc, SplitSegment* __restrict__ split) {
+  const int t = blockIdx.x, lane = threadIdx.x & (kWave - 1);
   const int N = header[kHdrSteps];
-  if (x >= N) return;
-  int a = 0, b = pt[p.S];  // largest t with tile_first[t] <= x
-  while (b - a > 1) {
-    const int mid = (a + b) >> 1;
-    if (tile_first[mid] <= x)
-      a = mid;
-    else
-      b = mid;
-  }
-  const int t = a, f = tile_steps[t];
-  const int r = (int)(x - tile_first[t]);
-  const int h = r / f, st = r - h * f;
+  const int f = tile_steps[t];
+  const int64_t x0 = tile_first[t];
+  const int total = (int)min((int64_t)f * p.Hkv, (int64_t)N - x0);  // steps with a descriptor
+  if ((int)(blockIdx.y * blockDim.x) >= total) return;
   const TileInfo info = tile_info[t];
+  // owners of the tile's first and last step: both searches advance together
+  const int64_t x_last = x0 + total - 1;
+  int a0 = 0, b0 = waves, a1 = 0, b1 = waves;
+  while (b0 - a0 > 1 || b1 - a1 > 1) {
+    const int s0 = (b0 - a0 + kWave - 1) / kWave, s1 = (b1 - a1 + kWave - 1) / kWave;
+    const int i0 = a0 + lane * s0, i1 = a1 + lane * s1;
+    const bool le0 = i0 < b0 && ranges[i0] <= x0, le1 = i1 < b1 && ranges[i1] <= x_last;
+    const int h0 = __builtin_popcountll(__builtin_amdgcn_ballot_w64(le0));  // lane 0 always hits
+    const int h1 = __builtin_popcountll(__builtin_amdgcn_ballot_w64(le1));
+    a0 += (h0 - 1) * s0;
+    b0 = min(b0, a0 + s0);
+    a1 += (h1 - 1) * s1;
+    b1 = min(b1, a1 + s1);
+  }
+  const int w_first = a0, w_last = a1;
   const int ctx = info.pos0 + info.nq;
   const int nb = (ctx + kBlock - 1) / kBlock;
   const int32_t* row = bt + (size_t)info.stream * p.max_nb;
-  const int ida = row[2 * st];
-  const int idb = (2 * st + 1 < nb) ? row[2 * st + 1] : ida;
-  int meta = min(kStepTokens, ctx - kStepTokens * st);
-  const int w = owner_wave(ranges, waves, x);
-  if (st == 0 || x == ranges[w]) meta |= kMetaFirst;
-  if (st == f - 1 || x == ranges[w + 1] - 1) meta |= kMetaLast;
-  // the segment's last step in the range that also holds its first: one run, no partial record
-  if (st == f - 1 && x - st >= ranges[w]) meta |= kMetaWhole;
-  MqDesc d;
-  d.a = make_int4(ida * p.Hkv + h, idb * p.Hkv + h, meta, t * p.Hkv + h);
-  d.b = make_int4(info.q_row0, info.nq, info.pos0 + 1 - kStepTokens * st, h);
-  desc[x] = d;
-  if (st == 0) {  // the segment's runs: waves w .. owner of its last step, slots w + sigma ..
-    const int w1 = owner_wave(ranges, waves, min((int64_t)N, x + f) - 1);
-    // a segment cut into several runs is the last one that starts in range w: entry w
-    if (w1 > w) {
-      SplitSegment e;
-      e.slot0 = w + t * p.Hkv + h;
-      e.nruns = w1 - w + 1;
-      e.q_row0 = info.q_row0;
-      e.nq = info.nq;
-      e.h = h;
-      e.pad0 = e.pad1 = e.pad2 = 0;
-      split[w] = e;
+  const int i = blockIdx.y * blockDim.x + threadIdx.x;
+  if (i < total) {
+    const int64_t x = x0 + i;
+    const int h = i / f, st = i - h * f;
+    const int ida = row[2 * st];
+    const int idb = (2 * st + 1 < nb) ? row[2 * st + 1] : ida;
+    int meta = min(kStepTokens, ctx - kStepTokens * st);
+    const int w = owner_between(ranges, w_first, w_last, x);
+    if (st == 0 || x == ranges[w]) meta |= kMetaFirst;
+    if (st == f - 1 || x == ranges[w + 1] - 1) meta |= kMetaLast;
+    // the segment's last step in the range that also holds its first: one run, no partial record
+    if (st == f - 1 && x - st >= ranges[w]) meta |= kMetaWhole;
+    MqDesc d;
+    d.a = make_int4(ida * p.Hkv + h, idb * p.Hkv + h, meta, t * p.Hkv + h);
+    d.b = make_int4(info.q_row0, info.nq, info.pos0 + 1 - kStepTokens * st, h);
+    desc[x] = d;
+    if (st == 0) {  // the segment's runs: waves w .. owner of its last step, slots w + sigma ..
+      const int w1 = owner_between(ranges, w, w_last, min((int64_t)N, x + f) - 1);
+      // a segment cut into several runs is the last one that starts in range w: entry w
+      if (w1 > w) {
+        SplitSegment e;
+        e.slot0 = w + t * p.Hkv + h;
+        e.nruns = w1 - w + 1;
+        e.q_row0 = info.q_row0;
+        e.nq = info.nq;
+        e.h = h;
+        e.pad0 = e.pad1 = e.pad2 = 0;
+        split[w] = e;
+      }
     }
   }
 }
@@ -794,7 +809,8 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
                           const void* q, const void* k_pool, const void* v_pool,
                           const int32_t* bt, const int32_t* lens, const int32_t* qo, float* out,
                           float* lse, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after,
-                          int phases, int64_t tile_streams, int32_t* lens_single) {
+                          int phases, int64_t tile_streams, int32_t* lens_single,
+                          int64_t max_tile_steps) {
   const int tq = (kCols / p.G) * ncg;  // query tokens per tile
   // most of the work re-reads contexts (several tiles per stream): keep K/V in the caches
   const bool reuse = tiles >= 4 * (tile_streams > 0 ? tile_streams : (int64_t)p.S);
@@ -821,9 +837,9 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
                        p, tq, lens, qo, pt, ps, tile_first, tile_steps, tile_info);
     hipLaunchKernelGGL(mq_ranges_kernel, dim3((unsigned)((waves + kWavesPerGroup) / 256 + 1)), dim3(256), 0,
                        st, p, waves, run_cost, header, pt, tile_first, tile_steps, ranges, split);
-    hipLaunchKernelGGL(mq_expand_kernel, dim3((unsigned)((steps + 255) / 256)), dim3(256), 0, st,
-                       p, bt, header, pt, tile_first, tile_steps, tile_info, ranges, waves, desc,
-                       split);
+    const dim3 eg((unsigned)tiles, (unsigned)((max_tile_steps + 255) / 256));
+    hipLaunchKernelGGL(mq_expand_kernel, eg, dim3(256), 0, st, p, bt, header, tile_first,
+                       tile_steps, tile_info, ranges, waves, desc, split);
   }
   if (tiles > 0 && (phases & kPrefillRun)) {
     const unsigned grid = (unsigned)((waves + kWavesPerGroup - 1) / kWavesPerGroup);
