@@ -33,8 +33,8 @@ METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 # in profiles/*_<workload>*.txt.  Workloads without a counter run report null.
 MEASURED_TRAFFIC = {
     "cfg3": 2356073726, "cfg4": 2730018149, "cfg5": 1103168749,
-    "chunk15": 2444163013, "chunk25": 2568399055, "chunk28": 2414360087, "admit": 2963864445,
-    "prefill": 468522237, "sample_small": 27864508, "sample_large": 321869659,
+    "chunk15": 2444131382, "chunk25": 2568475473, "chunk28": 2414401398, "admit": 2964099176,
+    "prefill": 468233930, "sample_small": 27864508, "sample_large": 321869659,
 }
 
 
