@@ -699,36 +699,49 @@ __global__ __launch_bounds__(256) void kv_append_multi_kernel(
           *reinterpret_cast<const u32x4*>(krow + h * D + d);
   }
   // V keeps four tokens of a dim together.  The row at the start of a quad whose other three
-  // tokens are new as well writes the whole quad, 16 bytes (two dims) per lane, from the four
-  // rows; the other three rows of such a quad skip V.  Quads that also hold older tokens, or
-  // end past the stream's last token, are written one 2-byte element at a time, so bytes of
-  // tokens that are not being appended are never touched.  D/2 lanes per head either way.
+  // tokens are new as well writes the whole quad from the four rows; the other three rows of
+  // such a quad skip V.  Quads that also hold older tokens, or end past the stream's last
+  // token, are written one 2-byte element at a time (D/2 lanes per head, two dims each), so
+  // bytes of tokens that are not being appended are never touched.
   const int j = row - qo[s];             // index among the stream's new tokens
   const int q0 = j - (t & 3);            // index of the quad's first token (may be < 0)
   const bool full_quad = q0 >= 0 && q0 + 3 < n;
   if (full_quad && (t & 3) != 0) return;
-  constexpr int kLanesV = D / 2, kHeadsV = kWave / kLanesV;
   const size_t stride = (size_t)p.Hkv * D;  // next new row of the same kv head
+  if (full_quad) {
+    // four rows x eight dims per lane in, the same 64 bytes transposed out (dim-major, the
+    // quad's four tokens of a dim together): D/8 lanes per head, as for K
+    for (int h0 = 0; h0 < p.Hkv; h0 += kHeadsK) {
+      const int h = h0 + lane / kLanesK, d = (lane % kLanesK) * 8;
+      if (h >= p.Hkv) continue;
+      const uint16_t* src = vrow + h * D + d;
+      u32x4 x[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) x[k] = *reinterpret_cast<const u32x4*>(src + k * stride);
+      u32x4* dst = reinterpret_cast<u32x4*>(v_pool + granule_offset(blk, h, p.Hkv, D) +
+                                            v_elem(t, d, D));
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {  // word w of a row holds dims 2w and 2w + 1
+        // low halves of tokens (0, 1) and (2, 3), then the high halves
+        dst[w] = u32x4{__builtin_amdgcn_perm(x[1][w], x[0][w], 0x05040100u),
+                       __builtin_amdgcn_perm(x[3][w], x[2][w], 0x05040100u),
+                       __builtin_amdgcn_perm(x[1][w], x[0][w], 0x07060302u),
+                       __builtin_amdgcn_perm(x[3][w], x[2][w], 0x07060302u)};
+      }
+    }
+    return;
+  }
+  constexpr int kLanesV = D / 2, kHeadsV = kWave / kLanesV;
   for (int h0 = 0; h0 < p.Hkv; h0 += kHeadsV) {
     const int h = h0 + lane / kLanesV, d = (lane % kLanesV) * 2;
     if (h >= p.Hkv) continue;
-    const uint16_t* src = vrow + h * D + d;
+    const uint32_t two = *reinterpret_cast<const uint32_t*>(vrow + h * D + d);
     uint16_t* dst = v_pool + granule_offset(blk, h, p.Hkv, D);
-    if (full_quad) {
-      uint32_t x[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) x[k] = *reinterpret_cast<const uint32_t*>(src + k * stride);
-      // dims d and d + 1, tokens t..t+3 each: eight consecutive elements
-      const u32x4 out = {(x[0] & 0xFFFFu) | (x[1] << 16), (x[2] & 0xFFFFu) | (x[3] << 16),
-                         (x[0] >> 16) | (x[1] & 0xFFFF0000u), (x[2] >> 16) | (x[3] & 0xFFFF0000u)};
-      *reinterpret_cast<u32x4*>(dst + v_elem(t, d, D)) = out;
-    } else {
-      const uint32_t two = *reinterpret_cast<const uint32_t*>(src);
-      dst[v_elem(t, d, D)] = (uint16_t)(two & 0xFFFFu);
-      dst[v_elem(t, d + 1, D)] = (uint16_t)(two >> 16);
-    }
+    dst[v_elem(t, d, D)] = (uint16_t)(two & 0xFFFFu);
+    dst[v_elem(t, d + 1, D)] = (uint16_t)(two >> 16);
   }
 }
+
 
 }  // namespace
 
