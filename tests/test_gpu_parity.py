@@ -619,6 +619,38 @@ def test_mixed_batches_of_decode_streams_and_prompts(dev, hq, hkv, d, singles):
         _assert_lse(lse.cpu().numpy(), ref_lse, f"mixed batch waves {waves}")
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_random_mixed_batches(dev, seed):
+    # many single-token streams of random lengths among prompts, chunks and empty slots; whether
+    # a batch is split depends on its lengths, so both ways of computing it are drawn
+    rng = np.random.default_rng(5000 + seed)
+    hq, hkv, d = [(24, 8, 128), (14, 2, 64), (8, 1, 128), (8, 8, 64), (12, 2, 128)][seed % 5]
+    S = int(rng.integers(33, 200))
+    kind = rng.random(S)
+    nq = np.where(kind < 0.7, 1, np.where(kind < 0.8, 0, rng.integers(2, 70, size=S)))
+    longest = 1200 + 1200 * (seed % 4) ** 2
+    lens = nq + np.where(rng.random(S) < 0.2, 0, rng.integers(0, longest, size=S))
+    lens = np.where((nq == 0) & (rng.random(S) < 0.5), 0, lens)
+    w, qo, q, k_new, v_new = _prefill_case(dev, lens, nq, hq, hkv, d, seed=600 + seed)
+    sh = binding.shape_of(w, split_waves=int(rng.choice([0, 0, 16, 300])))
+    bt, lens_d, qo_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev), _i32(qo, dev)
+    tq = int(qo[-1])
+    binding.kv_append_multi(sh, k_new, v_new, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d)
+    torch.cuda.synchronize()
+    kp, vp = _host_pools(w)
+    ref, ref_lse = oracle.paged_prefill(bits_of(q), kp, vp, w.block_tables, w.context_lens, qo,
+                                        w.scale, num_kv_heads=hkv)
+    out = torch.full((tq, hq, d), float("nan"), device=dev)
+    lse = torch.full((tq, hq), float("nan"), device=dev)
+    ws = torch.empty(binding.paged_prefill_workspace_bytes(sh, tq), dtype=torch.uint8, device=dev)
+    ws.fill_(0xFF)
+    binding.paged_prefill(sh, q, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d, w.context_lens, qo,
+                          out, ws, lse=lse)
+    torch.cuda.synchronize()
+    _assert_close(out.cpu().numpy(), ref, f"random mixed batch {seed}")
+    _assert_lse(lse.cpu().numpy(), ref_lse, f"random mixed batch {seed}")
+
+
 def test_prefill_with_one_token_per_stream_equals_decode(dev):
     lens = [33, 700, 64, 1, 255]
     w, qo, q, _, _ = _prefill_case(dev, lens, [1] * 5, 24, 8, 128, seed=90)
