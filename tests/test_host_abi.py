@@ -125,6 +125,9 @@ def test_multi_token_calls_validate_on_the_host(lib):
                                  None, one, 64, None) == -3
     assert lib.vox_paged_prefill_workspace_bytes(ctypes.byref(sh), 5) > 0
     assert lib.vox_paged_prefill_workspace_bytes(ctypes.byref(sh), -1) == 0
+    # it has room for the decode kernels' workspace too (mixed batches use both)
+    assert (lib.vox_paged_prefill_workspace_bytes(ctypes.byref(sh), 5) >
+            lib.vox_paged_decode_workspace_bytes(ctypes.byref(sh)))
 
 
 def test_rope_calls_validate_on_the_host(lib):
