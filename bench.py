@@ -496,7 +496,7 @@ def main() -> int:
                    2 * (waves + s_ * hkv_) * (hq_ // hkv_) * (d_ + 2) * 4)
     roofline = {
         "bound": "hbm",
-        "kernel": "decode_valu_kernel" if path == binding.PATH_VALU else "decode_mfma_kernel",
+        "kernel": "decode_kernel<ValuMath>" if path == binding.PATH_VALU else "decode_kernel<MfmaMath>",
         "achieved": round(achieved, 1),
         "peak": HBM_PEAK_GBPS,
         "unit": "GB/s",
