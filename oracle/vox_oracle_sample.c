@@ -34,7 +34,8 @@
  * Pins (tests/test_oracle_sample_pins.py): w(d) against exp(-d) to 4e-7 relative; the
  * distribution of draws over a grid of u against the softmax probabilities; top-k / top-p sets
  * against a numpy fp64 evaluation on inputs with clear margins; greedy = argmax; penalty and
- * tie rules on hand-made cases.
+ * tie rules on hand-made cases; the rows of vox_oracle_sample_weights against a numpy fp32
+ * evaluation of d bit for bit, against exp, and against the prefixes vox_oracle_sample keeps.
  */
 #include <math.h>
 #include <stdint.h>

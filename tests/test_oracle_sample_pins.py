@@ -111,3 +111,83 @@ def test_bad_arguments():
     z = np.zeros((1, 4), dtype=np.float32)
     with pytest.raises(ValueError):
         oracle.sample(z, _params(n=2), [0.5])
+
+
+def test_sample_weights_rows_follow_the_stated_arithmetic():
+    # d and w of every token, recomputed here in numpy with the same single fp32 operations
+    # (penalty on the window's tokens, one division for 1/T, one product, max, one difference):
+    # a wrong sign of d, a penalty applied the wrong way round, to the wrong tokens or twice, or
+    # a temperature that is divided instead of multiplied by its inverse changes bits of d.
+    rng = np.random.default_rng(11)
+    s, v, window = 5, 777, 40
+    z = (rng.standard_normal((s, v)) * 3.0).astype(np.float32)
+    hist = rng.integers(-3, v + 3, size=(s, window)).astype(np.int32)  # some ids out of range
+    hist[:, 5] = hist[:, 4]  # a token that occurs twice is penalised once
+    temps = np.float32([0.8, 0.6, 1.0, 0.0, 2.5])  # stream 3 is greedy: y = z'
+    pens = np.float32([1.1, 1.3, 1.0, 1.05, 2.0])
+    for r in np.unique(pens):
+        prm = oracle.sampling_params(temps, 1.0, np.float32(r), 0, s)
+        d, w = oracle.sample_weights(z, prm, history=hist)
+        for i in range(s):
+            seen = np.zeros(v, dtype=bool)
+            ids = hist[i][(hist[i] >= 0) & (hist[i] < v)]
+            seen[ids] = True
+            zp = z[i].copy()
+            pos = seen & (zp > 0)
+            neg = seen & ~(zp > 0)
+            zp[pos] = zp[pos] / np.float32(r)
+            zp[neg] = zp[neg] * np.float32(r)
+            inv_t = np.float32(1.0) / temps[i] if temps[i] > 0 else np.float32(1.0)
+            y = (zp * inv_t).astype(np.float32)
+            want = (y.max() - y).astype(np.float32)
+            assert want.dtype == np.float32
+            assert np.array_equal(d[i].view(np.uint32), want.view(np.uint32)), (r, i)
+            assert (d[i] >= 0).all() and d[i][int(np.argmax(y))] == 0
+            # the weight of each token is the scalar weight function of its own distance
+            # (pinned to exp above), and stays within that function's error of 2^40 exp(-d)
+            assert all(int(w[i, t]) == oracle.sample_weight(float(d[i, t])) for t in range(0, v, 7))
+            exact = 2.0 ** 40 * np.exp(-d[i].astype(np.float64))
+            assert np.all(np.abs(w[i].astype(np.float64) - exact)
+                          <= exact * (3e-7 + 1e-7 * d[i]) + 1.0)
+            assert int(w[i].max()) == 1 << 40
+    # without a window nothing is penalised, whatever the penalty says
+    prm = oracle.sampling_params(0.7, 1.0, 1.3, 0, s)
+    d0, _ = oracle.sample_weights(z, prm)
+    y = (z * (np.float32(1.0) / np.float32(0.7))).astype(np.float32)
+    assert np.array_equal(d0, (y.max(axis=1, keepdims=True) - y).astype(np.float32))
+
+
+def test_sample_weights_add_up_to_what_the_sampler_keeps():
+    # the kept count of a top-p draw is the shortest prefix, in the order (d, id), of exactly
+    # these integer weights that reaches trunc(top_p * total): the rows of sample_weights and the
+    # totals inside sample are the same numbers
+    rng = np.random.default_rng(12)
+    s, v = 6, 500
+    z = (rng.standard_normal((s, v)) * 2.0).astype(np.float32)
+    hist = rng.integers(0, v, size=(s, 16)).astype(np.int32)
+    for top_p, k in ((0.9, 0), (0.5, 0), (0.95, 50)):
+        prm = oracle.sampling_params(0.8, np.float32(top_p), 1.1, k, s)
+        d, w = oracle.sample_weights(z, prm, history=hist)
+        u = rng.random(s).astype(np.float32)
+        toks, kept = oracle.sample(z, prm, u, history=hist)
+        for i in range(s):
+            order = np.lexsort((np.arange(v), d[i].view(np.uint32)))
+            n = v if k == 0 else k
+            ws = [int(x) for x in w[i][order[:n]]]
+            total = sum(ws)
+            thr = max(1, int(float(np.float32(top_p)) * float(total)))
+            cum, size = 0, 0
+            while size < n:
+                cum += ws[size]
+                size += 1
+                if cum >= thr:
+                    break
+            assert kept[i] == size, (top_p, k, i)
+            target = int(float(u[i]) * float(cum))
+            run, pick = 0, size - 1
+            for j in range(size):
+                run += ws[j]
+                if run > target:
+                    pick = j
+                    break
+            assert toks[i] == order[pick], (top_p, k, i)
