@@ -130,10 +130,22 @@ size_t vox_paged_decode_workspace_bytes(const vox_shape_t* shape);
  * where K(s,h,t,d) / V(...) are read through block_tables.  Streams with
  * L_s == 0 get out = 0 and lse = -inf.  Inputs are bf16, accumulation fp32.
  *   q                 : [S][Hq][D] bf16
- *   context_lens_host : HOST copy of context_lens or NULL.  When given, the
- *                       planning launch and the workspace check are sized
- *                       from it; it must equal the device array.  The
- *                       attention launch itself never depends on lengths.
+ *   context_lens_host : HOST copy of context_lens or NULL.  When given it must
+ *                       equal the device array: the workspace check, the
+ *                       planning grid, the number of attention waves that get
+ *                       a range and the layout of the step axis the kernels
+ *                       work from are then taken from it (this saves every
+ *                       wave a dependent load).  With NULL all of that comes
+ *                       from the device array and the shape's bounds, and no
+ *                       launch depends on the lengths.
+ *                       Graph capture: a captured call is replayed when the
+ *                       device lengths may have changed, so while hip_stream
+ *                       is being captured the host copy is IGNORED (treated
+ *                       as NULL; the workspace must then have the full size
+ *                       of vox_paged_decode_workspace_bytes).  A replay reads
+ *                       context_lens and block_tables afresh and is correct
+ *                       for any lengths the shape admits.  The same holds for
+ *                       vox_decode_step and vox_decode_step_rope.
  *   out               : [S][Hq][D] fp32
  *   lse               : [S][Hq] fp32 or NULL
  * Split-K: the 32-token steps of all (stream, kv head) pairs are laid on one
@@ -233,12 +245,14 @@ int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const voi
  *   q_offsets         : int32 [S+1] device, q_offsets[0] == 0
  *   context_lens_host, q_offsets_host : HOST copies, both required (the scheduler that admits
  *                       a prompt knows its length); sizes of the launches come from them
+ *                       (a captured vox_paged_prefill therefore replays correctly only
+ *                       while the device arrays still hold these values)
  * With no query rows at all (total_q == 0) both calls return VOX_OK and touch nothing.
  * vox_paged_prefill_workspace_bytes(shape, total_q) is enough for any lengths the shape
  * admits; a smaller workspace is accepted when the actual step count fits.
  * A batch may mix decoding streams (n_s = 1) with prompts and chunks, as during admission
  * (Section 3.2.1): when many streams bring exactly one token (32 or more, with 32 768 or more
- * 32-token steps per kv head between them) those are computed by the kernels of
+ * 32-token steps between them, counted over all kv heads) those are computed by the kernels of
  * vox_paged_decode and the others by the multi-token kernels, in the same call and with the
  * same results; the workspace size above has room for both (with a smaller workspace every
  * stream takes the multi-token kernels).

@@ -97,6 +97,21 @@ Workspace map_workspace(const vox_shape_t* s, int64_t desc_capacity) {
   return w;
 }
 
+// A captured call is replayed later, when the device lengths may have moved on (every decode
+// step adds a token, and crossing a 32-token boundary changes the step count): nothing of the
+// recorded launches may then depend on the host copy of the lengths.  While the stream is being
+// captured the host copy is therefore ignored and the call behaves as if it were NULL: the
+// kernels read the layout of the step axis from the plan's header, grids cover the shape's bound.
+const int32_t* lens_for_planning(const int32_t* lens_host, hipStream_t st) {
+  if (!lens_host) return nullptr;
+  hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &status) != hipSuccess) {
+    (void)hipGetLastError();  // e.g. the legacy default stream while another stream captures
+    return nullptr;
+  }
+  return status == hipStreamCaptureStatusNone ? lens_host : nullptr;
+}
+
 struct Plan {
   int waves;
   int64_t desc_capacity;  // descriptors the workspace has room for
@@ -274,14 +289,15 @@ int vox_paged_decode_profiled(const vox_shape_t* shape, const void* q, const voi
   if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out || !workspace)
     return VOX_ERR_NULL;
   if ((uintptr_t)workspace % 256 || !all_aligned16(q, k_pool, v_pool, out)) return VOX_ERR_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
   Plan plan;
-  if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
+  if (int rc = make_plan(shape, lens_for_planning(context_lens_host, st), workspace_bytes, &plan))
+    return rc;
   Params p = make_params(shape);
   char* ws = (char*)workspace;
   p.pool_counter = pool_counter(plan, ws, 0);
   set_step_hints(&p, plan);
   p.wave_clock = (unsigned long long*)wave_clock;
-  hipStream_t st = (hipStream_t)hip_stream;
   if (int rc = enqueue_plan(p, plan, ws, block_tables, context_lens, st)) return rc;
   const WsPtrs w = ws_ptrs(plan, ws);
   if (int rc = enqueue_attention(shape, p, plan, w, q, k_pool, v_pool, st,
@@ -308,13 +324,14 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
   if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
   for (int l = 0; l < num_layers; ++l)
     if (!all_aligned16(q[l], k_new[l], v_new[l], k_pool[l], v_pool[l], out[l])) return VOX_ERR_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
   Plan plan;
-  if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
+  if (int rc = make_plan(shape, lens_for_planning(context_lens_host, st), workspace_bytes, &plan))
+    return rc;
   Params p = make_params(shape);
   char* ws = (char*)workspace;
   p.pool_counter = pool_counter(plan, ws, 0);  // the plan zeroes every layer's counter
   set_step_hints(&p, plan);
-  hipStream_t st = (hipStream_t)hip_stream;
   const WsPtrs w = ws_ptrs(plan, ws);
   // Launch chain: [plan + append(0)] attention(0) [merge(0) + append(1)] attention(1) ...
   // merge(L-1).  Each bracket is one launch of two independent roles.
@@ -379,13 +396,14 @@ int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const voi
   if ((uintptr_t)workspace % 256 || !all_aligned16(rope_cos, rope_sin)) return VOX_ERR_ARG;
   for (int l = 0; l < num_layers; ++l)
     if (!all_aligned16(qkv[l], q_rot[l], k_pool[l], v_pool[l], out[l])) return VOX_ERR_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
   Plan plan;
-  if (int rc = make_plan(shape, context_lens_host, workspace_bytes, &plan)) return rc;
+  if (int rc = make_plan(shape, lens_for_planning(context_lens_host, st), workspace_bytes, &plan))
+    return rc;
   Params p = make_params(shape);
   char* ws = (char*)workspace;
   p.pool_counter = pool_counter(plan, ws, 0);  // the plan zeroes every layer's counter
   set_step_hints(&p, plan);
-  hipStream_t st = (hipStream_t)hip_stream;
   const WsPtrs w = ws_ptrs(plan, ws);
   // [plan + rope/append(0)] attention(0) [merge(0) + rope/append(1)] attention(1) ... merge(L-1)
   const auto layer = [&](int l) {

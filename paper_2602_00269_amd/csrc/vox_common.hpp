@@ -119,7 +119,7 @@ __host__ __device__ inline int64_t pool_ranges_bound(int64_t steps_bound) {
 
 // Workspace map (byte offsets from the 256-byte aligned workspace base).
 struct Workspace {
-  size_t header;       // int32[64]
+  size_t header;       // int32[kHeaderWords]: 64 header words, then one pool counter per layer
   size_t step_prefix;  // int32[S + 1]: exclusive scan of n_s
   size_t desc;         // int4[desc_capacity]
   size_t partial_ml;   // float2[slots * G]: (running max in log2 units, sum)

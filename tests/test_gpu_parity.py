@@ -273,13 +273,21 @@ def test_single_key_and_equal_scores_closed_forms(dev):
 @pytest.mark.parametrize("cfg", [3, 4])
 def test_full_size_presets_match_oracle(dev, cfg):
     w = synth.make_workload(cfg, device=dev)
-    _append_both(w, dev)
-    ref, ref_lse = _oracle_decode(w)
+    kp0, vp0, kp_ref, vp_ref = _append_both(w, dev)
+    kp, vp = _host_pools(w)
+    assert np.array_equal(kp, kp_ref) and np.array_equal(vp, vp_ref)  # every block, every bit
+    assert (kp != kp0).any() and (vp != vp0).any()
+    del kp0, vp0, kp, vp
+    # the oracle attends over the pools its own append produced
+    ref, ref_lse = oracle.paged_decode(bits_of(w.q[0]), kp_ref, vp_ref, w.block_tables,
+                                       w.context_lens, w.scale, num_kv_heads=w.num_kv_heads)
     for path in PATHS:
-        out, lse = _decode(w, dev, path=path)
-        mx, mean = _assert_close(out, ref, f"cfg{cfg} path{path}")
-        _assert_lse(lse, ref_lse, f"cfg{cfg} path{path}")
-        print(f"cfg{cfg} path{path}: max abs {mx:.2e} mean abs {mean:.2e}")
+        for host_lens in (True, False):  # layout of the step axis as an argument / from the plan
+            out, lse = _decode(w, dev, path=path, host_lens=host_lens)
+            what = f"cfg{cfg} path{path} host_lens{host_lens}"
+            mx, mean = _assert_close(out, ref, what)
+            _assert_lse(lse, ref_lse, what)
+            print(f"{what}: max abs {mx:.2e} mean abs {mean:.2e}")
 
 
 def test_multi_layer_step_matches_oracle_on_sampled_streams(dev):
@@ -346,6 +354,57 @@ def test_full_28_layer_step_at_bench_size(dev):
                                          w.context_lens, w.scale, num_kv_heads=w.num_kv_heads,
                                          streams=(s, s + 1))
             _assert_close(got[s:s + 1], ref, f"cfg5 layer{l} stream{s}")
+    del before
+    # Every layer has its own pool pointers, output pointer and pool counter: the attention of
+    # ALL 28 layers is checked on the sampled streams.  Their cache rows are exported with
+    # vox_kv_gather (bit-exact against the oracle's gather, tested above) instead of copying
+    # 1.1 GB of pools per layer to the host; the appended token must be the last exported row;
+    # the rows are packed into a small contiguous pool (test-side layout views) and the oracle
+    # attends over that.
+    hkv, d = w.num_kv_heads, w.head_dim
+    masked = np.zeros_like(w.context_lens)
+    masked[sample] = w.context_lens[sample]
+    offs = np.zeros(w.num_streams, dtype=np.int64)
+    offs[1:] = np.cumsum(masked.astype(np.int64))[:-1]
+    total = int(masked.astype(np.int64).sum())
+    masked_d, offs_d = _i32(masked, dev), torch.from_numpy(offs).to(dev)
+    k_out = torch.zeros((total, hkv, d), dtype=torch.bfloat16, device=dev)
+    v_out = torch.zeros_like(k_out)
+    sub_lens = w.context_lens[sample]
+    nb = (sub_lens.astype(np.int64) + 15) // 16
+    sub_tables = np.full((len(sample), int(nb.max())), -1, dtype=np.int32)
+    pos = 0
+    for i, n in enumerate(nb):
+        sub_tables[i, :n] = np.arange(pos, pos + n)
+        pos += int(n)
+    for l in range(w.layers):
+        binding.kv_gather(sh, w.k_pool[l], w.v_pool[l], bt, masked_d, offs_d, k_out, v_out)
+        torch.cuda.synchronize()
+        kr, vr = bits_of(k_out), bits_of(v_out)
+        k_rows = [kr[offs[s]:offs[s] + masked[s]] for s in sample]
+        v_rows = [vr[offs[s]:offs[s] + masked[s]] for s in sample]
+        kn, vn = bits_of(w.k_new[l]), bits_of(w.v_new[l])
+        for i, s in enumerate(sample):  # the step's append reached this layer's cache
+            assert np.array_equal(k_rows[i][-1], kn[s]) and np.array_equal(v_rows[i][-1], vn[s])
+        kp_s, vp_s = _pack_rows_fast(k_rows, v_rows, sub_tables, pos, hkv, d)
+        ref, _ = oracle.paged_decode(bits_of(w.q[l])[sample], kp_s, vp_s, sub_tables, sub_lens,
+                                     w.scale, num_kv_heads=hkv)
+        got = outs[l].cpu().numpy()[sample]
+        _assert_close(got, ref, f"cfg5 layer{l} (gathered rows)")
+
+
+def _pack_rows_fast(k_rows, v_rows, tables, num_blocks, hkv, d):
+    """helpers.pack_pools for long streams: whole streams at a time through the same views."""
+    kp = np.full((num_blocks, hkv, 16 * d), 0x7FC0, dtype=np.uint16)
+    vp = np.full((num_blocks, hkv, 16 * d), 0x7FC0, dtype=np.uint16)
+    kv, vv = k_view(kp, hkv, d), v_view(vp, hkv, d)
+    for s, (kr, vr) in enumerate(zip(k_rows, v_rows)):
+        t = np.arange(kr.shape[0])
+        blk = tables[s, t // 16]
+        # [L, Hkv, D] -> k view [blk, h, d // 32, t % 16, d % 32], v view [blk, h, t // 4 % 4, d, t % 4]
+        kv[blk, :, :, t % 16, :] = kr.reshape(-1, hkv, d // 32, 32)
+        vv[blk, :, (t % 16) // 4, :, t % 4] = vr
+    return kp, vp
 
 
 def test_decode_step_replays_from_a_hip_graph(dev):
@@ -394,6 +453,129 @@ def test_decode_step_replays_from_a_hip_graph(dev):
             assert torch.equal(wl.v_pool[0].view(torch.int16), eager[2].view(torch.int16))
         ref, _ = _oracle_decode(wl)
         _assert_close(out.cpu().numpy(), ref, "graph replay vs oracle")
+
+
+def _pool_range_lens(seed, streams=160):
+    # enough 32-token steps (>= 96 per wave of 1024) for the pool of short ranges to be active
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(2960, 3041, size=streams).astype(np.int32)
+    lens[0], lens[1], lens[2], lens[3] = 3007, 2992, 0, 3009  # next to 32- and 16-token edges, padded
+    assert sum(((int(L) + 15) // 16 + 1) // 2 for L in lens) * 8 >= 96 * 1024
+    return lens
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_device_lengths_only_with_pool_ranges(dev, path):
+    # without the host copy of the lengths the kernels take the layout of the step axis (static
+    # ranges and the pool of short ones) from the header the plan kernel wrote
+    w = synth.make_custom(_pool_range_lens(410), 24, 8, 128, seed=410, device=dev)
+    ref, ref_lse = _oracle_decode(w)
+    for host_lens in (False, True):
+        out, lse = _decode(w, dev, path=path, host_lens=host_lens)
+        _assert_close(out, ref, f"pool ranges path{path} host_lens{host_lens}")
+        _assert_lse(lse, ref_lse, f"pool ranges path{path} host_lens{host_lens}")
+        assert (out[2] == 0).all()
+
+
+@pytest.mark.parametrize("rope", [False, True])
+def test_captured_step_follows_the_device_lengths(dev, rope):
+    # A step captured once is replayed while the streams grow: between replays every live
+    # stream's device length goes up by one (some cross a 16-token block edge, some a 32-token
+    # step edge, so the number of steps changes), with new rows each time.  Two layers, pool
+    # ranges active (one counter per layer, zeroed by the captured plan kernel).  The host copy
+    # given at capture time describes the lengths of THAT moment and must shape nothing.  Every
+    # replay is compared with an eager call on the same inputs (same pools: appending the same
+    # token twice is idempotent) bit for bit, the last state with the oracle.
+    layers, hq, hkv, d = 2, 24, 8, 128
+    lens0 = _pool_range_lens(420)
+    grown = np.where(lens0 > 0, lens0 + 3, 0).astype(np.int32)
+    w = synth.make_custom(grown, hq, hkv, d, seed=420, device=dev)  # tables cover the growth
+    w.context_lens = lens0.copy()
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(421)
+
+    def rnd(shape):
+        return torch.randn(shape, generator=gen, device=dev).to(torch.bfloat16)
+
+    S = w.num_streams
+    k_pool = [w.k_pool[0], rnd(tuple(w.k_pool[0].shape))]
+    v_pool = [w.v_pool[0], rnd(tuple(w.v_pool[0].shape))]
+    outs = [torch.full((S, hq, d), float("nan"), device=dev) for _ in range(layers)]
+    sh = binding.shape_of(w)
+    bt, lens_d = _i32(w.block_tables, dev), _i32(lens0, dev)
+    ws = binding.alloc_workspace(sh, dev)
+    if rope:
+        cos, sin = synth.rope_tables(w.max_blocks_per_stream * 16, d)
+        cos_d, sin_d = torch.from_numpy(cos).to(dev), torch.from_numpy(sin).to(dev)
+        qkv = [rnd((S, hq + 2 * hkv, d)) for _ in range(layers)]
+        q_rot = [torch.zeros((S, hq, d), dtype=torch.bfloat16, device=dev) for _ in range(layers)]
+        args = binding.RopeStepArgs(qkv, q_rot, k_pool, v_pool, outs, cos_d, sin_d)
+        rows = qkv
+
+        def step(host):
+            binding.decode_step_rope(sh, args, bt, lens_d, ws, context_lens_host=host)
+    else:
+        q = [rnd((S, hq, d)) for _ in range(layers)]
+        k_new = [rnd((S, hkv, d)) for _ in range(layers)]
+        v_new = [rnd((S, hkv, d)) for _ in range(layers)]
+        args = binding.StepArgs(q, k_new, v_new, k_pool, v_pool, outs)
+        rows = q + k_new + v_new
+
+        def step(host):
+            binding.decode_step(sh, args, bt, lens_d, ws, context_lens_host=host)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # warm-up on the capture stream
+        step(lens0)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(lens0)  # a host copy is passed on purpose: it must be ignored under capture
+    lens = lens0.copy()
+    for rep in range(3):
+        lens = np.where(lens > 0, lens + 1, 0).astype(np.int32)
+        lens_d.copy_(torch.from_numpy(lens))
+        for t in rows:
+            t.copy_(rnd(tuple(t.shape)))
+        for o in outs:
+            o.fill_(float("nan"))
+        step(lens)  # eager, with the host copy of the current lengths
+        torch.cuda.synchronize()
+        eager = [o.clone() for o in outs]
+        pools = [(k.clone(), v.clone()) for k, v in zip(k_pool, v_pool)] if rep == 0 else None
+        for o in outs:
+            o.fill_(float("nan"))
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(layers):
+            assert torch.equal(outs[l], eager[l]), f"replay {rep} layer {l}: differs from eager"
+        if pools is not None:
+            for l in range(layers):
+                assert torch.equal(k_pool[l].view(torch.int16), pools[l][0].view(torch.int16))
+                assert torch.equal(v_pool[l].view(torch.int16), pools[l][1].view(torch.int16))
+            del pools
+    # the final state against the oracle, on sampled streams of both layers (the ones next to
+    # the edges, the padded slot and a few more)
+    for l in range(layers):
+        kp, vp = bits_of(k_pool[l]), bits_of(v_pool[l])
+        qb = bits_of(q_rot[l] if rope else q[l])
+        got = outs[l].cpu().numpy()
+        for s in (0, 1, 2, 3, 77, S - 1):
+            ref, _ = oracle.paged_decode(qb, kp, vp, w.block_tables, lens, w.scale,
+                                         num_kv_heads=hkv, streams=(s, s + 1))
+            _assert_close(got[s:s + 1], ref, f"captured step layer {l} stream {s}")
+            if lens[s] > 0:  # the last replay's token is the last row of the cache
+                kr, vr, _ = oracle.kv_gather(kp, vp, w.block_tables[s:s + 1], lens[s:s + 1],
+                                             num_kv_heads=hkv, head_dim=d)
+                if not rope:
+                    assert np.array_equal(kr[-1], bits_of(k_new[l])[s])
+                    assert np.array_equal(vr[-1], bits_of(v_new[l])[s])
+                else:
+                    assert np.array_equal(vr[-1], bits_of(qkv[l])[s, hq + hkv:])
 
 
 @pytest.mark.parametrize("path", PATHS)
