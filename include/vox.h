@@ -65,6 +65,10 @@ extern "C" {
 #define VOX_ERR_WORKSPACE (-3) /* workspace too small for the steps of this call */
 #define VOX_ERR_HIP (-4)       /* a launch failed; hipGetLastError() still holds the cause */
 #define VOX_ERR_ARG (-5)       /* a scalar argument is out of range, or a misaligned tensor */
+#define VOX_ERR_SCRATCH (-6)   /* vox_paged_decode_static: the call needs more than the built-in scratch */
+
+/* Size of the built-in scratch memory of vox_paged_decode_static (per GPU, held until the process ends). */
+#define VOX_STATIC_SCRATCH_BYTES (64u << 20)
 
 /* Which decode kernel family runs; both give results within the same tolerance. */
 #define VOX_PATH_AUTO 0 /* the library's choice (MFMA) */
@@ -158,6 +162,28 @@ int vox_paged_decode(const vox_shape_t* shape, const void* q, const void* k_pool
                      const void* v_pool, const int32_t* block_tables,
                      const int32_t* context_lens, const int32_t* context_lens_host, float* out,
                      float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * vox_paged_decode for callers that cannot provide device memory beyond inputs and outputs and
+ * must not allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, kernels and results as vox_paged_decode, without the workspace:
+ * descriptors and partial records go to a built-in device array of VOX_STATIC_SCRATCH_BYTES
+ * (64 MiB) that each GPU the library runs on holds until the process ends.  The call allocates
+ * nothing and frees nothing.  Its very first use on a device looks up that device's copy of the
+ * array (hipGetSymbolAddress; make that first call outside graph capture).
+ * Size limit: the call needs what vox_paged_decode_workspace_bytes(shape) reports (or, with
+ * context_lens_host outside capture, the smaller amount the actual 32-token steps need); when
+ * that exceeds VOX_STATIC_SCRATCH_BYTES it returns VOX_ERR_SCRATCH and launches nothing
+ * (512 streams x 8192 tokens x 8 kv heads of head_dim 128 still fit without host lengths).
+ * Every call on a GPU shares that GPU's array, which keeps the previous call's contents: the
+ * planning kernel rewrites everything a call reads (header, pool counters, descriptors, step
+ * prefix) before it is read, so nothing needs clearing between calls, but two calls whose
+ * execution overlaps on one GPU (different streams, or concurrent graph launches) race on it.
+ */
+int vox_paged_decode_static(const vox_shape_t* shape, const void* q, const void* k_pool,
+                            const void* v_pool, const int32_t* block_tables,
+                            const int32_t* context_lens, const int32_t* context_lens_host,
+                            float* out, float* lse, void* hip_stream);
 
 /*
  * Measurement aid: vox_paged_decode that also records two caller-created hipEvent_t on

@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.vox_paged_decode.restype = ctypes.c_int
     lib.vox_paged_decode_profiled.argtypes = [sp] + [vp] * 9 + [ctypes.c_size_t, vp, vp, vp, vp]
     lib.vox_paged_decode_profiled.restype = ctypes.c_int
+    lib.vox_paged_decode_static.argtypes = [sp] + [vp] * 9
+    lib.vox_paged_decode_static.restype = ctypes.c_int
     lib.vox_decode_step.argtypes = [sp, i32] + [vp] * 10 + [ctypes.c_size_t, vp]
     lib.vox_decode_step.restype = ctypes.c_int
     lib.vox_rope_append.argtypes = [sp, vp, vp, vp, i32] + [vp] * 6
@@ -188,6 +190,20 @@ def paged_decode(shape, q, k_pool, v_pool, block_tables, context_lens, out, work
         _dev(wave_clock, torch.int64, "wave_clock", optional=True))
     del keep
     _check(rc, "vox_paged_decode")
+
+
+def paged_decode_static(shape, q, k_pool, v_pool, block_tables, context_lens, out, lse=None,
+                        context_lens_host=None, stream=None):
+    """``paged_decode`` on the library's built-in scratch memory: no workspace, no allocation."""
+    bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+    keep, host = _host_lens(context_lens_host)
+    rc = load().vox_paged_decode_static(
+        ctypes.byref(shape), _dev(q, bf, "q"), _dev(k_pool, bf, "k_pool"),
+        _dev(v_pool, bf, "v_pool"), _dev(block_tables, i32, "block_tables"),
+        _dev(context_lens, i32, "context_lens"), host, _dev(out, f32, "out"),
+        _dev(lse, f32, "lse", optional=True), _stream(stream))
+    del keep
+    _check(rc, "vox_paged_decode_static")
 
 
 class StepArgs:

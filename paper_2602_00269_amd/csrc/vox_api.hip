@@ -3,12 +3,35 @@
 // kernels.
 #include <math.h>
 
+#include <mutex>
 #include <vector>
 
 #include "vox_common.hpp"
 
+// Built-in scratch memory of vox_paged_decode_static: every GPU the library runs on holds its
+// own copy of this array, at its own address, until the process ends.  In host code the name is
+// only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[VOX_STATIC_SCRATCH_BYTES];
+
 namespace vox {
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+int static_scratch(void** out) {
+  static std::mutex mu;
+  static void* ptrs[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return VOX_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return VOX_ERR_HIP;
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return VOX_OK;
+}
 
 constexpr int kMaxSplitWaves = 1 << 20;
 
@@ -230,6 +253,34 @@ size_t mixed_batch_base(size_t prefill_bytes, const vox_shape_t* s) {
   return align_up(prefill_bytes, 256) + align_up((size_t)s->num_streams * sizeof(int32_t), 256);
 }
 
+// One decode call on a given workspace (the caller's, or the built-in scratch array).
+int decode_call(const vox_shape_t* shape, const void* q, const void* k_pool, const void* v_pool,
+                const int32_t* block_tables, const int32_t* context_lens,
+                const int32_t* context_lens_host, float* out, float* lse, void* workspace,
+                size_t workspace_bytes, void* hip_stream, void* event_before, void* event_after,
+                uint64_t* wave_clock) {
+  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out || !workspace)
+    return VOX_ERR_NULL;
+  if ((uintptr_t)workspace % 256 || !all_aligned16(q, k_pool, v_pool, out)) return VOX_ERR_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
+  Plan plan;
+  if (int rc = make_plan(shape, lens_for_planning(context_lens_host, st), workspace_bytes, &plan))
+    return rc;
+  Params p = make_params(shape);
+  char* ws = (char*)workspace;
+  p.pool_counter = pool_counter(plan, ws, 0);
+  set_step_hints(&p, plan);
+  p.wave_clock = (unsigned long long*)wave_clock;
+  if (int rc = enqueue_plan(p, plan, ws, block_tables, context_lens, st)) return rc;
+  const WsPtrs w = ws_ptrs(plan, ws);
+  if (int rc = enqueue_attention(shape, p, plan, w, q, k_pool, v_pool, st,
+                                 (hipEvent_t)event_before, (hipEvent_t)event_after))
+    return rc;
+  return launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out, lse, st) == hipSuccess
+             ? VOX_OK
+             : VOX_ERR_HIP;
+}
+
 }  // namespace
 }  // namespace vox
 
@@ -286,27 +337,26 @@ int vox_paged_decode_profiled(const vox_shape_t* shape, const void* q, const voi
                               void* hip_stream, void* event_before, void* event_after,
                               uint64_t* wave_clock) {
   if (int rc = validate(shape)) return rc;
-  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out || !workspace)
-    return VOX_ERR_NULL;
-  if ((uintptr_t)workspace % 256 || !all_aligned16(q, k_pool, v_pool, out)) return VOX_ERR_ARG;
-  hipStream_t st = (hipStream_t)hip_stream;
-  Plan plan;
-  if (int rc = make_plan(shape, lens_for_planning(context_lens_host, st), workspace_bytes, &plan))
-    return rc;
-  Params p = make_params(shape);
-  char* ws = (char*)workspace;
-  p.pool_counter = pool_counter(plan, ws, 0);
-  set_step_hints(&p, plan);
-  p.wave_clock = (unsigned long long*)wave_clock;
-  if (int rc = enqueue_plan(p, plan, ws, block_tables, context_lens, st)) return rc;
-  const WsPtrs w = ws_ptrs(plan, ws);
-  if (int rc = enqueue_attention(shape, p, plan, w, q, k_pool, v_pool, st,
-                                 (hipEvent_t)event_before, (hipEvent_t)event_after))
-    return rc;
-  return launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out, lse, st) == hipSuccess
-             ? VOX_OK
-             : VOX_ERR_HIP;
+  if (!workspace) return VOX_ERR_NULL;
+  return decode_call(shape, q, k_pool, v_pool, block_tables, context_lens, context_lens_host, out,
+                     lse, workspace, workspace_bytes, hip_stream, event_before, event_after,
+                     wave_clock);
 }
+
+int vox_paged_decode_static(const vox_shape_t* shape, const void* q, const void* k_pool,
+                            const void* v_pool, const int32_t* block_tables,
+                            const int32_t* context_lens, const int32_t* context_lens_host,
+                            float* out, float* lse, void* hip_stream) {
+  if (int rc = validate(shape)) return rc;
+  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out) return VOX_ERR_NULL;
+  void* ws = nullptr;
+  if (int rc = static_scratch(&ws)) return rc;
+  const int rc = decode_call(shape, q, k_pool, v_pool, block_tables, context_lens,
+                             context_lens_host, out, lse, ws, VOX_STATIC_SCRATCH_BYTES,
+                             hip_stream, nullptr, nullptr, nullptr);
+  return rc == VOX_ERR_WORKSPACE ? VOX_ERR_SCRATCH : rc;
+}
+
 
 int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* const* q,
                     const void* const* k_new, const void* const* v_new, void* const* k_pool,
@@ -595,6 +645,7 @@ const char* vox_strerror(int code) {
     case VOX_ERR_WORKSPACE: return "workspace too small (see vox_paged_decode_workspace_bytes)";
     case VOX_ERR_HIP: return "a HIP launch failed (see hipGetLastError)";
     case VOX_ERR_ARG: return "a scalar argument is out of range, or a tensor is not 16-byte aligned";
+    case VOX_ERR_SCRATCH: return "the call needs more than the VOX_STATIC_SCRATCH_BYTES of built-in scratch memory: use the entry point that takes a caller workspace";
     default: return "unknown vox error code";
   }
 }
