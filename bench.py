@@ -28,14 +28,26 @@ MULTI_WORKLOADS = ("chunk15", "chunk25", "chunk28", "prefill", "admit")
 SAMPLE_WORKLOADS = {"sample_small": (1024, 6564, "cosyvoice"), "sample_large": (256, 156940, "orpheus")}
 METRIC = "decode-step KV GB/s & % HBM peak; stream-steps/sec at 256 streams"
 
-# HBM bytes per attention-kernel launch from rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, each
-# scaled by what the same counter reads for a plain 1 GiB device copy); the runs are summarised
-# in profiles/*_<workload>*.txt.  Workloads without a counter run report null.
-MEASURED_TRAFFIC = {
-    "cfg3": 2356073726, "cfg4": 2730018149, "cfg5": 1103168749,
-    "chunk15": 2444131382, "chunk25": 2568475473, "chunk28": 2414401398, "admit": 2964099176,
-    "prefill": 468233930, "sample_small": 27864508, "sample_large": 321869659,
-}
+def measured_traffic(workload: str):
+    """HBM bytes per launch of the workload's dominant kernel, as the rocprofv3 --pmc runs
+    summarised under profiles/ measured them (FETCH_SIZE, then WRITE_SIZE, each scaled by what the
+    same counter reads for a plain 1 GiB device copy).  Read from the summary whose first line
+    names the workload; None when there is none."""
+    import glob
+    import re
+
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        try:
+            text = open(path).read()
+        except OSError:
+            continue
+        first = text.split("\n", 1)[0]
+        if not re.search(rf"workload {re.escape(workload)}\b", first):
+            continue
+        m = re.search(r"traffic = (\d+) bytes per launch", text)
+        if m:
+            return int(m.group(1))
+    return None
 
 
 def cpu_model() -> str:
@@ -134,7 +146,7 @@ def bench_multi(args, dev) -> int:
         kernels = "decode_kernel<MfmaMath>" + (" + decode_kernel<MqMath>" if (n64 > 1).any() else "")
     roofline.update({"kernel": kernels, "kernel_ms": round(kern_ms, 4),
                      "bytes_per_launch": kv_bytes, "flops_per_launch": flops,
-                     "traffic": MEASURED_TRAFFIC.get(args.workload)})
+                     "traffic": measured_traffic(m.name)})
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -258,7 +270,7 @@ def bench_sample(args, dev) -> int:
     roofline = {"bound": "hbm", "kernel": "sample_kernel", "achieved": round(ach, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
                 "kernel_ms": round(kern_ms, 4), "bytes_per_launch": nbytes,
-                "traffic": MEASURED_TRAFFIC.get(args.workload)}
+                "traffic": measured_traffic(f"{args.workload}_{s}x{v}")}
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -299,59 +311,21 @@ def bench_sample(args, dev) -> int:
     return 0
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg3",
-                    choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", *MULTI_WORKLOADS,
-                             *SAMPLE_WORKLOADS],
-                    help="cfg1..cfg5: decode step (cfg3 is the headline); the others are "
-                         "multi-token steps (detokenizer chunks, prompts, admission mix)")
-    ap.add_argument("--path", default="auto", choices=["auto", "mfma", "valu"])
-    ap.add_argument("--split-waves", type=int, default=0)
-    ap.add_argument("--layers", type=int, default=None, help="override the preset's layer count")
-    ap.add_argument("--pool-copies", type=int, default=None,
-                    help="distinct pool sets rotated across steps (default: enough to exceed 1 GiB)")
-    ap.add_argument("--no-device-lens-only", dest="host_lens", action="store_true", default=True)
-    ap.add_argument("--device-lens-only", dest="host_lens", action="store_false",
-                    help="do not hand the host copy of context_lens to the library")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain 1 GiB device copy (known traffic for scaling HBM counters)")
-    ap.add_argument("--hip-graph", action="store_true",
-                    help="capture one step per pool set into a HIP graph and time the replays")
-    ap.add_argument("--rope", action="store_true",
-                    help="time vox_decode_step_rope: rotary embedding + Q/K/V split fused into "
-                         "the append (inputs are packed QKV rows)")
-    ap.add_argument("--no-read-ceiling", action="store_true",
-                    help="skip the 4 GiB streaming-read probe that measures the chip's read ceiling")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    args = ap.parse_args()
-
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
-              "(the decode step shards by stream or by kv head with no exchange between GPUs)",
-              file=sys.stderr)
-        return 2
+def bench_decode(args, dev, workload, full=True):
+    """One decode-step workload: region A times the whole step through the production entry
+    point (wall clock over all steps for the mean, HIP events between the steps for the median),
+    region B the attention kernel alone between HIP events.  ``full`` adds the wave clocks, the
+    read-ceiling probe and the CPU baseline and returns the whole bench line; otherwise a short
+    record for the ``also`` list."""
+    import copy
 
     import numpy as np
     import torch
 
     from paper_2602_00269_amd import binding, synth
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 3
-    binding.load()
-    dev = torch.device("cuda:0")
-    if args.workload in MULTI_WORKLOADS:
-        return bench_multi(args, dev)
-    if args.workload in SAMPLE_WORKLOADS:
-        return bench_sample(args, dev)
-    cfg = int(args.workload[3:])
     path = {"auto": binding.PATH_AUTO, "mfma": binding.PATH_MFMA, "valu": binding.PATH_VALU}[args.path]
+    cfg = int(workload[3:])
 
     # ---- workload(s): distinct pool sets so small presets cannot live in the 256 MB cache
     base = synth.make_workload(cfg, device=dev, layers=args.layers)
@@ -360,8 +334,6 @@ def main() -> int:
     if copies is None:
         copies = 1 if kv_bytes_layer * base.layers >= (1 << 30) else \
             int(min(16, -(-(1 << 30) // max(1, kv_bytes_layer * base.layers))))
-    import copy
-
     sets = [base]
     for _ in range(1, copies):  # same streams and tables, pool contents copied to fresh memory
         w = copy.copy(base)
@@ -422,13 +394,18 @@ def main() -> int:
     # ---- timed region A: the production entry point, whole step
     for i in range(args.warmup):
         step(i)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    marks[0].record()  # on the stream the steps are launched on (torch's current stream)
     for i in range(args.steps):
         step(i)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    per_step = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)])
+    ms_median = float(np.median(per_step))
     kv_bytes_step = kv_bytes_layer * base.layers
     value = kv_bytes_step / (ms_per_step * 1e-3) / 1e9
 
@@ -449,11 +426,24 @@ def main() -> int:
                                  context_lens_host=host_lens, events=evs[e])
             e += 1
     torch.cuda.synchronize()
-    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    kern = np.array([a.elapsed_time(b) for a, b in evs])
+    kern_ms = float(kern.mean())
     achieved = kv_bytes_layer / (kern_ms * 1e-3) / 1e9
+    waves = args.split_waves if args.split_waves > 0 else 1024
+    if not full:  # a line of the `also` list: the whole step and the attention kernel
+        return {
+            "workload": base.name, "streams": base.num_streams, "layers": base.layers,
+            "kv_bytes_per_step": kv_bytes_step, "value": round(value, 1), "unit": "GB/s",
+            "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(ms_median, 4),
+            "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+            "pct_hbm_peak_median": round(100.0 * kv_bytes_step / (ms_median * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
+            "stream_steps_per_s": round(base.num_streams / (ms_per_step * 1e-3), 1),
+            "kernel_ms": round(kern_ms, 4), "kernel_ms_median": round(float(np.median(kern)), 4),
+            "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(base.name),
+            "pool_copies": copies,
+        }
 
     # ---- split-K balance: every wave's own start / end clock (100 MHz) in one more launch
-    waves = args.split_waves if args.split_waves > 0 else 1024
     clocks = torch.full((2 * waves,), -1, dtype=torch.int64, device=dev)
     w0, o0 = sets[0], outs[0]
     binding.kv_append(sh, w0.k_new[0], w0.v_new[0], w0.k_pool[0], w0.v_pool[0], bt, lens)
@@ -502,8 +492,9 @@ def main() -> int:
         "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4),
         "kernel_ms": round(kern_ms, 4),
+        "kernel_ms_median": round(float(np.median(kern)), 4),
         "bytes_per_launch": kv_bytes_layer,
-        "traffic": MEASURED_TRAFFIC.get(args.workload) if path != binding.PATH_VALU else None,
+        "traffic": measured_traffic(base.name) if path != binding.PATH_VALU else None,
         "read_ceiling_gbps": read_ceiling,
         "frac_of_read_ceiling": round(achieved / read_ceiling, 4) if read_ceiling else None,
         "other_algorithmic_bytes_per_launch": other_bytes,
@@ -562,6 +553,7 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(ms_median, 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -589,6 +581,75 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    return line
+
+
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg3",
+                    choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", *MULTI_WORKLOADS,
+                             *SAMPLE_WORKLOADS],
+                    help="cfg1..cfg5: decode step (cfg3 is the headline); the others are "
+                         "multi-token steps (detokenizer chunks, prompts, admission mix)")
+    ap.add_argument("--path", default="auto", choices=["auto", "mfma", "valu"])
+    ap.add_argument("--split-waves", type=int, default=0)
+    ap.add_argument("--layers", type=int, default=None, help="override the preset's layer count")
+    ap.add_argument("--pool-copies", type=int, default=None,
+                    help="distinct pool sets rotated across steps (default: enough to exceed 1 GiB)")
+    ap.add_argument("--no-device-lens-only", dest="host_lens", action="store_true", default=True)
+    ap.add_argument("--device-lens-only", dest="host_lens", action="store_false",
+                    help="do not hand the host copy of context_lens to the library")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (known traffic for scaling HBM counters)")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="capture one step per pool set into a HIP graph and time the replays")
+    ap.add_argument("--rope", action="store_true",
+                    help="time vox_decode_step_rope: rotary embedding + Q/K/V split fused into "
+                         "the append (inputs are packed QKV rows)")
+    ap.add_argument("--no-read-ceiling", action="store_true",
+                    help="skip the 4 GiB streaming-read probe that measures the chip's read ceiling")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-also", action="store_true",
+                    help="headline workload only: skip the cfg4 / cfg2 / cfg5 records of the default run")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
+              "(the decode step shards by stream or by kv head with no exchange between GPUs)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2602_00269_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    binding.load()
+    dev = torch.device("cuda:0")
+    if args.workload in MULTI_WORKLOADS:
+        return bench_multi(args, dev)
+    if args.workload in SAMPLE_WORKLOADS:
+        return bench_sample(args, dev)
+    line = bench_decode(args, dev, args.workload)
+    if args.workload == "cfg3" and not args.no_also:
+        # the other decode presets in the same run: the 512-stream target config, the small
+        # batch the paper's models run at, and the 28-layer full step
+        import gc
+
+        line["also"] = []
+        for other in ("cfg4", "cfg2", "cfg5"):
+            gc.collect()
+            torch.cuda.empty_cache()
+            line["also"].append(bench_decode(args, dev, other, full=False))
     print(json.dumps(line))
     return 0
 
