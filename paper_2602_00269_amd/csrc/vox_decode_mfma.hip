@@ -15,14 +15,15 @@
 //     the four lane groups.  Columns [0,G) keep hi = bf16(p); columns [G,2G) keep
 //     lo = bf16(p - hi), so hi + lo carries p to ~2^-17 relative and the two partial outputs
 //     are added once per run.
-//   Output per block (v_mfma_f32_16x16x16_bf16, D/16 of them):
-//       O_tile[16 dims x 16] += Vt_tile[16 dims x 16 tokens] * Pt[16 tokens x 16]
+//   Output per step (the same 32-deep MFMA, D/16 of them, one per 16-dim tile):
+//       O_tile[16 dims x 16] += Vt_tile[16 dims x 32 tokens] * Pt[32 tokens x 16]
 //     The V granule [4][D][4] keeps four consecutive tokens of a dim adjacent: lane (n, c)
 //     reads 16 bytes at c*D*8 + j*256 + n*16 = dims 32*j + 2*n and 32*j + 2*n + 1, tokens
-//     4*c .. 4*c+3.  The low 8 bytes are row n of tile 2j, the high 8 bytes row n of tile
-//     2j+1 (tile 2j row i is dim 32j + 2i, tile 2j+1 row i is dim 32j + 2i + 1).  B operand =
-//     the lane's own 4 probabilities of that block.  Nothing moves between lanes inside the
-//     loop except the max.
+//     4*c .. 4*c+3, of block A and of block B.  The low 8 bytes are row n of tile 2j, the
+//     high 8 bytes row n of tile 2j+1 (tile 2j row i is dim 32j + 2i, tile 2j+1 row i is dim
+//     32j + 2i + 1); reduction slots 0-3 of a lane group are its four tokens of block A,
+//     slots 4-7 its four tokens of block B.  B operand = the lane's own 8 probabilities.
+//     Nothing moves between lanes inside the loop except the max.
 //     Result layout: lane (n, c), register r of tile 2j+u = dim 32j + 8c + 2r + u of column n,
 //     so the per-column rescale factor is lane-local and a lane owns 8 consecutive dims.
 #include "vox_decode_core.hpp"
@@ -31,17 +32,11 @@ namespace vox {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ inline f32x4 mfma32(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
-__device__ inline f32x4 mfma16(u32x2 a, u32x2 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a),
-                                                   __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
 }
 
 __device__ inline uint32_t pack_bf16(float a, float b) {
@@ -63,7 +58,10 @@ struct MfmaMath {
   __device__ static int columns(const Params& p) { return p.G; }
 
   static constexpr int kBuffers = NBUF;
+  static constexpr int kHeadDim = D;
   static constexpr bool kDirect = false;  // every run leaves a partial record for the merge
+  static constexpr bool kSelfMerge = true;
+  static constexpr bool kFusedAppend = !PACKED;
   static constexpr int kStashFloats = 4096;  // 16 KB per wave: several decode records
   static constexpr int kMinWavesPerSimd = 1;
   static constexpr int KK = D / 32;  // score MFMAs per block = V loads per block
@@ -74,6 +72,10 @@ struct MfmaMath {
   };
   struct Regs {
     u32x4 k[2][KK], v[2][KK];
+    // fused append: the newest token's K dims 32kk + 8c .. +8 and V dims 32j + 2n, 32j + 2n + 1
+    // from k_new / v_new, requested with the step that holds the token
+    u32x4 kn[KK];
+    uint32_t vn[KK];
   };
   struct State {
     Q q;
@@ -129,6 +131,44 @@ struct MfmaMath {
     for (int j = 0; j < KK; ++j) r.v[0][j] = kv_load<STREAM>(va + j * 128);
 #pragma unroll
     for (int j = 0; j < KK; ++j) r.v[1][j] = kv_load<STREAM>(vb + j * 128);
+  }
+
+  // Fused append.  The rows of the token appended this step are not in the pools yet: the
+  // step that ends the stream loads them beside its K/V blocks ...
+  __device__ __forceinline__ void issue_new_token(Regs& r, const Desc& dsc) const {
+    const uint16_t* krow = p.k_new + (size_t)dsc.w * D + c * 8;
+    const uint16_t* vrow = p.v_new + (size_t)dsc.w * D + 2 * n;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) r.kn[kk] = *reinterpret_cast<const u32x4*>(krow + 32 * kk);
+#pragma unroll
+    for (int j = 0; j < KK; ++j) r.vn[j] = *reinterpret_cast<const uint32_t*>(vrow + 32 * j);
+  }
+  // ... and puts them where the pools will hold them: token t of a block is row t of the K
+  // operand (lanes n == t) and slot t % 4 of the V quads of lane group t / 4.
+  __device__ __forceinline__ void patch_new_token(Regs& r, const Desc& dsc) const {
+    const int tn = (dsc.z & kMetaTokMask) - 1;
+    const int t = tn & (kBlock - 1), e = t & 3;
+    const uint32_t keep = (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+    const int sh = (e & 1) * 16;
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      const bool here = (tn >> 4) == blk;
+      const bool krow = here && n == t, vlo = here && c == (t >> 2) && e < 2,
+                 vhi = here && c == (t >> 2) && e >= 2;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const u32x4 old = r.k[blk][kk], neu = r.kn[kk];
+        r.k[blk][kk] = u32x4{krow ? neu.x : old.x, krow ? neu.y : old.y, krow ? neu.z : old.z,
+                             krow ? neu.w : old.w};
+      }
+#pragma unroll
+      for (int j = 0; j < KK; ++j) {
+        const uint32_t d0 = (r.vn[j] & 0xFFFFu) << sh, d1 = (r.vn[j] >> 16) << sh;
+        const u32x4 v = r.v[blk][j];
+        r.v[blk][j] = u32x4{vlo ? (v.x & keep) | d0 : v.x, vhi ? (v.y & keep) | d0 : v.y,
+                            vlo ? (v.z & keep) | d1 : v.z, vhi ? (v.w & keep) | d1 : v.w};
+      }
+    }
   }
 
   __device__ void reset(State& s) const {
