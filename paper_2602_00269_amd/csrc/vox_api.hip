@@ -4,7 +4,6 @@
 #include <math.h>
 
 #include <mutex>
-#include <vector>
 
 #include "vox_common.hpp"
 
@@ -92,11 +91,6 @@ Params make_params(const vox_shape_t* s) {
   p.lse = nullptr;
   p.q_rows = nullptr;
   p.skip_single = 0;
-  p.seg_info = nullptr;
-  p.seg_count = nullptr;
-  p.lens = nullptr;
-  p.k_new = p.v_new = nullptr;
-  p.k_pool_w = p.v_pool_w = nullptr;
   return p;
 }
 
@@ -115,11 +109,6 @@ Workspace map_workspace(const vox_shape_t* s, int64_t desc_capacity) {
   off = align_up(off + kHeaderWords * sizeof(int32_t), 256);
   w.step_prefix = off;
   off = align_up(off + ((size_t)s->num_streams + 1) * sizeof(int32_t), 256);
-  const size_t segments = (size_t)s->num_streams * s->num_kv_heads;
-  w.seg_info = off;
-  off = align_up(off + segments * sizeof(int2), 256);
-  w.seg_count = off;
-  off = align_up(off + segments * sizeof(int32_t), 256);
   w.partial_ml = off;
   off = align_up(off + slots * g * sizeof(float2), 256);
   w.partial_acc = off;
@@ -153,7 +142,10 @@ struct Plan {
   Workspace ws;
 };
 
-int make_plan(const vox_shape_t* s, const int32_t* lens_host, size_t workspace_bytes, Plan* out) {
+// single_of: when not null (mixed batches), the host copy of q_offsets; only the streams that
+// bring exactly one token count, the others are planned as empty.
+int make_plan(const vox_shape_t* s, const int32_t* lens_host, size_t workspace_bytes, Plan* out,
+              const int32_t* single_of = nullptr) {
   const size_t fixed = map_workspace(s, 0).total;
   if (workspace_bytes < fixed + sizeof(int4)) return VOX_ERR_WORKSPACE;
   const int64_t cap = (int64_t)((workspace_bytes - fixed) / sizeof(int4));
@@ -163,6 +155,7 @@ int make_plan(const vox_shape_t* s, const int32_t* lens_host, size_t workspace_b
     for (int i = 0; i < s->num_streams; ++i) {
       if (lens_host[i] < 0 || lens_host[i] > (int64_t)s->max_blocks_per_stream * kBlock)
         return VOX_ERR_ARG;
+      if (single_of && single_of[i + 1] - single_of[i] != 1) continue;
       need += ((lens_host[i] + kBlock - 1) / kBlock + 1) / 2;
     }
     need *= s->num_kv_heads;
@@ -190,47 +183,26 @@ int32_t* pool_counter(const Plan& plan, char* ws, int layer) {
   return (int32_t*)(ws + plan.ws.header) + kHdrPoolCounters + layer;
 }
 
+int enqueue_plan(const Params& p, const Plan& plan, char* ws, const int32_t* bt,
+                 const int32_t* lens, hipStream_t st) {
+  hipError_t e = launch_plan(p, bt, lens, plan.waves, plan.desc_capacity, plan.max_steps,
+                             (int32_t*)(ws + plan.ws.header),
+                             (int32_t*)(ws + plan.ws.step_prefix), (int4*)(ws + plan.ws.desc), st);
+  return e == hipSuccess ? VOX_OK : VOX_ERR_HIP;
+}
+
 struct WsPtrs {
   int32_t* header;
   int32_t* step_prefix;
   int4* desc;
   float2* pml;
   float* pacc;
-  int2* seg_info;
-  int32_t* seg_count;
 };
 
 WsPtrs ws_ptrs(const Plan& plan, char* ws) {
   return WsPtrs{(int32_t*)(ws + plan.ws.header), (int32_t*)(ws + plan.ws.step_prefix),
                 (int4*)(ws + plan.ws.desc), (float2*)(ws + plan.ws.partial_ml),
-                (float*)(ws + plan.ws.partial_acc), (int2*)(ws + plan.ws.seg_info),
-                (int32_t*)(ws + plan.ws.seg_count)};
-}
-
-int enqueue_plan(const Params& p, const Plan& plan, char* ws, const int32_t* bt,
-                 const int32_t* lens, hipStream_t st) {
-  const WsPtrs w = ws_ptrs(plan, ws);
-  hipError_t e = launch_plan(p, bt, lens, plan.waves, plan.desc_capacity, plan.max_steps,
-                             w.header, w.step_prefix, w.desc, w.seg_info, w.seg_count, st);
-  return e == hipSuccess ? VOX_OK : VOX_ERR_HIP;
-}
-
-// What the attention launch needs for the merge by the last arriver: the plan's per-segment
-// data, the device lengths (rows of empty streams are zeroed there) and the output.
-void set_merge_target(Params* p, const WsPtrs& w, const int32_t* lens, float* out, float* lse) {
-  p->seg_info = w.seg_info;
-  p->seg_count = w.seg_count;
-  p->lens = lens;
-  p->out = out;
-  p->lse = lse;
-}
-// Fused append of this launch (matrix-core path only), or none.
-void set_fused_append(Params* p, const void* k_new, const void* v_new, void* k_pool,
-                      void* v_pool) {
-  p->k_new = (const uint16_t*)k_new;
-  p->v_new = (const uint16_t*)v_new;
-  p->k_pool_w = (uint16_t*)k_pool;
-  p->v_pool_w = (uint16_t*)v_pool;
+                (float*)(ws + plan.ws.partial_acc)};
 }
 
 // Append roles: rows that arrive as separate K and V tensors ...
@@ -250,18 +222,16 @@ bool rope_table_ok(const vox_shape_t* s, int32_t rope_positions) {
   return rope_positions >= s->max_blocks_per_stream * kBlock;
 }
 
-// The split-K attention launch; the wave that stores a segment's last record merges it.
+// The split-K attention launch alone (the merge follows separately).
 int enqueue_attention(const vox_shape_t* s, const Params& p, const Plan& plan, const WsPtrs& w,
                       const void* q, const void* k_pool, const void* v_pool, hipStream_t st,
                       hipEvent_t ev_before = nullptr, hipEvent_t ev_after = nullptr) {
-  // no more waves than steps can exist (a launched wave without a range only zeroes the rows
-  // of empty streams), and at least one workgroup for those rows
+  // no more waves than steps can exist (each launched wave without a range exits at once)
   int waves = plan.waves;
   if (plan.max_steps < waves)
     waves = (int)((plan.max_steps + kWavesPerGroup - 1) / kWavesPerGroup * kWavesPerGroup);
-  if (waves < kWavesPerGroup) waves = kWavesPerGroup;
   if (ev_before && hipEventRecord(ev_before, st) != hipSuccess) return VOX_ERR_HIP;
-  {
+  if (waves > 0) {
     hipError_t e = (s->decode_path == VOX_PATH_VALU)
                        ? launch_decode_valu(p, waves, q, k_pool, v_pool, w.header, w.desc, w.pml,
                                             w.pacc, st)
@@ -306,9 +276,12 @@ int decode_call(const vox_shape_t* shape, const void* q, const void* k_pool, con
   p.wave_clock = (unsigned long long*)wave_clock;
   if (int rc = enqueue_plan(p, plan, ws, block_tables, context_lens, st)) return rc;
   const WsPtrs w = ws_ptrs(plan, ws);
-  set_merge_target(&p, w, context_lens, out, lse);
-  return enqueue_attention(shape, p, plan, w, q, k_pool, v_pool, st, (hipEvent_t)event_before,
-                           (hipEvent_t)event_after);
+  if (int rc = enqueue_attention(shape, p, plan, w, q, k_pool, v_pool, st,
+                                 (hipEvent_t)event_before, (hipEvent_t)event_after))
+    return rc;
+  return launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out, lse, st) == hipSuccess
+             ? VOX_OK
+             : VOX_ERR_HIP;
 }
 
 }  // namespace
@@ -413,29 +386,24 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
   p.pool_counter = pool_counter(plan, ws, 0);  // the plan zeroes every layer's counter
   set_step_hints(&p, plan);
   const WsPtrs w = ws_ptrs(plan, ws);
-  // Launch chain on the matrix-core path: plan, then one attention launch per layer; the launch
-  // takes each stream's newest token from k_new / v_new, writes it into the layer's pools and
-  // merges its own partial records.  On the vector-ALU path the append stays a launch of its
-  // own (with the plan for layer 0).
-  const bool fused = shape->decode_path != VOX_PATH_VALU;
-  hipError_t e =
-      fused ? launch_plan(p, block_tables, context_lens, plan.waves, plan.desc_capacity,
-                          plan.max_steps, w.header, w.step_prefix, w.desc, w.seg_info,
-                          w.seg_count, st)
-            : launch_plan_append(p, block_tables, context_lens, plan.waves, plan.desc_capacity,
-                                 plan.max_steps, w.header, w.step_prefix, w.desc, w.seg_info,
-                                 w.seg_count,
-                                 plain_append(k_new[0], v_new[0], k_pool[0], v_pool[0]), st);
-  if (e != hipSuccess) return VOX_ERR_HIP;
+  // Launch chain: [plan + append(0)] attention(0) [merge(0) + append(1)] attention(1) ...
+  // merge(L-1).  Each bracket is one launch of two independent roles.
+  if (launch_plan_append(p, block_tables, context_lens, plan.waves, plan.desc_capacity,
+                         plan.max_steps, w.header, w.step_prefix, w.desc,
+                         plain_append(k_new[0], v_new[0], k_pool[0], v_pool[0]), st) != hipSuccess)
+    return VOX_ERR_HIP;
   for (int l = 0; l < num_layers; ++l) {
     p.pool_counter = pool_counter(plan, ws, l);
-    set_merge_target(&p, w, context_lens, out[l], nullptr);
-    if (fused)
-      set_fused_append(&p, k_new[l], v_new[l], k_pool[l], v_pool[l]);
-    else if (l > 0 && launch_append(p, plain_append(k_new[l], v_new[l], k_pool[l], v_pool[l]),
-                                    block_tables, context_lens, st) != hipSuccess)
-      return VOX_ERR_HIP;
     if (int rc = enqueue_attention(shape, p, plan, w, q[l], k_pool[l], v_pool[l], st)) return rc;
+    hipError_t e =
+        l + 1 < num_layers
+            ? launch_merge_append(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], block_tables,
+                                  context_lens,
+                                  plain_append(k_new[l + 1], v_new[l + 1], k_pool[l + 1],
+                                               v_pool[l + 1]),
+                                  st)
+            : launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], nullptr, st);
+    if (e != hipSuccess) return VOX_ERR_HIP;
   }
   return VOX_OK;
 }
@@ -490,22 +458,24 @@ int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const voi
   p.pool_counter = pool_counter(plan, ws, 0);  // the plan zeroes every layer's counter
   set_step_hints(&p, plan);
   const WsPtrs w = ws_ptrs(plan, ws);
-  // [plan + rope/append(0)] attention(0) rope/append(1) attention(1) ...: the rotated query
-  // rows must exist before the layer's attention starts, so this append is a launch of its own
+  // [plan + rope/append(0)] attention(0) [merge(0) + rope/append(1)] attention(1) ... merge(L-1)
   const auto layer = [&](int l) {
     return rope_append(qkv[l], rope_cos, rope_sin, q_rot[l], k_pool[l], v_pool[l]);
   };
   if (launch_plan_append(p, block_tables, context_lens, plan.waves, plan.desc_capacity,
-                         plan.max_steps, w.header, w.step_prefix, w.desc, w.seg_info,
-                         w.seg_count, layer(0), st) != hipSuccess)
+                         plan.max_steps, w.header, w.step_prefix, w.desc, layer(0),
+                         st) != hipSuccess)
     return VOX_ERR_HIP;
   for (int l = 0; l < num_layers; ++l) {
     p.pool_counter = pool_counter(plan, ws, l);
-    set_merge_target(&p, w, context_lens, out[l], nullptr);
-    if (l > 0 && launch_append(p, layer(l), block_tables, context_lens, st) != hipSuccess)
-      return VOX_ERR_HIP;
     if (int rc = enqueue_attention(shape, p, plan, w, q_rot[l], k_pool[l], v_pool[l], st))
       return rc;
+    hipError_t e =
+        l + 1 < num_layers
+            ? launch_merge_append(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], block_tables,
+                                  context_lens, layer(l + 1), st)
+            : launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], nullptr, st);
+    if (e != hipSuccess) return VOX_ERR_HIP;
   }
   return VOX_OK;
 }
@@ -635,11 +605,10 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
     // the decode part: masked lengths on both sides, its own workspace behind the multi-token one
     const size_t lens_off = align_up(m.total, 256), dec_off = mixed_batch_base(m.total, shape);
     if (dec_off >= workspace_bytes) continue;
-    std::vector<int32_t> single_lens((size_t)p.S);
-    for (int s = 0; s < p.S; ++s)
-      single_lens[s] = q_offsets_host[s + 1] - q_offsets_host[s] == 1 ? context_lens_host[s] : 0;
     Plan plan;
-    if (make_plan(shape, single_lens.data(), workspace_bytes - dec_off, &plan) != VOX_OK) continue;
+    if (make_plan(shape, context_lens_host, workspace_bytes - dec_off, &plan, q_offsets_host) !=
+        VOX_OK)
+      continue;
     int32_t* lens_single = (int32_t*)(ws + lens_off);
     char* dws = ws + dec_off;
     Params pd = p;  // the decode kernels' view
@@ -654,16 +623,16 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
       return VOX_ERR_HIP;
     if (int rc = enqueue_plan(pd, plan, dws, block_tables, lens_single, st)) return rc;
     const WsPtrs w = ws_ptrs(plan, dws);
-    set_merge_target(&pd, w, lens_single, out, lse);
     // the events enclose both attention kernels
     hipEvent_t after_decode = tiles > 0 ? nullptr : (hipEvent_t)event_after;
     if (int rc = enqueue_attention(shape, pd, plan, w, q, k_pool, v_pool, st,
                                    (hipEvent_t)event_before, after_decode))
       return rc;
-    return launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool,
-                          block_tables, context_lens, q_offsets, out, lse, st, nullptr,
-                          (hipEvent_t)event_after, kPrefillRun, tile_streams, nullptr,
-                          max_tile_steps) == hipSuccess
+    if (launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool, block_tables,
+                       context_lens, q_offsets, out, lse, st, nullptr, (hipEvent_t)event_after,
+                       kPrefillRun, tile_streams, nullptr, max_tile_steps) != hipSuccess)
+      return VOX_ERR_HIP;
+    return launch_merge(pd, w.header, w.step_prefix, w.pml, w.pacc, out, lse, st) == hipSuccess
                ? VOX_OK
                : VOX_ERR_HIP;
   }

@@ -1,5 +1,5 @@
-// KV append, block gather and split-K planning.
-#include "vox_common.hpp"
+// KV append, block gather, split-K planning and the partial-softmax merge.
+#include "vox_merge.hpp"
 
 namespace vox {
 namespace {
@@ -182,8 +182,7 @@ constexpr int kPlanMaxStreams = kMaxStreams;  // LDS-resident prefix
 __device__ inline void plan_role(const Params& p, int group, const int32_t* __restrict__ bt,
                                  const int32_t* __restrict__ lens, int waves,
                                  int64_t desc_capacity, int32_t* __restrict__ header,
-                                 int32_t* __restrict__ step_prefix, int4* __restrict__ desc,
-                                 int2* __restrict__ seg_info, int32_t* __restrict__ seg_count) {
+                                 int32_t* __restrict__ step_prefix, int4* __restrict__ desc) {
   __shared__ int prefix[kPlanMaxStreams + 1];
   __shared__ int wave_total[kPlanThreads / kWave];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
@@ -254,23 +253,13 @@ __device__ inline void plan_role(const Params& p, int group, const int32_t* __re
   if (st == n - 1 || step_closes_range(lay, x)) meta |= kMetaLast;
   if (st == n - 1) meta |= kMetaTail;
   desc[x] = make_int4(ida * p.Hkv + h, idb * p.Hkv + h, meta, s * p.Hkv + h);
-  if (st == 0) {
-    // The segment's runs lie in the ranges of its first and last step; run j leaves its record
-    // in slot r0 + j + sigma.  The wave that stores the last of them merges the segment.
-    const int sigma = s * p.Hkv + h;
-    const int64_t last = min(N, x + n) - 1;
-    const int64_t r0 = range_of_step(lay, x), r1 = range_of_step(lay, last);
-    seg_info[sigma] = make_int2((int)(r0 + sigma), (int)(r1 - r0 + 1));
-    seg_count[sigma] = 0;
-  }
 }
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     Params p, const int32_t* __restrict__ bt, const int32_t* __restrict__ lens, int waves,
     int64_t desc_capacity, int32_t* __restrict__ header, int32_t* __restrict__ step_prefix,
-    int4* __restrict__ desc, int2* __restrict__ seg_info, int32_t* __restrict__ seg_count) {
-  plan_role(p, blockIdx.x, bt, lens, waves, desc_capacity, header, step_prefix, desc, seg_info,
-            seg_count);
+    int4* __restrict__ desc) {
+  plan_role(p, blockIdx.x, bt, lens, waves, desc_capacity, header, step_prefix, desc);
 }
 
 // Plan and the first layer's append in one launch: the two are independent and both are
@@ -279,13 +268,67 @@ template <int D>
 __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
     Params p, int plan_groups, AppendArgs a, const int32_t* __restrict__ bt,
     const int32_t* __restrict__ lens, int waves, int64_t desc_capacity,
-    int32_t* __restrict__ header, int32_t* __restrict__ step_prefix, int4* __restrict__ desc,
-    int2* __restrict__ seg_info, int32_t* __restrict__ seg_count) {
+    int32_t* __restrict__ header, int32_t* __restrict__ step_prefix, int4* __restrict__ desc) {
   if ((int)blockIdx.x < plan_groups)
-    plan_role(p, blockIdx.x, bt, lens, waves, desc_capacity, header, step_prefix, desc, seg_info,
-              seg_count);
+    plan_role(p, blockIdx.x, bt, lens, waves, desc_capacity, header, step_prefix, desc);
   else
     any_append_role<D>(p, blockIdx.x - plan_groups, a, bt, lens);
+}
+
+// ---------------------------------------------------------------------------------------
+// Merge: one wave per (stream, q head).  The runs of segment sigma lie in the ranges r0 .. r1 of
+// its first and last global step; run j is slot r0 + j + sigma.
+// Lanes hold the runs' (max, sum) records; the global max and the rescaled sum are wave
+// reductions; the accumulators are then combined with each lane owning D/64 output dims.
+template <int D>
+__device__ inline void merge_role(const Params& p, int group, const int32_t* __restrict__ header,
+                                  const int32_t* __restrict__ step_prefix,
+                                  const float2* __restrict__ pml, const float* __restrict__ pacc,
+                                  float* __restrict__ out, float* __restrict__ lse) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int w = group * kWavesPerGroup + (threadIdx.x >> 6);
+  if (w >= p.S * p.Hq) return;
+  const int s = w / p.Hq, i = w % p.Hq;
+  const int h = i / p.G, g = i % p.G;
+  const int sigma = s * p.Hkv + h;
+  const StepLayout lay = p.n_steps >= 0 ? p.lay : layout_from_header(header);
+  const int64_t N = lay.N;
+  const int nseg = step_prefix[s + 1] - step_prefix[s];
+  const int64_t first = (int64_t)step_prefix[s] * p.Hkv + (int64_t)h * nseg;
+  int n = 0;          // number of runs
+  int64_t slot0 = 0;  // slot of run 0
+  if (nseg > 0 && first < N) {
+    const int64_t last = min(N, first + nseg) - 1;
+    const int64_t r0 = range_of_step(lay, first), r1 = range_of_step(lay, last);
+    n = (int)(r1 - r0 + 1);
+    slot0 = r0 + sigma;
+  }
+  if (p.q_rows && n == 0) return;  // packed rows: a stream without a run owns no output row
+  const size_t row = (size_t)(p.q_rows ? p.q_rows[s] : s) * p.Hq + i;
+  merge_runs<D>(pml, pacc, slot0, n, p.G, g, lane, out + row * D, lse ? lse + row : nullptr);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(Params p, const int32_t* __restrict__ header,
+                                                    const int32_t* __restrict__ step_prefix,
+                                                    const float2* __restrict__ pml,
+                                                    const float* __restrict__ pacc,
+                                                    float* __restrict__ out,
+                                                    float* __restrict__ lse) {
+  merge_role<D>(p, blockIdx.x, header, step_prefix, pml, pacc, out, lse);
+}
+
+// Merge of layer l and the append of layer l + 1 in one launch (independent buffers).
+template <int D>
+__global__ __launch_bounds__(256) void merge_append_kernel(
+    Params p, int merge_grps, const int32_t* __restrict__ header,
+    const int32_t* __restrict__ step_prefix, const float2* __restrict__ pml,
+    const float* __restrict__ pacc, float* __restrict__ out, AppendArgs a,
+    const int32_t* __restrict__ bt, const int32_t* __restrict__ lens) {
+  if ((int)blockIdx.x < merge_grps)
+    merge_role<D>(p, blockIdx.x, header, step_prefix, pml, pacc, out, nullptr);
+  else
+    any_append_role<D>(p, blockIdx.x - merge_grps, a, bt, lens);
 }
 
 // Streaming-read probe with the attention kernel's memory pipeline and none of its arithmetic:
@@ -350,6 +393,9 @@ static unsigned host_append_groups(const Params& p, const AppendArgs& a) {
   const int64_t waves = (int64_t)p.S * (a.qkv ? p.Hq + p.Hkv : p.Hkv);
   return (unsigned)((waves + kWavesPerGroup - 1) / kWavesPerGroup);
 }
+static unsigned host_merge_groups(const Params& p) {
+  return (unsigned)(((int64_t)p.S * p.Hq + kWavesPerGroup - 1) / kWavesPerGroup);
+}
 static unsigned host_plan_groups(int64_t max_steps) {
   return (unsigned)max((int64_t)1, (max_steps + kPlanThreads - 1) / kPlanThreads);
 }
@@ -378,29 +424,55 @@ hipError_t launch_kv_gather(const Params& p, const void* k_pool, const void* v_p
 
 hipError_t launch_plan(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
                        int64_t desc_capacity, int64_t max_steps, int32_t* header,
-                       int32_t* step_prefix, int4* desc, int2* seg_info, int32_t* seg_count,
-                       hipStream_t st) {
+                       int32_t* step_prefix, int4* desc, hipStream_t st) {
   if (p.S > kPlanMaxStreams) return hipErrorInvalidValue;
   hipLaunchKernelGGL(plan_kernel, dim3(host_plan_groups(max_steps)), dim3(kPlanThreads), 0, st, p,
-                     bt, lens, waves, desc_capacity, header, step_prefix, desc, seg_info,
-                     seg_count);
+                     bt, lens, waves, desc_capacity, header, step_prefix, desc);
   return hipGetLastError();
 }
 
 hipError_t launch_plan_append(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
                               int64_t desc_capacity, int64_t max_steps, int32_t* header,
-                              int32_t* step_prefix, int4* desc, int2* seg_info, int32_t* seg_count,
-                              const AppendArgs& a, hipStream_t st) {
+                              int32_t* step_prefix, int4* desc, const AppendArgs& a,
+                              hipStream_t st) {
   if (p.S > kPlanMaxStreams) return hipErrorInvalidValue;
   const unsigned pg = host_plan_groups(max_steps);
   if (p.D == 128)
     hipLaunchKernelGGL(plan_append_kernel<128>, dim3(pg + host_append_groups(p, a)),
                        dim3(kPlanThreads), 0, st, p, (int)pg, a, bt, lens, waves, desc_capacity,
-                       header, step_prefix, desc, seg_info, seg_count);
+                       header, step_prefix, desc);
   else
     hipLaunchKernelGGL(plan_append_kernel<64>, dim3(pg + host_append_groups(p, a)),
                        dim3(kPlanThreads), 0, st, p, (int)pg, a, bt, lens, waves, desc_capacity,
-                       header, step_prefix, desc, seg_info, seg_count);
+                       header, step_prefix, desc);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge(const Params& p, const int32_t* header, const int32_t* step_prefix,
+                        const float2* partial_ml, const float* partial_acc, float* out,
+                        float* lse, hipStream_t st) {
+  if (p.D == 128)
+    hipLaunchKernelGGL(merge_kernel<128>, dim3(host_merge_groups(p)), dim3(256), 0, st, p, header,
+                       step_prefix, partial_ml, partial_acc, out, lse);
+  else
+    hipLaunchKernelGGL(merge_kernel<64>, dim3(host_merge_groups(p)), dim3(256), 0, st, p, header,
+                       step_prefix, partial_ml, partial_acc, out, lse);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_append(const Params& p, const int32_t* header, const int32_t* step_prefix,
+                               const float2* partial_ml, const float* partial_acc, float* out,
+                               const int32_t* bt, const int32_t* lens, const AppendArgs& a,
+                               hipStream_t st) {
+  const unsigned mg = host_merge_groups(p);
+  if (p.D == 128)
+    hipLaunchKernelGGL(merge_append_kernel<128>, dim3(mg + host_append_groups(p, a)), dim3(256), 0,
+                       st, p, (int)mg, header, step_prefix, partial_ml, partial_acc, out, a, bt,
+                       lens);
+  else
+    hipLaunchKernelGGL(merge_append_kernel<64>, dim3(mg + host_append_groups(p, a)), dim3(256), 0,
+                       st, p, (int)mg, header, step_prefix, partial_ml, partial_acc, out, a, bt,
+                       lens);
   return hipGetLastError();
 }
 

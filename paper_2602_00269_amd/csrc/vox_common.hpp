@@ -10,10 +10,8 @@
 // one segment, several whole short segments and the head of another.  Every maximal run of one
 // segment inside one range yields one partial record (max, sum, accumulator); ranges and runs
 // are numbered along the axis, so the record of the run of segment sigma in range r is slot
-// r + sigma.  The plan kernel notes, per segment, the slot of its first run and the number of
-// its runs; the wave that stores the last of a segment's records (counted with one atomic per
-// record) merges them and writes the output rows, so the attention launch is the layer's only
-// launch.
+// r + sigma.  The merge kernel recomputes which ranges a segment crosses from the prefix sums
+// and the layout alone.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -123,8 +121,6 @@ __host__ __device__ inline int64_t pool_ranges_bound(int64_t steps_bound) {
 struct Workspace {
   size_t header;       // int32[kHeaderWords]: 64 header words, then one pool counter per layer
   size_t step_prefix;  // int32[S + 1]: exclusive scan of n_s
-  size_t seg_info;     // int2[S * Hkv]: slot of the segment's first run, number of its runs
-  size_t seg_count;    // int32[S * Hkv]: records of the segment stored so far (zero between launches)
   size_t desc;         // int4[desc_capacity]
   size_t partial_ml;   // float2[slots * G]: (running max in log2 units, sum)
   size_t partial_acc;  // float[slots * G * D]
@@ -165,20 +161,6 @@ struct Params {
   // arrays instead of s.  skip_single (multi-token plan): such streams get no tiles.
   const int32_t* q_rows;
   int32_t skip_single;
-  // Decode step, merge by the last arriver: per-segment (first slot, runs) written by the plan,
-  // per-segment arrival counters (zero when a launch starts and again when it ends), and the
-  // device lengths (streams without tokens get zero rows from the attention launch itself).
-  const int2* seg_info;
-  int32_t* seg_count;
-  const int32_t* lens;
-  // Fused append (null: the caller has appended already): the step of a stream that holds its
-  // newest token takes that token's K / V rows from k_new / v_new ([S][Hkv][D] bf16) instead of
-  // the pools, and the wave writes them into the pools (through these writable aliases) when
-  // it has finished its ranges.
-  const uint16_t* k_new;
-  const uint16_t* v_new;
-  uint16_t* k_pool_w;
-  uint16_t* v_pool_w;
 };
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -212,15 +194,18 @@ hipError_t launch_append(const Params& p, const AppendArgs& a, const int32_t* bt
                          const int32_t* lens, hipStream_t st);
 hipError_t launch_plan_append(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
                               int64_t desc_capacity, int64_t max_steps, int32_t* header,
-                              int32_t* step_prefix, int4* desc, int2* seg_info, int32_t* seg_count,
-                              const AppendArgs& a, hipStream_t st);
+                              int32_t* step_prefix, int4* desc, const AppendArgs& a,
+                              hipStream_t st);
+hipError_t launch_merge_append(const Params& p, const int32_t* header, const int32_t* step_prefix,
+                               const float2* partial_ml, const float* partial_acc, float* out,
+                               const int32_t* bt, const int32_t* lens, const AppendArgs& a,
+                               hipStream_t st);
 hipError_t launch_kv_gather(const Params& p, const void* k_pool, const void* v_pool,
                             const int32_t* bt, const int32_t* lens, const int64_t* row_offsets,
                             void* k_out, void* v_out, hipStream_t st);
 hipError_t launch_plan(const Params& p, const int32_t* bt, const int32_t* lens, int waves,
                        int64_t desc_capacity, int64_t max_steps, int32_t* header,
-                       int32_t* step_prefix, int4* desc, int2* seg_info, int32_t* seg_count,
-                       hipStream_t st);
+                       int32_t* step_prefix, int4* desc, hipStream_t st);
 PrefillWorkspace map_prefill_workspace(const Params& p, int ncg, int64_t tiles, int64_t slots,
                                        int64_t desc_capacity, int waves);
 int prefill_column_groups(const Params& p, int max_new_tokens);
@@ -247,5 +232,8 @@ hipError_t launch_decode_mfma(const Params& p, int waves, const void* q, const v
 hipError_t launch_decode_valu(const Params& p, int waves, const void* q, const void* k_pool,
                               const void* v_pool, const int32_t* header, const int4* desc,
                               float2* partial_ml, float* partial_acc, hipStream_t st);
+hipError_t launch_merge(const Params& p, const int32_t* header, const int32_t* step_prefix,
+                        const float2* partial_ml, const float* partial_acc, float* out,
+                        float* lse, hipStream_t st);
 
 }  // namespace vox

@@ -58,10 +58,7 @@ struct MfmaMath {
   __device__ static int columns(const Params& p) { return p.G; }
 
   static constexpr int kBuffers = NBUF;
-  static constexpr int kHeadDim = D;
   static constexpr bool kDirect = false;  // every run leaves a partial record for the merge
-  static constexpr bool kSelfMerge = true;
-  static constexpr bool kFusedAppend = !PACKED;
   static constexpr int kStashFloats = 4096;  // 16 KB per wave: several decode records
   static constexpr int kMinWavesPerSimd = 1;
   static constexpr int KK = D / 32;  // score MFMAs per block = V loads per block
@@ -72,10 +69,6 @@ struct MfmaMath {
   };
   struct Regs {
     u32x4 k[2][KK], v[2][KK];
-    // fused append: the newest token's K dims 32kk + 8c .. +8 and V dims 32j + 2n, 32j + 2n + 1
-    // from k_new / v_new, requested with the step that holds the token
-    u32x4 kn[KK];
-    uint32_t vn[KK];
   };
   struct State {
     Q q;
@@ -131,44 +124,6 @@ struct MfmaMath {
     for (int j = 0; j < KK; ++j) r.v[0][j] = kv_load<STREAM>(va + j * 128);
 #pragma unroll
     for (int j = 0; j < KK; ++j) r.v[1][j] = kv_load<STREAM>(vb + j * 128);
-  }
-
-  // Fused append.  The rows of the token appended this step are not in the pools yet: the
-  // step that ends the stream loads them beside its K/V blocks ...
-  __device__ __forceinline__ void issue_new_token(Regs& r, const Desc& dsc) const {
-    const uint16_t* krow = p.k_new + (size_t)dsc.w * D + c * 8;
-    const uint16_t* vrow = p.v_new + (size_t)dsc.w * D + 2 * n;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) r.kn[kk] = *reinterpret_cast<const u32x4*>(krow + 32 * kk);
-#pragma unroll
-    for (int j = 0; j < KK; ++j) r.vn[j] = *reinterpret_cast<const uint32_t*>(vrow + 32 * j);
-  }
-  // ... and puts them where the pools will hold them: token t of a block is row t of the K
-  // operand (lanes n == t) and slot t % 4 of the V quads of lane group t / 4.
-  __device__ __forceinline__ void patch_new_token(Regs& r, const Desc& dsc) const {
-    const int tn = (dsc.z & kMetaTokMask) - 1;
-    const int t = tn & (kBlock - 1), e = t & 3;
-    const uint32_t keep = (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
-    const int sh = (e & 1) * 16;
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-      const bool here = (tn >> 4) == blk;
-      const bool krow = here && n == t, vlo = here && c == (t >> 2) && e < 2,
-                 vhi = here && c == (t >> 2) && e >= 2;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const u32x4 old = r.k[blk][kk], neu = r.kn[kk];
-        r.k[blk][kk] = u32x4{krow ? neu.x : old.x, krow ? neu.y : old.y, krow ? neu.z : old.z,
-                             krow ? neu.w : old.w};
-      }
-#pragma unroll
-      for (int j = 0; j < KK; ++j) {
-        const uint32_t d0 = (r.vn[j] & 0xFFFFu) << sh, d1 = (r.vn[j] >> 16) << sh;
-        const u32x4 v = r.v[blk][j];
-        r.v[blk][j] = u32x4{vlo ? (v.x & keep) | d0 : v.x, vhi ? (v.y & keep) | d0 : v.y,
-                            vlo ? (v.z & keep) | d1 : v.z, vhi ? (v.w & keep) | d1 : v.w};
-      }
-    }
   }
 
   __device__ void reset(State& s) const {

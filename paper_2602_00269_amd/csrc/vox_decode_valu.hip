@@ -56,10 +56,7 @@ struct ValuMath {
   __device__ static int columns(const Params& p) { return p.G; }
 
   static constexpr int kBuffers = 2;
-  static constexpr int kHeadDim = D;
   static constexpr bool kDirect = false;  // every run leaves a partial record for the merge
-  static constexpr bool kSelfMerge = true;
-  static constexpr bool kFusedAppend = false;  // the append is a launch of its own on this path
   static constexpr int kStashFloats = 4096;  // 16 KB per wave: several decode records
   static constexpr int kMinWavesPerSimd = 2;
   static constexpr int NL = D / 32;  // 16-byte loads per lane per granule

@@ -79,9 +79,6 @@ struct MqMath {
   static constexpr int kBuffers = NBUF;
   // a run that is its whole segment writes finished rows instead of a partial record
   static constexpr bool kDirect = true;
-  static constexpr bool kSelfMerge = false;    // the multi-token step has its own merge kernel
-  static constexpr bool kFusedAppend = false;
-  static constexpr int kHeadDim = D;
   // 39 KB per wave (all four waves: 156 of the CU's 160 KB): 4, 2, 1 records at head_dim 128
   // with 1, 2, 4 column groups; 9, 4, 2, 1 at head_dim 64 with 1, 2, 4, 8.  With the query rows
   // in LDS there is no room for records: they go straight to global memory.
