@@ -796,7 +796,8 @@ int prefill_column_groups(const Params& p, int max_new_tokens) {
   const int want = (max_new_tokens + tq - 1) / tq;  // groups the longest stream fills
   // Six groups (query rows in LDS, records straight to global memory) cost more per step than
   // four; they pay only where they save a second pass over the context: 5 or 6 groups wanted.
-  if (p.D == 128 && (want == 5 || want == 6)) return 6;
+  if (p.D == 128 && want == 5) return 5;
+  if (p.D == 128 && want == 6) return 6;
   // register budget: eight groups at head_dim 64, four at head_dim 128
   const int most = p.D == 64 ? 8 : 4;
   // fewest tiles first (each tile streams the context again), then the smallest kernel that
@@ -865,6 +866,8 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
     if (p.D == 128) {
       if (ncg == 6)
         launch_mq<128, 2, 6, true>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
+      else if (ncg == 5)
+        launch_mq<128, 2, 5, true>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc, st);
       else if (ncg == 4 && reuse)
         launch_mq<128, 2, 4, false, true>(pk, grid, q, k_pool, v_pool, header, desc, pml, pacc,
                                           st);

@@ -729,6 +729,7 @@ PREFILL_CASES = [
     ([50, 90, 400], [8, 5, 1], 8, 2, 64),                          # two groups, D = 64
     ([50, 90, 400], [16, 13, 2], 8, 2, 64),                        # four groups, D = 64
     ([300, 90, 1000], [25, 21, 30], 24, 8, 128),                   # six groups (query rows in LDS), D = 128
+    ([300, 90, 1000, 25], [25, 21, 22, 25], 24, 8, 128),           # five groups (query rows in LDS), D = 128
 ]
 
 
