@@ -191,3 +191,28 @@ def test_sample_weights_add_up_to_what_the_sampler_keeps():
                     pick = j
                     break
             assert toks[i] == order[pick], (top_p, k, i)
+
+
+def test_weight_polynomial_is_the_taylor_series_of_the_exponential():
+    # the ten constants of the weight function, read from the oracle's source, are the Taylor
+    # coefficients (-ln 2)^k / k! of 2^-f rounded to fp32, highest degree first (Horner form):
+    # nothing fitted or tuned hides in them
+    import os
+    import re
+
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "vox_oracle_sample.c")).read()
+    body = src[src.index("uint64_t vox_oracle_sample_weight(float d)"):]
+    body = body[:body.index("\n}\n")]
+    consts = [float.fromhex(c) for c in re.findall(r"(-?0x1\.[0-9a-f]+p[+-]\d+)f", body)]
+    assert np.float32(consts[0]) == np.float32(1.4426950408889634)  # log2(e), scales d
+    coeffs = consts[1:]
+    assert len(coeffs) == 9 and body.count("fmaf(p, f,") == 9 and "fmaf(p, f, 1.0f)" in body
+    ln2 = math.log(2.0)
+    for i, c in enumerate(coeffs):
+        k = 9 - i
+        want = (-ln2) ** k / math.factorial(k)
+        # rounded to fp32, give or take the last bits (the series may have been rounded after a
+        # final adjustment of the truncated tail): well inside 1e-6 relative of the series term
+        assert abs(c - want) <= abs(want) * 2e-6, (k, c, want)
+    # degree 9 on [0, 1): the first neglected term bounds the truncation error far below 2^-24
+    assert ln2 ** 10 / math.factorial(10) < 2.0 ** -25
