@@ -311,12 +311,14 @@ def bench_sample(args, dev) -> int:
     return 0
 
 
-def bench_decode(args, dev, workload, full=True):
+def bench_decode(args, dev, workload, full=True, layerwise=False):
     """One decode-step workload: region A times the whole step through the production entry
     point (wall clock over all steps for the mean, HIP events between the steps for the median),
     region B the attention kernel alone between HIP events.  ``full`` adds the wave clocks, the
     read-ceiling probe and the CPU baseline and returns the whole bench line; otherwise a short
-    record for the ``also`` list."""
+    record for the ``also`` list.  ``layerwise``: the step as a backbone would issue it, one plan
+    and then one call per layer (vox_decode_plan + vox_decode_layer), instead of vox_decode_step,
+    whose launches carry the neighbouring layer's append."""
     import copy
 
     import numpy as np
@@ -359,7 +361,14 @@ def bench_decode(args, dev, workload, full=True):
                      for w, o in zip(sets, outs)]
 
     def eager_step(i):
-        if args.rope:
+        if layerwise:
+            a = sets[i % copies]
+            o = outs[i % copies]
+            binding.decode_plan(sh, bt, lens, ws, context_lens_host=host_lens)
+            for l in range(base.layers):
+                binding.decode_layer(sh, l, a.q[l], a.k_new[l], a.v_new[l], a.k_pool[l],
+                                     a.v_pool[l], bt, lens, o[l], ws, context_lens_host=host_lens)
+        elif args.rope:
             binding.decode_step_rope(sh, step_args[i % copies], bt, lens, ws,
                                      context_lens_host=host_lens)
         else:
@@ -433,6 +442,7 @@ def bench_decode(args, dev, workload, full=True):
     if not full:  # a line of the `also` list: the whole step and the attention kernel
         return {
             "workload": base.name, "streams": base.num_streams, "layers": base.layers,
+            "entry": "vox_decode_plan + vox_decode_layer per layer" if layerwise else "vox_decode_step",
             "kv_bytes_per_step": kv_bytes_step, "value": round(value, 1), "unit": "GB/s",
             "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(ms_median, 4),
             "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
@@ -574,6 +584,7 @@ def bench_decode(args, dev, workload, full=True):
             "host_lens": bool(args.host_lens),
             "hip_graph": bool(args.hip_graph),
             "rope_fused_append": bool(args.rope),
+            "layerwise": bool(layerwise),
         },
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "stream_steps_per_s": round(base.num_streams / (ms_per_step * 1e-3), 1),
@@ -613,6 +624,8 @@ def main() -> int:
                          "the append (inputs are packed QKV rows)")
     ap.add_argument("--no-read-ceiling", action="store_true",
                     help="skip the 4 GiB streaming-read probe that measures the chip's read ceiling")
+    ap.add_argument("--layerwise", action="store_true",
+                    help="time the step as one vox_decode_plan and a vox_decode_layer call per layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true",
                     help="headline workload only: skip the cfg4 / cfg2 / cfg5 records of the default run")
@@ -639,7 +652,7 @@ def main() -> int:
         return bench_multi(args, dev)
     if args.workload in SAMPLE_WORKLOADS:
         return bench_sample(args, dev)
-    line = bench_decode(args, dev, args.workload)
+    line = bench_decode(args, dev, args.workload, layerwise=args.layerwise)
     if args.workload == "cfg3" and not args.no_also:
         # the other decode presets in the same run: the 512-stream target config, the small
         # batch the paper's models run at, and the 28-layer full step
@@ -650,6 +663,9 @@ def main() -> int:
             gc.collect()
             torch.cuda.empty_cache()
             line["also"].append(bench_decode(args, dev, other, full=False))
+        gc.collect()
+        torch.cuda.empty_cache()
+        line["also"].append(bench_decode(args, dev, "cfg5", full=False, layerwise=True))
     print(json.dumps(line))
     return 0
 

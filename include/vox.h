@@ -225,6 +225,27 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
                     size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The same step one layer at a time, for a backbone whose other kernels (projections, MLP) run
+ * between the attention calls of consecutive layers (paper Section 3.1, LLM Forward: the
+ * attention backend is called once per layer).  vox_decode_plan builds the split-K step
+ * descriptors of this step's block_tables / context_lens once; vox_decode_layer then runs
+ * vox_kv_append (skipped when k_new and v_new are both NULL) and the attention of one layer on
+ * that plan.  `layer` in [0, 4096) names the layer (each has its own counter of the shared
+ * range pool, set to zero by the plan): within one step, call every layer index at most once
+ * after the plan.  Shape, block_tables, context_lens, context_lens_host, workspace and stream
+ * must be the ones given to vox_decode_plan, and the workspace must not be used by anything
+ * else between the plan and the step's last layer.  Results equal vox_decode_step's bit for
+ * bit; lse may be NULL.  Graph capture: as for vox_paged_decode (the host copy is ignored).
+ */
+int vox_decode_plan(const vox_shape_t* shape, const int32_t* block_tables,
+                    const int32_t* context_lens, const int32_t* context_lens_host, void* workspace,
+                    size_t workspace_bytes, void* hip_stream);
+int vox_decode_layer(const vox_shape_t* shape, int32_t layer, const void* q, const void* k_new,
+                     const void* v_new, void* k_pool, void* v_pool, const int32_t* block_tables,
+                     const int32_t* context_lens, const int32_t* context_lens_host, float* out,
+                     float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Fused step input (the paper puts the whole LLM Forward stage on one captured fast path,
  * Section 3.1.1, so the small steps between the QKV projection and the attention call are
  * folded into the append): rotary position embedding of q and k, split of the packed rows,

@@ -70,6 +70,10 @@ def load() -> ctypes.CDLL:
     lib.vox_paged_decode_static.restype = ctypes.c_int
     lib.vox_decode_step.argtypes = [sp, i32] + [vp] * 10 + [ctypes.c_size_t, vp]
     lib.vox_decode_step.restype = ctypes.c_int
+    lib.vox_decode_plan.argtypes = [sp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.vox_decode_plan.restype = ctypes.c_int
+    lib.vox_decode_layer.argtypes = [sp, i32] + [vp] * 11 + [ctypes.c_size_t, vp]
+    lib.vox_decode_layer.restype = ctypes.c_int
     lib.vox_rope_append.argtypes = [sp, vp, vp, vp, i32] + [vp] * 6
     lib.vox_rope_append.restype = ctypes.c_int
     lib.vox_decode_step_rope.argtypes = [sp, i32, vp, vp, vp, i32] + [vp] * 8 + [ctypes.c_size_t, vp]
@@ -243,6 +247,34 @@ def decode_step(shape, args: StepArgs, block_tables, context_lens, workspace,
                                 _stream(stream))
     del keep
     _check(rc, "vox_decode_step")
+
+
+def decode_plan(shape, block_tables, context_lens, workspace, context_lens_host=None, stream=None):
+    """Split-K descriptors of one step, shared by the ``decode_layer`` calls that follow."""
+    i32 = torch.int32
+    keep, host = _host_lens(context_lens_host)
+    rc = load().vox_decode_plan(ctypes.byref(shape), _dev(block_tables, i32, "block_tables"),
+                                _dev(context_lens, i32, "context_lens"), host,
+                                _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                _stream(stream))
+    del keep
+    _check(rc, "vox_decode_plan")
+
+
+def decode_layer(shape, layer, q, k_new, v_new, k_pool, v_pool, block_tables, context_lens, out,
+                 workspace, lse=None, context_lens_host=None, stream=None):
+    """Append (unless ``k_new`` / ``v_new`` are None) and attention of one layer on the plan."""
+    bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+    keep, host = _host_lens(context_lens_host)
+    rc = load().vox_decode_layer(
+        ctypes.byref(shape), int(layer), _dev(q, bf, "q"), _dev(k_new, bf, "k_new", optional=True),
+        _dev(v_new, bf, "v_new", optional=True), _dev(k_pool, bf, "k_pool"),
+        _dev(v_pool, bf, "v_pool"), _dev(block_tables, i32, "block_tables"),
+        _dev(context_lens, i32, "context_lens"), host, _dev(out, f32, "out"),
+        _dev(lse, f32, "lse", optional=True), _dev(workspace, torch.uint8, "workspace"),
+        workspace.numel(), _stream(stream))
+    del keep
+    _check(rc, "vox_decode_layer")
 
 
 def rope_append(shape, qkv, rope_cos, rope_sin, q_out, k_pool, v_pool, block_tables,

@@ -408,6 +408,50 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
   return VOX_OK;
 }
 
+int vox_decode_plan(const vox_shape_t* shape, const int32_t* block_tables,
+                    const int32_t* context_lens, const int32_t* context_lens_host, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+  if (int rc = validate(shape)) return rc;
+  if (!block_tables || !context_lens || !workspace) return VOX_ERR_NULL;
+  if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
+  Plan plan;
+  if (int rc = make_plan(shape, lens_for_planning(context_lens_host, st), workspace_bytes, &plan))
+    return rc;
+  Params p = make_params(shape);
+  p.pool_counter = pool_counter(plan, (char*)workspace, 0);  // the plan zeroes every layer's counter
+  return enqueue_plan(p, plan, (char*)workspace, block_tables, context_lens, st);
+}
+
+int vox_decode_layer(const vox_shape_t* shape, int32_t layer, const void* q, const void* k_new,
+                     const void* v_new, void* k_pool, void* v_pool, const int32_t* block_tables,
+                     const int32_t* context_lens, const int32_t* context_lens_host, float* out,
+                     float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (int rc = validate(shape)) return rc;
+  if (layer < 0 || layer >= kMaxLayers) return VOX_ERR_ARG;
+  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !out || !workspace)
+    return VOX_ERR_NULL;
+  if ((k_new == nullptr) != (v_new == nullptr)) return VOX_ERR_NULL;
+  if ((uintptr_t)workspace % 256 || !all_aligned16(q, k_pool, v_pool, out)) return VOX_ERR_ARG;
+  if (k_new && !all_aligned16(k_new, v_new)) return VOX_ERR_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
+  Plan plan;
+  if (int rc = make_plan(shape, lens_for_planning(context_lens_host, st), workspace_bytes, &plan))
+    return rc;
+  Params p = make_params(shape);
+  char* ws = (char*)workspace;
+  p.pool_counter = pool_counter(plan, ws, layer);
+  set_step_hints(&p, plan);
+  const WsPtrs w = ws_ptrs(plan, ws);
+  if (k_new && launch_append(p, plain_append(k_new, v_new, k_pool, v_pool), block_tables,
+                             context_lens, st) != hipSuccess)
+    return VOX_ERR_HIP;
+  if (int rc = enqueue_attention(shape, p, plan, w, q, k_pool, v_pool, st)) return rc;
+  return launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out, lse, st) == hipSuccess
+             ? VOX_OK
+             : VOX_ERR_HIP;
+}
+
 int vox_read_probe(const void* buf, size_t bytes, void* sink, void* hip_stream) {
   if (!buf || !sink) return VOX_ERR_NULL;
   if (bytes == 0 || bytes % 16 || (uintptr_t)buf % 16) return VOX_ERR_ARG;

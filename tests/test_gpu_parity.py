@@ -407,6 +407,63 @@ def _pack_rows_fast(k_rows, v_rows, tables, num_blocks, hkv, d):
     return kp, vp
 
 
+def test_layer_by_layer_step_equals_whole_step(dev):
+    # one plan, then a call per layer (what a backbone does whose projections run between the
+    # attention calls): outputs and pools equal vox_decode_step's bit for bit, with and without
+    # the host copy of the lengths, with pool ranges active and not; the log-sum-exp and the
+    # outputs against the oracle
+    small = synth.make_workload(1, device=dev, layers=3)
+    big = synth.make_custom(_pool_range_lens(430), 24, 8, 128, seed=430, device=dev)
+    for w in (small, big):
+        layers = w.layers
+        sh = binding.shape_of(w)
+        bt, lens = _i32(w.block_tables, dev), _i32(w.context_lens, dev)
+        shape = (w.num_streams, w.num_q_heads, w.head_dim)
+        pools0 = [(k.clone(), v.clone()) for k, v in zip(w.k_pool, w.v_pool)]
+        outs = [torch.full(shape, float("nan"), device=dev) for _ in range(layers)]
+        ws = binding.alloc_workspace(sh, dev)
+        binding.decode_step(sh, binding.StepArgs(w.q, w.k_new, w.v_new, w.k_pool, w.v_pool, outs),
+                            bt, lens, ws, context_lens_host=w.context_lens)
+        torch.cuda.synchronize()
+        want = [(o.clone(), k.clone(), v.clone()) for o, k, v in zip(outs, w.k_pool, w.v_pool)]
+        for host in (w.context_lens, None):
+            for (k0, v0), k, v in zip(pools0, w.k_pool, w.v_pool):
+                k.copy_(k0)
+                v.copy_(v0)
+            ws.fill_(0xFF)
+            lses = [torch.full(shape[:2], float("nan"), device=dev) for _ in range(layers)]
+            for o in outs:
+                o.fill_(float("nan"))
+            binding.decode_plan(sh, bt, lens, ws, context_lens_host=host)
+            for l in range(layers):
+                # other work of the layer would run here; scribble on an unrelated buffer
+                torch.zeros(1 << 16, device=dev).add_(1.0)
+                binding.decode_layer(sh, l, w.q[l], w.k_new[l], w.v_new[l], w.k_pool[l],
+                                     w.v_pool[l], bt, lens, outs[l], ws, lse=lses[l],
+                                     context_lens_host=host)
+            torch.cuda.synchronize()
+            for l in range(layers):
+                assert torch.equal(outs[l], want[l][0]), f"{w.name} layer {l}: output"
+                assert torch.equal(w.k_pool[l].view(torch.int16), want[l][1].view(torch.int16))
+                assert torch.equal(w.v_pool[l].view(torch.int16), want[l][2].view(torch.int16))
+        for l in (0, layers - 1):
+            sample = range(w.num_streams) if w.num_streams <= 8 else (0, 2, 3, 159)
+            for s in sample:
+                ref, ref_lse = oracle.paged_decode(bits_of(w.q[l]), bits_of(w.k_pool[l]),
+                                                   bits_of(w.v_pool[l]), w.block_tables,
+                                                   w.context_lens, w.scale,
+                                                   num_kv_heads=w.num_kv_heads, streams=(s, s + 1))
+                _assert_close(outs[l].cpu().numpy()[s:s + 1], ref, f"{w.name} layer {l} stream {s}")
+                _assert_lse(lses[l].cpu().numpy()[s:s + 1], ref_lse, f"{w.name} layer {l} stream {s}")
+        # a layer call without new rows attends over the cache as it is
+        out2 = torch.full(shape, float("nan"), device=dev)
+        binding.decode_plan(sh, bt, lens, ws, context_lens_host=w.context_lens)
+        binding.decode_layer(sh, 0, w.q[0], None, None, w.k_pool[0], w.v_pool[0], bt, lens, out2,
+                             ws, context_lens_host=w.context_lens)
+        torch.cuda.synchronize()
+        assert torch.equal(out2, want[0][0])
+
+
 def test_decode_step_replays_from_a_hip_graph(dev):
     # The step only enqueues kernels with length-independent attention grids, so it can be
     # captured once and replayed with new queries / new tokens in the same buffers.  Each replay

@@ -31,7 +31,9 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"vox_kv_append", "vox_kv_gather", "vox_paged_decode", "vox_decode_step",
             "vox_paged_decode_workspace_bytes", "vox_paged_decode_profiled", "vox_strerror",
             "vox_kv_append_multi", "vox_paged_prefill", "vox_paged_prefill_profiled",
-            "vox_paged_prefill_workspace_bytes", "vox_rope_append", "vox_decode_step_rope", "vox_sample", "vox_sample_weights"} <= set(names)
+            "vox_paged_prefill_workspace_bytes", "vox_rope_append", "vox_decode_step_rope", "vox_sample",
+            "vox_sample_weights", "vox_paged_decode_static", "vox_decode_plan",
+            "vox_decode_layer"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -153,6 +155,42 @@ def test_sampling_call_validates_on_the_host(lib):
     assert lib.vox_sample(4, 100, one, one, None, 8, one, one, None, None) == -1  # window without history
     assert lib.vox_sample_weights(4, 100, one, one, None, 0, None, one, None) == -1
     assert ctypes.sizeof(ctypes.c_float) * 3 + 4 == 16  # vox_sampling_t: three floats and an int32
+
+
+def test_layer_by_layer_and_static_calls_validate_on_the_host(lib):
+    sh = _shape()
+    one, odd = ctypes.c_void_p(256), ctypes.c_void_p(264)
+    big = 1 << 20
+    # plan: null pointers, misaligned or too small workspace, bad shape
+    assert lib.vox_decode_plan(ctypes.byref(sh), None, one, None, one, big, None) == -1
+    assert lib.vox_decode_plan(ctypes.byref(sh), one, one, None, None, big, None) == -1
+    assert lib.vox_decode_plan(ctypes.byref(sh), one, one, None, ctypes.c_void_p(257), big, None) == -5
+    assert lib.vox_decode_plan(ctypes.byref(sh), one, one, None, one, 64, None) == -3
+    assert lib.vox_decode_plan(ctypes.byref(_shape(head_dim=96)), one, one, None, one, big, None) == -2
+    # layer: index range, pointers, k_new without v_new, alignment, workspace
+    args = [one] * 7 + [None, one, None, one, big, None]  # q k_new v_new k_pool v_pool bt lens | host out lse ws bytes stream
+    assert lib.vox_decode_layer(ctypes.byref(sh), -1, *args) == -5
+    assert lib.vox_decode_layer(ctypes.byref(sh), 4096, *args) == -5
+    for missing in (0, 3, 4, 5, 6, 8, 10):
+        a = list(args)
+        a[missing] = None
+        assert lib.vox_decode_layer(ctypes.byref(sh), 0, *a) == -1, missing
+    a = list(args)
+    a[2] = None  # v_new without k_new's partner
+    assert lib.vox_decode_layer(ctypes.byref(sh), 0, *a) == -1
+    for bad in (0, 1, 3, 8):
+        a = list(args)
+        a[bad] = odd
+        assert lib.vox_decode_layer(ctypes.byref(sh), 0, *a) == -5, bad
+    a = list(args)
+    a[11] = 64
+    assert lib.vox_decode_layer(ctypes.byref(sh), 0, *a) == -3
+    # the static-scratch call checks its arguments before it looks for a device
+    assert lib.vox_paged_decode_static(ctypes.byref(sh), None, one, one, one, one, None, one, None,
+                                       None) == -1
+    assert lib.vox_paged_decode_static(ctypes.byref(_shape(num_streams=0)), one, one, one, one, one,
+                                       None, one, None, None) == -2
+    assert binding.strerror(-6)
 
 
 def test_workspace_too_small_is_reported(lib):
