@@ -91,3 +91,35 @@ def test_static_scratch_decode_refuses_what_does_not_fit(dev):
                                 context_lens_host=np.zeros(8192, dtype=np.int32))
     torch.cuda.synchronize()
     assert bool((out == 0).all())
+
+
+def test_static_scratch_decode_replays_from_a_graph(dev):
+    # the callers it is for include code under graph capture: captured after one eager call on
+    # the device (which looks up the scratch array), replayed while the device lengths grow
+    lens0 = np.array([33, 0, 700, 64, 1, 255, 17, 31], dtype=np.int32)
+    w = synth.make_custom(np.where(lens0 > 0, lens0 + 3, 0), 24, 8, 128, seed=434, device=dev)
+    sh = binding.shape_of(w)
+    bt, lens_d = _i32(w.block_tables, dev), _i32(lens0, dev)
+    out = torch.full((w.num_streams, w.num_q_heads, w.head_dim), float("nan"), device=dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        binding.paged_decode_static(sh, w.q[0], w.k_pool[0], w.v_pool[0], bt, lens_d, out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        binding.paged_decode_static(sh, w.q[0], w.k_pool[0], w.v_pool[0], bt, lens_d, out,
+                                    context_lens_host=lens0)  # ignored under capture
+    lens = lens0.copy()
+    for rep in range(3):
+        lens = np.where(lens > 0, lens + 1, 0).astype(np.int32)
+        lens_d.copy_(torch.from_numpy(lens))
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref, _ = oracle.paged_decode(bits_of(w.q[0]), bits_of(w.k_pool[0]), bits_of(w.v_pool[0]),
+                                     w.block_tables, lens, w.scale, num_kv_heads=w.num_kv_heads)
+        err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+        assert np.isfinite(out.cpu().numpy()).all() and err.max() <= 5e-3 and err.mean() <= 5e-4, rep
