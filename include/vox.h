@@ -170,7 +170,9 @@ int vox_paged_decode(const vox_shape_t* shape, const void* q, const void* k_pool
  * descriptors and partial records go to a built-in device array of VOX_STATIC_SCRATCH_BYTES
  * (64 MiB) that each GPU the library runs on holds until the process ends.  The call allocates
  * nothing and frees nothing.  Its very first use on a device looks up that device's copy of the
- * array (hipGetSymbolAddress; make that first call outside graph capture).
+ * array (hipGetSymbolAddress; make that first call outside graph capture).  The array used is
+ * the current device's (hipGetDevice): hip_stream must belong to the current device, as for
+ * every launch.
  * Size limit: the call needs what vox_paged_decode_workspace_bytes(shape) reports (or, with
  * context_lens_host outside capture, the smaller amount the actual 32-token steps need); when
  * that exceeds VOX_STATIC_SCRATCH_BYTES it returns VOX_ERR_SCRATCH and launches nothing
