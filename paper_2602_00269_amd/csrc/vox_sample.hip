@@ -1,6 +1,6 @@
 // Sampling step: logits -> next token per stream (repetition penalty, temperature, top-k, top-p,
-// draw), one workgroup per stream (1024 threads, or 512 for vocabularies up to 32768 so that two
-// streams share a CU), everything besides the logits in LDS.
+// draw), one workgroup per stream (1024 threads, or 256 for vocabularies up to 16384 so that
+// four streams share a CU), everything besides the logits in LDS.
 //
 // The token is decided by exact arithmetic: every float step is a single IEEE fp32 operation
 // in a fixed order (contraction is off in this file's arithmetic helpers), softmax weights are
@@ -33,7 +33,6 @@ constexpr int kIdBits = 18;  // vocabulary of at most 2^18 tokens
 constexpr int kMaxVocab = 1 << kIdBits;
 constexpr int kKeyBits = 31 + kIdBits;
 constexpr int kLevels = 5;
-constexpr int kBins = 2048;
 constexpr int kQuadMinVocab = 16384;  // below this a thread has too few tokens for quads to pay
 
 // Workgroup shapes.  Results do not depend on them (the candidate limits only decide which of
@@ -42,23 +41,33 @@ struct AnyVocab {  // one workgroup per CU
   static constexpr int kThreads = 1024;
   static constexpr int kVocab = kMaxVocab;  // largest vocabulary: sizes the window bitmap
   static constexpr int kCandidates = 4096;  // tokens of a bucket / of the near range kept in LDS
+  static constexpr int kBins = 2048;        // bins of a histogram: 2^(widest digit)
+  // digits of the 49-bit key, most significant first: 11 + 10 + 10 + 9 + 9 bits
+  static __device__ constexpr int width(int level) { return level == 0 ? 11 : level < 3 ? 10 : 9; }
+  static __device__ constexpr int shift(int level) {
+    return level == 0 ? 38 : level == 1 ? 28 : level == 2 ? 18 : level == 3 ? 9 : 0;
+  }
 };
-struct SmallVocab {  // 68 KB of LDS and half the threads: two workgroups per CU, whose short
-                     // dependent phases then overlap
-  static constexpr int kThreads = 512;
-  static constexpr int kVocab = 32768;
-  static constexpr int kCandidates = 2048;
+struct SmallVocab {  // a few thousand tokens per stream are little work: a quarter of the
+                     // threads and under 40 KB of LDS, so that four workgroups share a CU and a
+                     // batch of a thousand streams is resident at once
+  static constexpr int kThreads = 256;
+  static constexpr int kVocab = 16384;
+  static constexpr int kCandidates = 1536;
+  static constexpr int kBins = 1024;
+  // 10 + 10 + 10 + 10 + 9 bits
+  static __device__ constexpr int width(int level) { return level < 4 ? 10 : 9; }
+  static __device__ constexpr int shift(int level) { return level < 4 ? 39 - 10 * level : 0; }
 };
-
-__device__ constexpr int kWidth[kLevels] = {11, 10, 10, 9, 9};
-__device__ constexpr int kShift[kLevels] = {38, 28, 18, 9, 0};
 
 // 2^40 * exp(-d): x = d * log2(e); n = floor(x), f = x - n; p = Taylor polynomial of 2^-f of
 // degree 9 (Horner, fused multiply-adds); q = trunc(p * 2^24); result (q << 16) >> n.
 __device__ inline uint64_t weight_of(float d) {
 #pragma clang fp contract(off)
-  const float x = d * 0x1.715476p+0f;
-  if (!(x < 64.0f)) return 0;
+  // No branch: from x = 41 on the shift leaves nothing of q's 25 bits, so x is clamped to 63
+  // (NaN included) and the result is zero as the definition asks for x >= 64.
+  const float x0 = d * 0x1.715476p+0f;
+  const float x = x0 < 63.0f ? x0 : 63.0f;
   const float nf = __builtin_floorf(x);
   const int n = (int)nf;
   const float f = x - nf;
@@ -107,6 +116,17 @@ __device__ inline uint64_t key_of(const StreamCtx& c, int v, float z, uint32_t w
   return (dkey << kIdBits) | (uint32_t)v;
 }
 
+__device__ inline uint64_t key_from(float d, int v) {
+  const uint64_t dkey = __builtin_bit_cast(uint32_t, d) & 0x7FFFFFFFu;
+  return (dkey << kIdBits) | (uint32_t)v;
+}
+// d of a token outside the window: max - z / T
+__device__ inline float plain_distance(const StreamCtx& c, float z) {
+#pragma clang fp contract(off)
+  const float y = z * c.invT;
+  return c.m - y;
+}
+
 __device__ inline float d_of_key(uint64_t comp) {
   return __builtin_bit_cast(float, (uint32_t)(comp >> kIdBits));
 }
@@ -119,10 +139,9 @@ struct Located {
 constexpr float kBucketsPerUnit = 64.0f;
 constexpr float kNearRange = 8.0f;
 constexpr int kNearBuckets = 512;  // kNearRange * kBucketsPerUnit
-constexpr float kCountRange = 32.0f;  // kBins / kBucketsPerUnit: counts are kept out to here
 
 
-__device__ inline int bucket_of(float d) { return (int)(d * kBucketsPerUnit); }  // d in [0, 32)
+__device__ inline int bucket_of(float d) { return (int)(d * kBucketsPerUnit); }  // d in [0, kCountRange)
 
 // First index i in [0, n) with cum[i] >= thr (n if none).
 __device__ inline int first_reaching(const unsigned long long* cum, int n,
@@ -146,6 +165,8 @@ static constexpr int kThreads = Cfg::kThreads;
 static constexpr int kWaves = kThreads / 64;
 static constexpr int kCandidates = Cfg::kCandidates;
 static constexpr int kSuperset = Cfg::kCandidates;
+static constexpr int kBins = Cfg::kBins;
+static constexpr float kCountRange = kBins / kBucketsPerUnit;  // counts are kept out to here
 
 // Calls f(v, z[v], bitmap word of v) for every token of the stream, this thread's share, in
 // no particular order (nothing the callers compute depends on it); the logits of several
@@ -192,6 +213,33 @@ static __device__ inline void for_each_token(const Ctx& c, F f) {
         if (v < c.V) f(v, z[e], c.seen ? c.seen[v >> 5] : 0u);
       }
     }
+  }
+}
+
+// Calls f(v, four logits from token v on, bitmap word of v) for this thread's quads of a row
+// read in quads; the next quads are requested before the current ones are worked on.
+template <class Ctx, class F>
+static __device__ inline void for_each_quad(const Ctx& c, F f) {
+  constexpr int kQuads = 2;
+  const float4* z4 = reinterpret_cast<const float4*>(c.z);
+  const int quads = c.V >> 2;
+  if (quads <= 0) return;
+  // a quad past the end is never used: its load reads the row's last quad instead, so that
+  // every load is one unconditional 16-byte access
+  const int last = quads - 1;
+  float4 cur[kQuads], next[kQuads];
+#pragma unroll
+  for (int e = 0; e < kQuads; ++e) cur[e] = z4[min((int)threadIdx.x + e * kThreads, last)];
+  for (int q0 = threadIdx.x; q0 < quads; q0 += kThreads * kQuads) {
+#pragma unroll
+    for (int e = 0; e < kQuads; ++e) next[e] = z4[min(q0 + (kQuads + e) * kThreads, last)];
+#pragma unroll
+    for (int e = 0; e < kQuads; ++e) {
+      const int q = q0 + e * kThreads;
+      if (q < quads) f(4 * q, cur[e], c.seen ? c.seen[q >> 3] : 0u);
+    }
+#pragma unroll
+    for (int e = 0; e < kQuads; ++e) cur[e] = next[e];
   }
 }
 
@@ -279,7 +327,7 @@ static __device__ Located locate(Lds& s, const Ctx& c, bool by_mass, unsigned lo
   bool in_lds = false;
   uint32_t n_cand = 0;
   for (int level = 0; level < kLevels; ++level) {
-    const int width = kWidth[level], shift = kShift[level];
+    const int width = Cfg::width(level), shift = Cfg::shift(level);
     const uint32_t* cnt = s.cnt;
     const unsigned long long* mass = s.mass;
     if (level == 0) {  // built once per stream
@@ -352,9 +400,12 @@ static __device__ Ctx open_stream(Lds& s, int V, const float* __restrict__ logit
   c.invT = (prm.temperature > 0.0f) ? 1.0f / prm.temperature : 1.0f;
   c.seen = nullptr;
   if (window > 0) {
+    // the first window entries are requested before the barrier, not after it
+    const int32_t first = tid < window ? history[(size_t)stream * window + tid] : -1;
     for (int i = tid; i < (V + 31) / 32; i += kThreads) s.seen[i] = 0;
     __syncthreads();
-    for (int j = tid; j < window; j += kThreads) {
+    if (first >= 0 && first < V) atomicOr(&s.seen[first >> 5], 1u << (first & 31));
+    for (int j = tid + kThreads; j < window; j += kThreads) {
       const int32_t v = history[(size_t)stream * window + j];
       if (v >= 0 && v < V) atomicOr(&s.seen[v >> 5], 1u << (v & 31));
     }
@@ -404,7 +455,7 @@ static __device__ void build_key_histogram(Lds& s, const Ctx& c) {
   for_each_token(c, [&](int v, float z, uint32_t word) {
     float d;
     const uint64_t comp = key_of(c, v, z, word, &d);
-    const uint32_t b = (uint32_t)(comp >> kShift[0]);
+    const uint32_t b = (uint32_t)(comp >> Cfg::shift(0));
     atomicAdd(&s.cnt0[b], 1u);
     const unsigned long long w = weight_of(d);
     if (w) atomicAdd(&s.mass[kBins + b], w);
@@ -478,21 +529,50 @@ static __device__ void sample_body(
   if (tid == 0) s.n_cand = 0;
   __syncthreads();
   unsigned long long far_mass = 0;
-  for_each_token(c, [&](int v, float z, uint32_t word) {
-    float d;
-    const uint64_t comp = key_of(c, v, z, word, &d);
-    const unsigned long long w = weight_of(d);
+  const auto place = [&](int v, float d, unsigned long long w) {
     if (d < kNearRange) {
       const int b = bucket_of(d);
       atomicAdd(&s.cnt0[b], 1u);
       atomicAdd(&s.mass[kBins + b], w);
       const uint32_t slot = atomicAdd(&s.n_cand, 1u);
-      if (slot < (uint32_t)kSuperset) s.cand[slot] = comp;
+      if (slot < (uint32_t)kSuperset) s.cand[slot] = key_from(d, v);
     } else {
       far_mass += w;
       if (use_k && d < kCountRange) atomicAdd(&s.cnt0[bucket_of(d)], 1u);
     }
-  });
+  };
+  if constexpr (QUAD) {
+    // Nearly every quad lies outside the window and beyond the ranges that are bucketed: one
+    // test each per quad, and the four weights are added without a branch.
+    const float bucketed = use_k ? kCountRange : kNearRange;
+    for_each_quad(c, [&](int v, const float4& z4, uint32_t word) {
+      const float z[4] = {z4.x, z4.y, z4.z, z4.w};
+      float d[4];
+      unsigned long long w[4];
+      if ((word >> (v & 28)) & 0xFu) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) (void)key_of(c, v + e, z[e], word, &d[e]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) d[e] = plain_distance(c, z[e]);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[e] = weight_of(d[e]);
+      const float nearest = fminf(fminf(d[0], d[1]), fminf(d[2], d[3]));
+      if (nearest < bucketed) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) place(v + e, d[e], w[e]);
+      } else {
+        far_mass += (w[0] + w[1]) + (w[2] + w[3]);
+      }
+    });
+  } else {
+    for_each_token(c, [&](int v, float z, uint32_t word) {
+      float d;
+      (void)key_of(c, v, z, word, &d);
+      place(v, d, weight_of(d));
+    });
+  }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) far_mass += __shfl_xor(far_mass, o);
   if (lane == 0) s.wave_cnt[wv] = far_mass;
@@ -554,11 +634,23 @@ static __device__ void sample_body(
     }
     __syncthreads();
     const int m = (int)s.n_cand;
+    if (m <= kThreads) {
+      // few keys (the usual case under a top-k cut): a thread's key goes where the number of
+      // smaller keys says (keys are distinct), two barriers instead of a sorting network's dozens
+      const unsigned long long mine = tid < m ? keys[tid] : 0ull;
+      int rank = 0;
+      for (int j = 0; j < m; ++j) rank += keys[j] < mine ? 1 : 0;
+      __syncthreads();
+      if (tid < m) keys[rank] = mine;
+      __syncthreads();
+    }
     int np2 = 64;
     while (np2 < m) np2 <<= 1;
-    for (int i = m + tid; i < np2; i += kThreads) keys[i] = ~0ull;
-    __syncthreads();
-    for (int k = 2; k <= np2; k <<= 1) {
+    if (m > kThreads) {
+      for (int i = m + tid; i < np2; i += kThreads) keys[i] = ~0ull;
+      __syncthreads();
+    }
+    for (int k = 2; m > kThreads && k <= np2; k <<= 1) {
       for (int j = k >> 1; j > 0; j >>= 1) {
         for (int t = tid; t < np2 / 2; t += kThreads) {
           const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));  // lower index of the pair
