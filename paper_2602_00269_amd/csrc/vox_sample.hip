@@ -33,7 +33,6 @@ constexpr int kIdBits = 18;  // vocabulary of at most 2^18 tokens
 constexpr int kMaxVocab = 1 << kIdBits;
 constexpr int kKeyBits = 31 + kIdBits;
 constexpr int kLevels = 5;
-constexpr int kQuadMinVocab = 16384;  // below this a thread has too few tokens for quads to pay
 
 // Workgroup shapes.  Results do not depend on them (the candidate limits only decide which of
 // two equivalent paths runs); what differs is how much of a CU a stream takes.
@@ -220,7 +219,7 @@ static __device__ inline void for_each_token(const Ctx& c, F f) {
 // read in quads; the next quads are requested before the current ones are worked on.
 template <class Ctx, class F>
 static __device__ inline void for_each_quad(const Ctx& c, F f) {
-  constexpr int kQuads = 2;
+  constexpr int kQuads = 1;  // measured: more quads per turn do not pay, the pass is bound by its arithmetic
   const float4* z4 = reinterpret_cast<const float4*>(c.z);
   const int quads = c.V >> 2;
   if (quads <= 0) return;
@@ -754,9 +753,12 @@ extern "C" int vox_sample(int32_t num_streams, int32_t vocab, const float* logit
   using namespace vox;
   const dim3 grid((unsigned)num_streams);
   hipStream_t st = (hipStream_t)hip_stream;
-  // large vocabularies whose rows start 16-byte aligned are read four tokens per lane and load
-  const bool quad = vocab >= kQuadMinVocab && vocab % 4 == 0 && ((uintptr_t)logits & 15) == 0;
-  if (vocab <= SmallVocab::kVocab && !quad)
+  // rows that start 16-byte aligned are read four tokens per lane and load
+  const bool quad = vocab % 4 == 0 && ((uintptr_t)logits & 15) == 0;
+  if (vocab <= SmallVocab::kVocab && quad)
+    hipLaunchKernelGGL((sample_kernel<SmallVocab, true>), grid, dim3(SmallVocab::kThreads), 0, st,
+                       vocab, logits, params, history, window, uniforms, tokens, kept);
+  else if (vocab <= SmallVocab::kVocab)
     hipLaunchKernelGGL((sample_kernel<SmallVocab, false>), grid, dim3(SmallVocab::kThreads), 0, st,
                        vocab, logits, params, history, window, uniforms, tokens, kept);
   else if (quad)
