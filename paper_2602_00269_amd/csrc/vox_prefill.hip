@@ -388,16 +388,43 @@ __device__ inline int tile_ctx(int L, int n, int tq, int tau) {
 }
 __device__ inline int steps_of(int ctx) { return (ctx + kStepTokens - 1) / kStepTokens; }
 
-constexpr int kScanThreads = 256;
+// Plan of the multi-token step, first part, one workgroup: (1) per-stream tile and step counts
+// and their prefixes, (2) per tile its first step, step count and query rows, (3) the waves'
+// ranges.  Each part needs the whole of the one before and is a chain of a few dependent
+// look-ups per thread, so one workgroup that keeps the prefixes and the tile table in LDS
+// (binary searches at LDS latency, no launch in between) is quicker than three launches.
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanTilesLds = 6144;  // tile tables beyond this are searched in global memory
 
-__global__ __launch_bounds__(kScanThreads) void mq_scan_kernel(
+// Start of the run of segment sigma = t * Hkv + h on the global step axis.
+__device__ inline int64_t segment_first(const int32_t* tile_first, const int32_t* tile_steps,
+                                        int sigma, int Hkv) {
+  const int t = sigma / Hkv, h = sigma - t * Hkv;
+  return (int64_t)tile_first[t] + (int64_t)h * tile_steps[t];
+}
+
+// Ranges are balanced by cost rather than by step count.  A run costs its steps plus a fixed
+// `run_cost` (in steps) for fetching its query rows and storing its record, which matters when
+// runs are a few steps long (tiles of a short prompt): on the cost axis segment sigma occupies
+// [first(sigma) + run_cost * sigma, ... + run_cost + steps(sigma)), overhead units first.
+// Wave w starts at the step under cost w * quota, quota = ceil(total cost / waves); cost units
+// inside an overhead zone map to the segment's first step, so a range can be empty but never
+// lies strictly inside another segment's span of ranges.
+__global__ __launch_bounds__(kPlanThreads) void mq_plan_kernel(
     Params p, int tq, const int32_t* __restrict__ lens, const int32_t* __restrict__ qo, int waves,
-    int64_t desc_capacity, int32_t* __restrict__ header, int32_t* __restrict__ pt,
-    int32_t* __restrict__ ps, int32_t* __restrict__ lens_single) {
-  __shared__ int wave_tiles[kScanThreads / kWave], wave_steps[kScanThreads / kWave];
+    int run_cost, int64_t desc_capacity, int32_t* __restrict__ header, int32_t* __restrict__ pt,
+    int32_t* __restrict__ ps, int32_t* __restrict__ lens_single, int32_t* __restrict__ tile_first,
+    int32_t* __restrict__ tile_steps, TileInfo* __restrict__ tile_info,
+    int32_t* __restrict__ ranges, SplitSegment* __restrict__ split) {
+  __shared__ int32_t s_pt[kMaxStreams + 1], s_ps[kMaxStreams + 1];
+  __shared__ int32_t s_first[kPlanTilesLds + 1], s_steps[kPlanTilesLds];
+  __shared__ int wave_tiles[kPlanThreads / kWave], wave_steps[kPlanThreads / kWave];
+  __shared__ int s_N;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
   const int S = p.S;
-  const int per = (S + kScanThreads - 1) / kScanThreads;
+
+  // (1) tiles and steps per stream, exclusive prefixes
+  const int per = (S + kPlanThreads - 1) / kPlanThreads;
   const int lo = min(S, tid * per), hi = min(S, lo + per);
   int tiles = 0, steps = 0;
   for (int s = lo; s < hi; ++s) {
@@ -426,8 +453,8 @@ __global__ __launch_bounds__(kScanThreads) void mq_scan_kernel(
     bs_ += wave_steps[k];
   }
   for (int s = lo; s < hi; ++s) {  // second walk writes the exclusive prefixes
-    pt[s] = bt_;
-    ps[s] = bs_;
+    pt[s] = s_pt[s] = bt_;
+    ps[s] = s_ps[s] = bs_;
     const int L = lens[s], n = planned_tokens(p, qo, s);
     const int nt = (n + tq - 1) / tq;
     for (int tau = 0; tau < nt; ++tau) bs_ += steps_of(tile_ctx(L, n, tq, tau));
@@ -436,93 +463,80 @@ __global__ __launch_bounds__(kScanThreads) void mq_scan_kernel(
     // token keep theirs, all others become padded slots)
     if (lens_single) lens_single[s] = (qo[s + 1] - qo[s] == 1) ? L : 0;
   }
-  if (tid == kScanThreads - 1) {
-    pt[S] = bt_;
-    ps[S] = bs_;
+  if (tid == kPlanThreads - 1) {
+    pt[S] = s_pt[S] = bt_;
+    ps[S] = s_ps[S] = bs_;
     const int64_t n_all = (int64_t)bs_ * p.Hkv;
     const int64_t N = min(n_all, desc_capacity);
-    header[kHdrSteps] = (int)N;
+    header[kHdrSteps] = s_N = (int)N;
     header[kHdrPerWave] = (int)max((int64_t)1, (N + waves - 1) / waves);
     header[kHdrWaves] = waves;
     header[kHdrOverflow] = n_all > desc_capacity;
   }
-}
+  __syncthreads();
 
-__global__ __launch_bounds__(256) void mq_tiles_kernel(
-    Params p, int tq, const int32_t* __restrict__ lens, const int32_t* __restrict__ qo,
-    const int32_t* __restrict__ pt, const int32_t* __restrict__ ps,
-    int32_t* __restrict__ tile_first, int32_t* __restrict__ tile_steps,
-    TileInfo* __restrict__ tile_info) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  const int total = pt[p.S];
-  if (t >= total) return;
-  int a = 0, b = p.S;  // largest s with pt[s] <= t
-  while (b - a > 1) {
-    const int mid = (a + b) >> 1;
-    if (pt[mid] <= t)
-      a = mid;
-    else
-      b = mid;
+  // (2) the tile table
+  const int total = s_pt[S];
+  const bool in_lds = total <= kPlanTilesLds;
+  for (int t = tid; t < total; t += kPlanThreads) {
+    int a = 0, b = S;  // largest s with pt[s] <= t
+    while (b - a > 1) {
+      const int mid = (a + b) >> 1;
+      if (s_pt[mid] <= t)
+        a = mid;
+      else
+        b = mid;
+    }
+    const int s = a, tau = t - s_pt[s];
+    const int L = lens[s], n = planned_tokens(p, qo, s);
+    int cum = 0;
+    for (int k = 0; k < tau; ++k) cum += steps_of(tile_ctx(L, n, tq, k));
+    const int first = (s_ps[s] + cum) * p.Hkv, nsteps = steps_of(tile_ctx(L, n, tq, tau));
+    tile_first[t] = first;
+    tile_steps[t] = nsteps;
+    if (in_lds) {
+      s_first[t] = first;
+      s_steps[t] = nsteps;
+    }
+    TileInfo info;
+    info.stream = s;
+    info.q_row0 = qo[s] + tau * tq;
+    info.nq = min(tq, n - tau * tq);
+    info.pos0 = L - n + tau * tq;
+    tile_info[t] = info;
+    if (t == total - 1) tile_first[total] = s_ps[S] * p.Hkv;
   }
-  const int s = a, tau = t - pt[s];
-  const int L = lens[s], n = planned_tokens(p, qo, s);
-  int cum = 0;
-  for (int k = 0; k < tau; ++k) cum += steps_of(tile_ctx(L, n, tq, k));
-  tile_first[t] = (ps[s] + cum) * p.Hkv;
-  tile_steps[t] = steps_of(tile_ctx(L, n, tq, tau));
-  TileInfo info;
-  info.stream = s;
-  info.q_row0 = qo[s] + tau * tq;
-  info.nq = min(tq, n - tau * tq);
-  info.pos0 = L - n + tau * tq;
-  tile_info[t] = info;
-  if (t == total - 1) tile_first[total] = ps[p.S] * p.Hkv;
-}
+  __syncthreads();  // the table is complete, in LDS or (same workgroup, same CU) in memory
 
-// Start of the run of segment sigma = t * Hkv + h on the global step axis.
-__device__ inline int64_t segment_first(const int32_t* tile_first, const int32_t* tile_steps,
-                                        int sigma, int Hkv) {
-  const int t = sigma / Hkv, h = sigma - t * Hkv;
-  return (int64_t)tile_first[t] + (int64_t)h * tile_steps[t];
-}
-
-// Ranges balanced by cost rather than by step count.  A run costs its steps plus a fixed
-// `run_cost` (in steps) for fetching its query rows and storing its record, which matters when
-// runs are a few steps long (tiles of a short prompt): on the cost axis segment sigma occupies
-// [first(sigma) + run_cost * sigma, ... + run_cost + steps(sigma)), overhead units first.
-// Wave w starts at the step under cost w * quota, quota = ceil(total cost / waves); cost units
-// inside an overhead zone map to the segment's first step, so a range can be empty but never
-// lies strictly inside another segment's span of ranges.
-__global__ __launch_bounds__(256) void mq_ranges_kernel(
-    Params p, int waves, int run_cost, const int32_t* __restrict__ header,
-    const int32_t* __restrict__ pt, const int32_t* __restrict__ tile_first,
-    const int32_t* __restrict__ tile_steps, int32_t* __restrict__ ranges,
-    SplitSegment* __restrict__ split) {
-  const int w = blockIdx.x * blockDim.x + threadIdx.x;
+  // (3) the waves' ranges
+  const int32_t* first_of = in_lds ? s_first : tile_first;
+  const int32_t* steps_of_tile = in_lds ? s_steps : tile_steps;
   const int launched = (waves + kWavesPerGroup - 1) / kWavesPerGroup * kWavesPerGroup;
-  if (w > launched) return;  // waves past `waves` exist only to fill a workgroup: empty ranges
-  if (w < waves) split[w].nruns = 0;  // the expand kernel fills in the cut segments
-  const int N = header[kHdrSteps];
-  const int segments = pt[p.S] * p.Hkv;
-  const int64_t total = (int64_t)N + (int64_t)run_cost * segments;
-  const int64_t quota = max((int64_t)1, (total + waves - 1) / waves);
-  const int64_t target = (int64_t)w * quota;
-  if (w >= waves || target >= total || segments == 0) {
-    ranges[w] = N;
-    return;
+  const int N = s_N;
+  const int segments = total * p.Hkv;
+  const int64_t all_cost = (int64_t)N + (int64_t)run_cost * segments;
+  const int64_t quota = max((int64_t)1, (all_cost + waves - 1) / waves);
+  for (int w = tid; w <= launched; w += kPlanThreads) {
+    // waves past `waves` exist only to fill a workgroup: empty ranges
+    if (w < waves) split[w].nruns = 0;  // the expand kernel fills in the cut segments
+    const int64_t target = (int64_t)w * quota;
+    if (w >= waves || target >= all_cost || segments == 0) {
+      ranges[w] = N;
+      continue;
+    }
+    int a = 0, b = segments;  // largest sigma whose cost interval starts at or before target
+    while (b - a > 1) {
+      const int mid = (a + b) >> 1;
+      if (segment_first(first_of, steps_of_tile, mid, p.Hkv) + (int64_t)run_cost * mid <= target)
+        a = mid;
+      else
+        b = mid;
+    }
+    const int64_t first = segment_first(first_of, steps_of_tile, a, p.Hkv);
+    const int64_t into = target - (first + (int64_t)run_cost * a) - run_cost;
+    const int64_t nsteps = steps_of_tile[a / p.Hkv];
+    ranges[w] = (int)min((int64_t)N, first + min(nsteps, max((int64_t)0, into)));
   }
-  int a = 0, b = segments;  // largest sigma whose cost interval starts at or before target
-  while (b - a > 1) {
-    const int mid = (a + b) >> 1;
-    if (segment_first(tile_first, tile_steps, mid, p.Hkv) + (int64_t)run_cost * mid <= target)
-      a = mid;
-    else
-      b = mid;
-  }
-  const int64_t first = segment_first(tile_first, tile_steps, a, p.Hkv);
-  const int64_t into = target - (first + (int64_t)run_cost * a) - run_cost;
-  const int64_t steps = tile_steps[a / p.Hkv];
-  ranges[w] = (int)min((int64_t)N, first + min(steps, max((int64_t)0, into)));
 }
 
 // The wave that owns step x is the largest w with ranges[w] <= x (empty ranges share their
@@ -844,13 +858,10 @@ hipError_t launch_prefill(const Params& p, const PrefillWorkspace& m, char* ws, 
   const int run_cost = 4;
 
   if (phases & kPrefillPlan)
-    hipLaunchKernelGGL(mq_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, p, tq, lens, qo, waves,
-                       desc_capacity, header, pt, ps, lens_single);
+    hipLaunchKernelGGL(mq_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, p, tq, lens, qo, waves,
+                       run_cost, desc_capacity, header, pt, ps, lens_single, tile_first,
+                       tile_steps, tile_info, ranges, split);
   if (tiles > 0 && (phases & kPrefillPlan)) {
-    hipLaunchKernelGGL(mq_tiles_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, st,
-                       p, tq, lens, qo, pt, ps, tile_first, tile_steps, tile_info);
-    hipLaunchKernelGGL(mq_ranges_kernel, dim3((unsigned)((waves + kWavesPerGroup) / 256 + 1)), dim3(256), 0,
-                       st, p, waves, run_cost, header, pt, tile_first, tile_steps, ranges, split);
     const dim3 eg((unsigned)tiles, (unsigned)((max_tile_steps + 255) / 256));
     hipLaunchKernelGGL(mq_expand_kernel, eg, dim3(256), 0, st, p, bt, header, tile_first,
                        tile_steps, tile_info, ranges, waves, desc, split);
