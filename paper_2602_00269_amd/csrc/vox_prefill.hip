@@ -57,6 +57,8 @@ __device__ inline float max_across_16(float x) {
   const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
+constexpr float kMaxSlack = 8.f;
+
 __device__ inline float max_across_32(float x) {
   const uint32_t u = __float_as_uint(x);
   const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
@@ -270,7 +272,13 @@ struct MqMath {
 #pragma unroll
       for (int b = 0; b < CB; ++b) {
         const int cg = cg0 + b;
-        const float m_new = fmaxf(s.m[cg], mx[b]);
+        // The reference maximum of a column follows the scores lazily: it moves only when a
+        // score exceeds it by more than kMaxSlack (in log2 units), so probabilities reach at
+        // most 2^kMaxSlack and the accumulators are rescaled in the first steps of a run and
+        // hardly ever after (a running maximum of random scores still grows, by little, in
+        // most steps of a wave that carries 16 * CB columns).  The record's (max, sum,
+        // accumulator) are all relative to this reference, which is all the merge asks for.
+        const float m_new = mx[b] > s.m[cg] + kMaxSlack ? mx[b] : s.m[cg];
         // a column may have seen no token yet (its run starts past its causal limit): keep
         // the exponent arguments from being inf - inf, everything it contributes is zero
         const float m_ref = fmaxf(m_new, -FLT_MAX);
