@@ -256,6 +256,41 @@ size_t mixed_batch_base(size_t prefill_bytes, const vox_shape_t* s) {
   return align_up(prefill_bytes, 256) + align_up((size_t)s->num_streams * sizeof(int32_t), 256);
 }
 
+// The layers of a step.  q_of(l): layer l's query rows as the attention reads them;
+// append_of(l): the append role of layer l.
+// Launch chain: [plan + append(0)] attention(0) [merge(0) + append(1)] attention(1) ...
+// merge(L-1).  Each bracket is one launch of two independent roles.
+template <class QOf, class AppendOf>
+int step_layers(const vox_shape_t* shape, int num_layers, QOf q_of, AppendOf append_of,
+                void* const* k_pool, void* const* v_pool, const int32_t* block_tables,
+                const int32_t* context_lens, const int32_t* context_lens_host, float* const* out,
+                void* workspace, size_t workspace_bytes, hipStream_t st) {
+  Plan plan;
+  if (int rc = make_plan(shape, lens_for_planning(context_lens_host, st), workspace_bytes, &plan))
+    return rc;
+  Params p = make_params(shape);
+  char* ws = (char*)workspace;
+  p.pool_counter = pool_counter(plan, ws, 0);  // the plan zeroes every layer's counter
+  set_step_hints(&p, plan);
+  const WsPtrs w = ws_ptrs(plan, ws);
+  if (launch_plan_append(p, block_tables, context_lens, plan.waves, plan.desc_capacity,
+                         plan.max_steps, w.header, w.step_prefix, w.desc, append_of(0),
+                         st) != hipSuccess)
+    return VOX_ERR_HIP;
+  for (int l = 0; l < num_layers; ++l) {
+    p.pool_counter = pool_counter(plan, ws, l);
+    if (int rc = enqueue_attention(shape, p, plan, w, q_of(l), k_pool[l], v_pool[l], st))
+      return rc;
+    hipError_t e = l + 1 < num_layers
+                       ? launch_merge_append(p, w.header, w.step_prefix, w.pml, w.pacc, out[l],
+                                             block_tables, context_lens, append_of(l + 1), st)
+                       : launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], nullptr,
+                                      st);
+    if (e != hipSuccess) return VOX_ERR_HIP;
+  }
+  return VOX_OK;
+}
+
 // One decode call on a given workspace (the caller's, or the built-in scratch array).
 int decode_call(const vox_shape_t* shape, const void* q, const void* k_pool, const void* v_pool,
                 const int32_t* block_tables, const int32_t* context_lens,
@@ -377,35 +412,11 @@ int vox_decode_step(const vox_shape_t* shape, int32_t num_layers, const void* co
   if ((uintptr_t)workspace % 256) return VOX_ERR_ARG;
   for (int l = 0; l < num_layers; ++l)
     if (!all_aligned16(q[l], k_new[l], v_new[l], k_pool[l], v_pool[l], out[l])) return VOX_ERR_ARG;
-  hipStream_t st = (hipStream_t)hip_stream;
-  Plan plan;
-  if (int rc = make_plan(shape, lens_for_planning(context_lens_host, st), workspace_bytes, &plan))
-    return rc;
-  Params p = make_params(shape);
-  char* ws = (char*)workspace;
-  p.pool_counter = pool_counter(plan, ws, 0);  // the plan zeroes every layer's counter
-  set_step_hints(&p, plan);
-  const WsPtrs w = ws_ptrs(plan, ws);
-  // Launch chain: [plan + append(0)] attention(0) [merge(0) + append(1)] attention(1) ...
-  // merge(L-1).  Each bracket is one launch of two independent roles.
-  if (launch_plan_append(p, block_tables, context_lens, plan.waves, plan.desc_capacity,
-                         plan.max_steps, w.header, w.step_prefix, w.desc,
-                         plain_append(k_new[0], v_new[0], k_pool[0], v_pool[0]), st) != hipSuccess)
-    return VOX_ERR_HIP;
-  for (int l = 0; l < num_layers; ++l) {
-    p.pool_counter = pool_counter(plan, ws, l);
-    if (int rc = enqueue_attention(shape, p, plan, w, q[l], k_pool[l], v_pool[l], st)) return rc;
-    hipError_t e =
-        l + 1 < num_layers
-            ? launch_merge_append(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], block_tables,
-                                  context_lens,
-                                  plain_append(k_new[l + 1], v_new[l + 1], k_pool[l + 1],
-                                               v_pool[l + 1]),
-                                  st)
-            : launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], nullptr, st);
-    if (e != hipSuccess) return VOX_ERR_HIP;
-  }
-  return VOX_OK;
+  return step_layers(
+      shape, num_layers, [&](int l) { return q[l]; },
+      [&](int l) { return plain_append(k_new[l], v_new[l], k_pool[l], v_pool[l]); }, k_pool,
+      v_pool, block_tables, context_lens, context_lens_host, out, workspace, workspace_bytes,
+      (hipStream_t)hip_stream);
 }
 
 int vox_decode_plan(const vox_shape_t* shape, const int32_t* block_tables,
@@ -493,35 +504,13 @@ int vox_decode_step_rope(const vox_shape_t* shape, int32_t num_layers, const voi
   if ((uintptr_t)workspace % 256 || !all_aligned16(rope_cos, rope_sin)) return VOX_ERR_ARG;
   for (int l = 0; l < num_layers; ++l)
     if (!all_aligned16(qkv[l], q_rot[l], k_pool[l], v_pool[l], out[l])) return VOX_ERR_ARG;
-  hipStream_t st = (hipStream_t)hip_stream;
-  Plan plan;
-  if (int rc = make_plan(shape, lens_for_planning(context_lens_host, st), workspace_bytes, &plan))
-    return rc;
-  Params p = make_params(shape);
-  char* ws = (char*)workspace;
-  p.pool_counter = pool_counter(plan, ws, 0);  // the plan zeroes every layer's counter
-  set_step_hints(&p, plan);
-  const WsPtrs w = ws_ptrs(plan, ws);
-  // [plan + rope/append(0)] attention(0) [merge(0) + rope/append(1)] attention(1) ... merge(L-1)
-  const auto layer = [&](int l) {
-    return rope_append(qkv[l], rope_cos, rope_sin, q_rot[l], k_pool[l], v_pool[l]);
-  };
-  if (launch_plan_append(p, block_tables, context_lens, plan.waves, plan.desc_capacity,
-                         plan.max_steps, w.header, w.step_prefix, w.desc, layer(0),
-                         st) != hipSuccess)
-    return VOX_ERR_HIP;
-  for (int l = 0; l < num_layers; ++l) {
-    p.pool_counter = pool_counter(plan, ws, l);
-    if (int rc = enqueue_attention(shape, p, plan, w, q_rot[l], k_pool[l], v_pool[l], st))
-      return rc;
-    hipError_t e =
-        l + 1 < num_layers
-            ? launch_merge_append(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], block_tables,
-                                  context_lens, layer(l + 1), st)
-            : launch_merge(p, w.header, w.step_prefix, w.pml, w.pacc, out[l], nullptr, st);
-    if (e != hipSuccess) return VOX_ERR_HIP;
-  }
-  return VOX_OK;
+  return step_layers(
+      shape, num_layers, [&](int l) { return (const void*)q_rot[l]; },
+      [&](int l) {
+        return rope_append(qkv[l], rope_cos, rope_sin, q_rot[l], k_pool[l], v_pool[l]);
+      },
+      k_pool, v_pool, block_tables, context_lens, context_lens_host, out, workspace,
+      workspace_bytes, (hipStream_t)hip_stream);
 }
 
 size_t vox_paged_prefill_workspace_bytes(const vox_shape_t* shape, int32_t total_q) {
