@@ -1147,6 +1147,16 @@ SAMPLE_CASES = [
     (5, 1, 1.0),
     (9, 63, 0.0),
     (2, 262144, 2.0),
+    # rows read four tokens per load (length a multiple of four) in both workgroup shapes, next
+    # to rows that are not, around the 16 384-token limit of the small shape, and tiny rows
+    (37, 6564, 2.0),
+    (6, 4, 1.0),
+    (6, 8, 0.5),
+    (7, 1024, 2.0),
+    (5, 16383, 2.0),
+    (5, 16384, 2.0),
+    (3, 16386, 2.0),
+    (5, 16388, 2.0),
 ]
 
 
