@@ -820,6 +820,41 @@ def test_multi_token_append_and_prefill_match_oracle(dev, case):
         _assert_lse(lse.cpu().numpy(), ref_lse, f"prefill case {case} waves {waves}")
 
 
+def test_multi_token_plan_with_more_tiles_than_its_lds_table_holds(dev):
+    # the plan keeps the tile table in LDS up to 6144 tiles and searches it in memory beyond
+    # that: 7000 short streams with two or three new tokens each (one tile per stream), a few
+    # empty slots and one long prompt among them, against the oracle on every row
+    rng = np.random.default_rng(77)
+    s = 7000
+    lens = rng.integers(2, 41, size=s).astype(np.int32)
+    nq = np.minimum(lens, rng.integers(2, 4, size=s)).astype(np.int32)
+    lens[5], nq[5] = 0, 0
+    lens[6999], nq[6999] = 9, 0
+    lens[3000], nq[3000] = 700, 650
+    w, qo, q, k_new, v_new = _prefill_case(dev, lens, nq, 4, 2, 64, seed=78)
+    sh = binding.shape_of(w)
+    bt, lens_d, qo_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev), _i32(qo, dev)
+    kp_ref, vp_ref = _host_pools(w)
+    oracle.kv_append_multi(bits_of(k_new), bits_of(v_new), kp_ref, vp_ref, w.block_tables,
+                           w.context_lens, qo, head_dim=64)
+    binding.kv_append_multi(sh, k_new, v_new, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d)
+    torch.cuda.synchronize()
+    kp, vp = _host_pools(w)
+    assert np.array_equal(kp, kp_ref) and np.array_equal(vp, vp_ref)
+    ref, ref_lse = oracle.paged_prefill(bits_of(q), kp_ref, vp_ref, w.block_tables,
+                                        w.context_lens, qo, w.scale, num_kv_heads=2)
+    tq = int(qo[-1])
+    out = torch.full((tq, 4, 64), float("nan"), device=dev)
+    lse = torch.full((tq, 4), float("nan"), device=dev)
+    ws = torch.empty(binding.paged_prefill_workspace_bytes(sh, tq), dtype=torch.uint8, device=dev)
+    ws.fill_(0xFF)
+    binding.paged_prefill(sh, q, w.k_pool[0], w.v_pool[0], bt, lens_d, qo_d, w.context_lens, qo,
+                          out, ws, lse=lse)
+    torch.cuda.synchronize()
+    _assert_close(out.cpu().numpy(), ref, "7000 tiles")
+    _assert_lse(lse.cpu().numpy(), ref_lse, "7000 tiles")
+
+
 @pytest.mark.parametrize("hq,hkv,d,singles", [(24, 8, 128, 70), (14, 2, 64, 100), (8, 8, 64, 33)])
 def test_mixed_batches_of_decode_streams_and_prompts(dev, hq, hkv, d, singles):
     # with many single-token streams in a call those go through the decode kernels and the
