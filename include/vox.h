@@ -319,6 +319,29 @@ int vox_paged_prefill(const vox_shape_t* shape, const void* q, const void* k_poo
                       void* hip_stream);
 
 /*
+ * The multi-token step for a backbone that calls the attention once per layer (Section 3
+ * "LLM Forward": every layer has its own cache, all layers share lengths, offsets and block
+ * tables).  vox_prefill_plan does, once per step, everything of vox_paged_prefill that depends
+ * only on those: tiles, wave ranges and step descriptors (and, for a mixed batch, the plan of
+ * its decode part), left in the workspace.  vox_prefill_layer then runs one layer on that plan:
+ * vox_kv_append_multi of k_new / v_new when they are given (both or neither), the attention
+ * kernels and the merge; plan + layer give vox_paged_prefill's results bit for bit.  The host
+ * copies, the shape and workspace_bytes must be the ones the plan was made with (the layer call
+ * derives the same workspace map and the same split of a mixed batch from them); the plan stays
+ * valid until the workspace is written by something else.  layer (0 <= layer < 4096) selects
+ * the scheduling counter the decode part of a mixed batch uses, as in vox_decode_layer.
+ */
+int vox_prefill_plan(const vox_shape_t* shape, const int32_t* block_tables,
+                     const int32_t* context_lens, const int32_t* q_offsets,
+                     const int32_t* context_lens_host, const int32_t* q_offsets_host,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+int vox_prefill_layer(const vox_shape_t* shape, int32_t layer, const void* q, const void* k_new,
+                      const void* v_new, void* k_pool, void* v_pool, const int32_t* block_tables,
+                      const int32_t* context_lens, const int32_t* q_offsets,
+                      const int32_t* context_lens_host, const int32_t* q_offsets_host, float* out,
+                      float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Measurement aid: vox_paged_prefill that also records two caller-created hipEvent_t on
  * hip_stream around the multi-token attention kernel (the launch that reads the KV cache; in a
  * mixed batch the two launches that do, decode kernel first).

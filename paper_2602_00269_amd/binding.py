@@ -86,6 +86,10 @@ def load() -> ctypes.CDLL:
     lib.vox_paged_prefill.restype = ctypes.c_int
     lib.vox_paged_prefill_profiled.argtypes = [sp] + [vp] * 11 + [ctypes.c_size_t, vp, vp, vp]
     lib.vox_paged_prefill_profiled.restype = ctypes.c_int
+    lib.vox_prefill_plan.argtypes = [sp] + [vp] * 6 + [ctypes.c_size_t, vp]
+    lib.vox_prefill_plan.restype = ctypes.c_int
+    lib.vox_prefill_layer.argtypes = [sp, i32] + [vp] * 13 + [ctypes.c_size_t, vp]
+    lib.vox_prefill_layer.restype = ctypes.c_int
     lib.vox_sample.argtypes = [i32, i32, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.vox_sample.restype = ctypes.c_int
     lib.vox_sample_weights.argtypes = [i32, i32, vp, vp, vp, i32, vp, vp, vp]
@@ -377,6 +381,43 @@ def paged_prefill(shape, q, k_pool, v_pool, block_tables, context_lens, q_offset
                                   _stream(stream), ev0, ev1)
     del keep1, keep2
     _check(rc, "vox_paged_prefill")
+
+
+def prefill_plan(shape, block_tables, context_lens, q_offsets, context_lens_host, q_offsets_host,
+                 workspace, stream=None):
+    """Plan of one multi-token step, shared by the ``prefill_layer`` calls that follow."""
+    i32 = torch.int32
+    keep1, lens_h = _host_lens(context_lens_host)
+    keep2, qo_h = _host_lens(q_offsets_host)
+    rc = load().vox_prefill_plan(ctypes.byref(shape), _dev(block_tables, i32, "block_tables"),
+                                 _dev(context_lens, i32, "context_lens"),
+                                 _dev(q_offsets, i32, "q_offsets"), lens_h, qo_h,
+                                 _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                 _stream(stream))
+    del keep1, keep2
+    _check(rc, "vox_prefill_plan")
+
+
+def prefill_layer(shape, layer, q, k_new, v_new, k_pool, v_pool, block_tables, context_lens,
+                  q_offsets, context_lens_host, q_offsets_host, out, workspace, lse=None,
+                  stream=None):
+    """One layer on the plan ``prefill_plan`` left in ``workspace``; ``k_new`` / ``v_new`` may
+    both be None (attention over the cache as it is)."""
+    bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+    keep1, lens_h = _host_lens(context_lens_host)
+    keep2, qo_h = _host_lens(q_offsets_host)
+    rc = load().vox_prefill_layer(ctypes.byref(shape), int(layer), _dev(q, bf, "q"),
+                                  _dev(k_new, bf, "k_new", optional=True),
+                                  _dev(v_new, bf, "v_new", optional=True),
+                                  _dev(k_pool, bf, "k_pool"), _dev(v_pool, bf, "v_pool"),
+                                  _dev(block_tables, i32, "block_tables"),
+                                  _dev(context_lens, i32, "context_lens"),
+                                  _dev(q_offsets, i32, "q_offsets"), lens_h, qo_h,
+                                  _dev(out, f32, "out"), _dev(lse, f32, "lse", optional=True),
+                                  _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                  _stream(stream))
+    del keep1, keep2
+    _check(rc, "vox_prefill_layer")
 
 
 def sampling_params(temperature, top_p, repetition_penalty, top_k, num_streams, device="cuda"):

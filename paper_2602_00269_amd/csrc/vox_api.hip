@@ -319,6 +319,124 @@ int decode_call(const vox_shape_t* shape, const void* q, const void* k_pool, con
              : VOX_ERR_HIP;
 }
 
+// The multi-token step: its plan (phases & kPrefillPlan: everything that depends only on the
+// lengths, the offsets and the block tables), its attention and merge on one layer's buffers
+// (phases & kPrefillRun), or both.  `layer` selects the pool counter of the decode part of a
+// mixed batch.
+int prefill_call(const vox_shape_t* shape, int phases, int layer, const void* q,
+                 const void* k_pool, const void* v_pool, const int32_t* block_tables,
+                 const int32_t* context_lens, const int32_t* q_offsets,
+                 const int32_t* context_lens_host, const int32_t* q_offsets_host, float* out,
+                 float* lse, void* workspace, size_t workspace_bytes, void* hip_stream,
+                 void* event_before, void* event_after) {
+  if (int rc = validate(shape)) return rc;
+  if (!context_lens_host || !q_offsets_host) return VOX_ERR_NULL;
+  if (q_offsets_host[shape->num_streams] == 0 && q_offsets_host[0] == 0)
+    return VOX_OK;  // no query rows: nothing to compute, the row arrays may be empty (NULL)
+  const bool run = (phases & kPrefillRun) != 0;
+  if (!block_tables || !context_lens || !q_offsets || !workspace) return VOX_ERR_NULL;
+  if (run && (!q || !k_pool || !v_pool || !out)) return VOX_ERR_NULL;
+  if ((uintptr_t)workspace % 256 || (run && !all_aligned16(q, k_pool, v_pool, out)))
+    return VOX_ERR_ARG;
+  Params p = make_params(shape);
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  // exact tile and step counts from the host copies (the scheduler that admits a prompt
+  // knows its length)
+  if (q_offsets_host[0] != 0) return VOX_ERR_ARG;
+  int singles = 0;
+  int64_t single_steps = 0;
+  for (int s = 0; s < p.S; ++s) {
+    const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
+    const int64_t L = context_lens_host[s];
+    if (n < 0 || n > L || L > (int64_t)shape->max_blocks_per_stream * kBlock) return VOX_ERR_ARG;
+    if (n == 1) {
+      ++singles;
+      single_steps += (L + kStepTokens - 1) / kStepTokens * p.Hkv;
+    }
+  }
+  const bool split = singles >= kMinSingleStreams && single_steps >= kMinSingleSteps &&
+                     shape->decode_path != VOX_PATH_VALU;
+  const int waves = split_waves(shape);
+  // Two passes at most: with the single-token streams left to the decode kernels when there are
+  // enough of them and the workspace has room for both parts, else with every stream here.
+  for (int mixed = split ? 1 : 0; mixed >= 0; --mixed) {
+    int64_t max_new = 0, tile_streams = 0;
+    for (int s = 0; s < p.S; ++s) {
+      const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
+      if (mixed && n == 1) continue;
+      if (n > max_new) max_new = n;
+      tile_streams += n > 0;
+    }
+    const int ncg = prefill_column_groups(p, (int)(max_new < INT32_MAX ? max_new : INT32_MAX));
+    const int tq = (16 / p.G) * ncg;
+    int64_t tiles = 0, steps = 0, max_tile_steps = 1;
+    for (int s = 0; s < p.S; ++s) {
+      const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
+      if (mixed && n == 1) continue;
+      const int64_t L = context_lens_host[s];
+      const int64_t nt = (n + tq - 1) / tq;
+      if (n > 0 && (L + kStepTokens - 1) / kStepTokens * p.Hkv > max_tile_steps)
+        max_tile_steps = (L + kStepTokens - 1) / kStepTokens * p.Hkv;
+      for (int64_t tau = 0; tau < nt; ++tau) {
+        const int64_t ctx = L - n + (n < (tau + 1) * tq ? n : (tau + 1) * tq);
+        steps += (ctx + kStepTokens - 1) / kStepTokens;
+      }
+      tiles += nt;
+    }
+    steps *= p.Hkv;
+    if (steps > INT32_MAX || tiles * p.Hkv > INT32_MAX / 2) return VOX_ERR_SHAPE;
+    const int64_t slots = waves + tiles * p.Hkv;
+    const PrefillWorkspace m = map_prefill_workspace(p, ncg, tiles, slots, steps, waves);
+    if (!mixed) {
+      if (m.total > workspace_bytes) return VOX_ERR_WORKSPACE;
+      return launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool,
+                            block_tables, context_lens, q_offsets, out, lse, st,
+                            (hipEvent_t)event_before, (hipEvent_t)event_after, phases, 0,
+                            nullptr, max_tile_steps) == hipSuccess
+                 ? VOX_OK
+                 : VOX_ERR_HIP;
+    }
+    // the decode part: masked lengths on both sides, its own workspace behind the multi-token one
+    const size_t lens_off = align_up(m.total, 256), dec_off = mixed_batch_base(m.total, shape);
+    if (dec_off >= workspace_bytes) continue;
+    Plan plan;
+    if (make_plan(shape, context_lens_host, workspace_bytes - dec_off, &plan, q_offsets_host) !=
+        VOX_OK)
+      continue;
+    int32_t* lens_single = (int32_t*)(ws + lens_off);
+    char* dws = ws + dec_off;
+    Params pd = p;  // the decode kernels' view
+    pd.q_rows = q_offsets;
+    pd.pool_counter = pool_counter(plan, dws, layer);  // the plan zeroes every layer's counter
+    set_step_hints(&pd, plan);
+    p.skip_single = 1;  // the multi-token plan's view
+    if (phases & kPrefillPlan) {
+      // the multi-token plan's first kernel also writes the masked lengths
+      if (launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool,
+                         block_tables, context_lens, q_offsets, out, lse, st, nullptr, nullptr,
+                         kPrefillPlan, tile_streams, lens_single, max_tile_steps) != hipSuccess)
+        return VOX_ERR_HIP;
+      if (int rc = enqueue_plan(pd, plan, dws, block_tables, lens_single, st)) return rc;
+    }
+    if (!run) return VOX_OK;
+    const WsPtrs w = ws_ptrs(plan, dws);
+    // the events enclose both attention kernels
+    hipEvent_t after_decode = tiles > 0 ? nullptr : (hipEvent_t)event_after;
+    if (int rc = enqueue_attention(shape, pd, plan, w, q, k_pool, v_pool, st,
+                                   (hipEvent_t)event_before, after_decode))
+      return rc;
+    if (launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool, block_tables,
+                       context_lens, q_offsets, out, lse, st, nullptr, (hipEvent_t)event_after,
+                       kPrefillRun, tile_streams, nullptr, max_tile_steps) != hipSuccess)
+      return VOX_ERR_HIP;
+    return launch_merge(pd, w.header, w.step_prefix, w.pml, w.pacc, out, lse, st) == hipSuccess
+               ? VOX_OK
+               : VOX_ERR_HIP;
+  }
+  return VOX_ERR_WORKSPACE;  // not reached: the pass with every stream here returns
+}
+
 }  // namespace
 }  // namespace vox
 
@@ -568,108 +686,38 @@ int vox_paged_prefill_profiled(const vox_shape_t* shape, const void* q, const vo
                                const int32_t* context_lens_host, const int32_t* q_offsets_host,
                                float* out, float* lse, void* workspace, size_t workspace_bytes,
                                void* hip_stream, void* event_before, void* event_after) {
+  return prefill_call(shape, kPrefillPlan | kPrefillRun, 0, q, k_pool, v_pool, block_tables,
+                      context_lens, q_offsets, context_lens_host, q_offsets_host, out, lse,
+                      workspace, workspace_bytes, hip_stream, event_before, event_after);
+}
+
+int vox_prefill_plan(const vox_shape_t* shape, const int32_t* block_tables,
+                     const int32_t* context_lens, const int32_t* q_offsets,
+                     const int32_t* context_lens_host, const int32_t* q_offsets_host,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return prefill_call(shape, kPrefillPlan, 0, nullptr, nullptr, nullptr, block_tables,
+                      context_lens, q_offsets, context_lens_host, q_offsets_host, nullptr, nullptr,
+                      workspace, workspace_bytes, hip_stream, nullptr, nullptr);
+}
+
+int vox_prefill_layer(const vox_shape_t* shape, int32_t layer, const void* q, const void* k_new,
+                      const void* v_new, void* k_pool, void* v_pool, const int32_t* block_tables,
+                      const int32_t* context_lens, const int32_t* q_offsets,
+                      const int32_t* context_lens_host, const int32_t* q_offsets_host, float* out,
+                      float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (int rc = validate(shape)) return rc;
-  if (!context_lens_host || !q_offsets_host) return VOX_ERR_NULL;
-  if (q_offsets_host[shape->num_streams] == 0 && q_offsets_host[0] == 0)
-    return VOX_OK;  // no query rows: nothing to compute, the row arrays may be empty (NULL)
-  if (!q || !k_pool || !v_pool || !block_tables || !context_lens || !q_offsets || !out ||
-      !workspace)
-    return VOX_ERR_NULL;
-  if ((uintptr_t)workspace % 256 || !all_aligned16(q, k_pool, v_pool, out)) return VOX_ERR_ARG;
-  Params p = make_params(shape);
-  hipStream_t st = (hipStream_t)hip_stream;
-  char* ws = (char*)workspace;
-  // exact tile and step counts from the host copies (the scheduler that admits a prompt
-  // knows its length)
-  if (q_offsets_host[0] != 0) return VOX_ERR_ARG;
-  int singles = 0;
-  int64_t single_steps = 0;
-  for (int s = 0; s < p.S; ++s) {
-    const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
-    const int64_t L = context_lens_host[s];
-    if (n < 0 || n > L || L > (int64_t)shape->max_blocks_per_stream * kBlock) return VOX_ERR_ARG;
-    if (n == 1) {
-      ++singles;
-      single_steps += (L + kStepTokens - 1) / kStepTokens * p.Hkv;
-    }
-  }
-  const bool split = singles >= kMinSingleStreams && single_steps >= kMinSingleSteps &&
-                     shape->decode_path != VOX_PATH_VALU;
-  const int waves = split_waves(shape);
-  // Two passes at most: with the single-token streams left to the decode kernels when there are
-  // enough of them and the workspace has room for both parts, else with every stream here.
-  for (int mixed = split ? 1 : 0; mixed >= 0; --mixed) {
-    int64_t max_new = 0, tile_streams = 0;
-    for (int s = 0; s < p.S; ++s) {
-      const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
-      if (mixed && n == 1) continue;
-      if (n > max_new) max_new = n;
-      tile_streams += n > 0;
-    }
-    const int ncg = prefill_column_groups(p, (int)(max_new < INT32_MAX ? max_new : INT32_MAX));
-    const int tq = (16 / p.G) * ncg;
-    int64_t tiles = 0, steps = 0, max_tile_steps = 1;
-    for (int s = 0; s < p.S; ++s) {
-      const int64_t n = (int64_t)q_offsets_host[s + 1] - q_offsets_host[s];
-      if (mixed && n == 1) continue;
-      const int64_t L = context_lens_host[s];
-      const int64_t nt = (n + tq - 1) / tq;
-      if (n > 0 && (L + kStepTokens - 1) / kStepTokens * p.Hkv > max_tile_steps)
-        max_tile_steps = (L + kStepTokens - 1) / kStepTokens * p.Hkv;
-      for (int64_t tau = 0; tau < nt; ++tau) {
-        const int64_t ctx = L - n + (n < (tau + 1) * tq ? n : (tau + 1) * tq);
-        steps += (ctx + kStepTokens - 1) / kStepTokens;
-      }
-      tiles += nt;
-    }
-    steps *= p.Hkv;
-    if (steps > INT32_MAX || tiles * p.Hkv > INT32_MAX / 2) return VOX_ERR_SHAPE;
-    const int64_t slots = waves + tiles * p.Hkv;
-    const PrefillWorkspace m = map_prefill_workspace(p, ncg, tiles, slots, steps, waves);
-    if (!mixed) {
-      if (m.total > workspace_bytes) return VOX_ERR_WORKSPACE;
-      return launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool,
-                            block_tables, context_lens, q_offsets, out, lse, st,
-                            (hipEvent_t)event_before, (hipEvent_t)event_after,
-                            kPrefillPlan | kPrefillRun, 0, nullptr, max_tile_steps) == hipSuccess
-                 ? VOX_OK
-                 : VOX_ERR_HIP;
-    }
-    // the decode part: masked lengths on both sides, its own workspace behind the multi-token one
-    const size_t lens_off = align_up(m.total, 256), dec_off = mixed_batch_base(m.total, shape);
-    if (dec_off >= workspace_bytes) continue;
-    Plan plan;
-    if (make_plan(shape, context_lens_host, workspace_bytes - dec_off, &plan, q_offsets_host) !=
-        VOX_OK)
-      continue;
-    int32_t* lens_single = (int32_t*)(ws + lens_off);
-    char* dws = ws + dec_off;
-    Params pd = p;  // the decode kernels' view
-    pd.q_rows = q_offsets;
-    pd.pool_counter = pool_counter(plan, dws, 0);
-    set_step_hints(&pd, plan);
-    p.skip_single = 1;  // the multi-token plan's view
-    // the multi-token plan's first kernel also writes the masked lengths
-    if (launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool, block_tables,
-                       context_lens, q_offsets, out, lse, st, nullptr, nullptr, kPrefillPlan,
-                       tile_streams, lens_single, max_tile_steps) != hipSuccess)
-      return VOX_ERR_HIP;
-    if (int rc = enqueue_plan(pd, plan, dws, block_tables, lens_single, st)) return rc;
-    const WsPtrs w = ws_ptrs(plan, dws);
-    // the events enclose both attention kernels
-    hipEvent_t after_decode = tiles > 0 ? nullptr : (hipEvent_t)event_after;
-    if (int rc = enqueue_attention(shape, pd, plan, w, q, k_pool, v_pool, st,
-                                   (hipEvent_t)event_before, after_decode))
+  if (layer < 0 || layer >= kMaxLayers) return VOX_ERR_ARG;
+  if (!q_offsets_host || (k_new == nullptr) != (v_new == nullptr)) return VOX_ERR_NULL;
+  if (k_new) {
+    const int64_t rows = (int64_t)q_offsets_host[shape->num_streams] - q_offsets_host[0];
+    if (rows < 0 || rows > INT32_MAX) return VOX_ERR_ARG;
+    if (int rc = vox_kv_append_multi(shape, k_new, v_new, k_pool, v_pool, block_tables,
+                                     context_lens, q_offsets, (int32_t)rows, hip_stream))
       return rc;
-    if (launch_prefill(p, m, ws, ncg, tiles, steps, steps, waves, q, k_pool, v_pool, block_tables,
-                       context_lens, q_offsets, out, lse, st, nullptr, (hipEvent_t)event_after,
-                       kPrefillRun, tile_streams, nullptr, max_tile_steps) != hipSuccess)
-      return VOX_ERR_HIP;
-    return launch_merge(pd, w.header, w.step_prefix, w.pml, w.pacc, out, lse, st) == hipSuccess
-               ? VOX_OK
-               : VOX_ERR_HIP;
   }
-  return VOX_ERR_WORKSPACE;  // not reached: the pass with every stream here returns
+  return prefill_call(shape, kPrefillRun, layer, q, k_pool, v_pool, block_tables, context_lens,
+                      q_offsets, context_lens_host, q_offsets_host, out, lse, workspace,
+                      workspace_bytes, hip_stream, nullptr, nullptr);
 }
 
 const char* vox_strerror(int code) {

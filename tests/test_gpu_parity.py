@@ -926,6 +926,83 @@ def test_random_mixed_batches(dev, seed):
     _assert_lse(lse.cpu().numpy(), ref_lse, f"random mixed batch {seed}")
 
 
+@pytest.mark.parametrize("kind", ["chunks", "prompts", "mixed"])
+def test_multi_token_plan_then_a_call_per_layer(dev, kind):
+    # what a backbone does whose projections run between the attention calls: one
+    # vox_prefill_plan, then a vox_prefill_layer call per layer (three layers with pools, rows
+    # and outputs of their own, other work on the stream in between).  Outputs, log-sum-exps
+    # and pools must equal those of vox_kv_append_multi + vox_paged_prefill on the same layer
+    # bit for bit, and the oracle's within the tolerance; a layer call without new rows attends
+    # over the cache as it is
+    layers = 3
+    if kind == "chunks":
+        lens, nq, hq, hkv, d = [700, 1500, 90, 0, 33], [28, 25, 15, 0, 1], 14, 2, 64
+    elif kind == "prompts":
+        lens, nq, hq, hkv, d = [37, 16, 5, 64, 9, 300, 129], [37, 3, 0, 17, 9, 1, 129], 24, 8, 128
+    else:  # enough single-token streams for the decode kernels to take them
+        rng = np.random.default_rng(41)
+        singles, hq, hkv, d = 70, 24, 8, 128
+        avg = 32 * 40000 // (singles * hkv)
+        lens = list(rng.integers(avg - avg // 4, avg + avg // 4, size=singles)) + [300, 64, 0, 250, 40]
+        nq = [1] * singles + [300, 20, 0, 0, 2]
+        assert sum((L + 31) // 32 for L in lens[:singles]) * hkv >= 32768
+        lens, nq = [int(x) for x in lens], [int(x) for x in nq]
+    w, qo, q0, k0, v0 = _prefill_case(dev, lens, nq, hq, hkv, d, seed=300)
+    sh = binding.shape_of(w)
+    bt, lens_d, qo_d = _i32(w.block_tables, dev), _i32(w.context_lens, dev), _i32(qo, dev)
+    tq = int(qo[-1])
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(301)
+
+    def rnd(shape):
+        return torch.randn(shape, generator=gen, device=dev).to(torch.bfloat16)
+
+    q = [q0] + [rnd((tq, hq, d)) for _ in range(layers - 1)]
+    k_new = [k0] + [rnd((tq, hkv, d)) for _ in range(layers - 1)]
+    v_new = [v0] + [rnd((tq, hkv, d)) for _ in range(layers - 1)]
+    k_pool = [w.k_pool[0]] + [w.k_pool[0].clone() for _ in range(layers - 1)]
+    v_pool = [w.v_pool[0]] + [w.v_pool[0].clone() for _ in range(layers - 1)]
+    pools0 = [(k.clone(), v.clone()) for k, v in zip(k_pool, v_pool)]
+    ws = torch.empty(binding.paged_prefill_workspace_bytes(sh, tq), dtype=torch.uint8, device=dev)
+    want = []
+    for l in range(layers):
+        out = torch.full((tq, hq, d), float("nan"), device=dev)
+        lse = torch.full((tq, hq), float("nan"), device=dev)
+        binding.kv_append_multi(sh, k_new[l], v_new[l], k_pool[l], v_pool[l], bt, lens_d, qo_d)
+        binding.paged_prefill(sh, q[l], k_pool[l], v_pool[l], bt, lens_d, qo_d, w.context_lens, qo,
+                              out, ws, lse=lse)
+        torch.cuda.synchronize()
+        want.append((out, lse, k_pool[l].clone(), v_pool[l].clone()))
+    kp, vp = bits_of(want[0][2]), bits_of(want[0][3])
+    ref, ref_lse = oracle.paged_prefill(bits_of(q[0]), kp, vp, w.block_tables, w.context_lens, qo,
+                                        w.scale, num_kv_heads=hkv)
+    _assert_close(want[0][0].cpu().numpy(), ref, f"{kind} layer 0")
+    _assert_lse(want[0][1].cpu().numpy(), ref_lse, f"{kind} layer 0")
+    for (k_0, v_0), k, v in zip(pools0, k_pool, v_pool):
+        k.copy_(k_0)
+        v.copy_(v_0)
+    ws.fill_(0xFF)
+    outs = [torch.full((tq, hq, d), float("nan"), device=dev) for _ in range(layers)]
+    lses = [torch.full((tq, hq), float("nan"), device=dev) for _ in range(layers)]
+    binding.prefill_plan(sh, bt, lens_d, qo_d, w.context_lens, qo, ws)
+    for l in range(layers):
+        torch.zeros(1 << 16, device=dev).add_(1.0)  # other work of the layer
+        binding.prefill_layer(sh, l, q[l], k_new[l], v_new[l], k_pool[l], v_pool[l], bt, lens_d,
+                              qo_d, w.context_lens, qo, outs[l], ws, lse=lses[l])
+    torch.cuda.synchronize()
+    for l in range(layers):
+        assert torch.equal(outs[l], want[l][0]), f"{kind} layer {l}: output"
+        assert torch.equal(lses[l], want[l][1]), f"{kind} layer {l}: log-sum-exp"
+        assert torch.equal(k_pool[l].view(torch.int16), want[l][2].view(torch.int16))
+        assert torch.equal(v_pool[l].view(torch.int16), want[l][3].view(torch.int16))
+    again = torch.full((tq, hq, d), float("nan"), device=dev)
+    binding.prefill_layer(sh, 1, q[1], None, None, k_pool[1], v_pool[1], bt, lens_d, qo_d,
+                          w.context_lens, qo, again, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(again, want[1][0])
+    assert torch.equal(k_pool[1].view(torch.int16), want[1][2].view(torch.int16))
+
+
 def test_prefill_with_one_token_per_stream_equals_decode(dev):
     lens = [33, 700, 64, 1, 255]
     w, qo, q, _, _ = _prefill_case(dev, lens, [1] * 5, 24, 8, 128, seed=90)

@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
             "vox_kv_append_multi", "vox_paged_prefill", "vox_paged_prefill_profiled",
             "vox_paged_prefill_workspace_bytes", "vox_rope_append", "vox_decode_step_rope", "vox_sample",
             "vox_sample_weights", "vox_paged_decode_static", "vox_decode_plan",
-            "vox_decode_layer"} <= set(names)
+            "vox_decode_layer", "vox_prefill_plan", "vox_prefill_layer"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -130,6 +130,45 @@ def test_multi_token_calls_validate_on_the_host(lib):
     # it has room for the decode kernels' workspace too (mixed batches use both)
     assert (lib.vox_paged_prefill_workspace_bytes(ctypes.byref(sh), 5) >
             lib.vox_paged_decode_workspace_bytes(ctypes.byref(sh)))
+
+
+def test_multi_token_plan_and_layer_calls_validate_on_the_host(lib):
+    sh = _shape()
+    one, odd = ctypes.c_void_p(256), ctypes.c_void_p(264)
+    i32 = ctypes.c_int32
+    lens = (i32 * 4)(40, 7, 0, 3)
+    qo = (i32 * 5)(0, 5, 5, 5, 8)
+    big = 1 << 22
+    none = (i32 * 5)(0, 0, 0, 0, 0)
+    # no rows: nothing to plan or run
+    assert lib.vox_prefill_plan(ctypes.byref(sh), None, None, None, lens, none, None, 0, None) == 0
+    # plan: host copies and device arrays are required, workspace aligned and large enough
+    assert lib.vox_prefill_plan(ctypes.byref(sh), one, one, one, None, qo, one, big, None) == -1
+    assert lib.vox_prefill_plan(ctypes.byref(sh), one, None, one, lens, qo, one, big, None) == -1
+    assert lib.vox_prefill_plan(ctypes.byref(sh), one, one, one, lens, qo, ctypes.c_void_p(257),
+                                big, None) == -5
+    assert lib.vox_prefill_plan(ctypes.byref(sh), one, one, one, lens, qo, one, 64, None) == -3
+    bad = (i32 * 5)(0, 41, 41, 41, 41)  # more new tokens than the stream holds
+    assert lib.vox_prefill_plan(ctypes.byref(sh), one, one, one, lens, bad, one, big, None) == -5
+    # layer: index range, k_new without v_new, missing and misaligned tensors
+    # q k_new v_new k_pool v_pool bt lens qo | lens_host qo_host | out lse ws bytes stream
+    args = [one, None, None, one, one, one, one, one, lens, qo, one, None, one, big, None]
+    assert lib.vox_prefill_layer(ctypes.byref(sh), -1, *args) == -5
+    assert lib.vox_prefill_layer(ctypes.byref(sh), 4096, *args) == -5
+    a = list(args)
+    a[1] = one
+    assert lib.vox_prefill_layer(ctypes.byref(sh), 0, *a) == -1
+    for missing in (0, 3, 4, 5, 6, 7, 10, 12):
+        a = list(args)
+        a[missing] = None
+        assert lib.vox_prefill_layer(ctypes.byref(sh), 0, *a) == -1, missing
+    for odd_at in (0, 3, 10):
+        a = list(args)
+        a[odd_at] = odd
+        assert lib.vox_prefill_layer(ctypes.byref(sh), 0, *a) == -5, odd_at
+    a = list(args)
+    a[13] = 64
+    assert lib.vox_prefill_layer(ctypes.byref(sh), 0, *a) == -3
 
 
 def test_rope_calls_validate_on_the_host(lib):
