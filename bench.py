@@ -61,7 +61,7 @@ def cpu_model() -> str:
     return "unknown"
 
 
-def bench_multi(args, dev) -> int:
+def bench_multi(args, dev, emit=True):
     """Multi-token step (append of n_s new tokens per stream + causal paged attention).
 
     Algorithmic work per step: every context token's K and V read once per kv head
@@ -186,7 +186,7 @@ def bench_multi(args, dev) -> int:
             "host_cpus": os.cpu_count(),
         }
 
-    print(json.dumps({
+    line = {
         "metric": "multi-token step context KV GB/s (each context byte counted once)",
         "value": round(value, 1),
         "unit": "GB/s",
@@ -217,11 +217,14 @@ def bench_multi(args, dev) -> int:
         "tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 2),
         "roofline": roofline,
         "cpu_baseline": cpu,
-    }))
-    return 0
+    }
+    if emit:
+        print(json.dumps(line))
+        return 0
+    return line
 
 
-def bench_sample(args, dev) -> int:
+def bench_sample(args, dev, emit=True):
     """Sampling step: one launch turns fp32 logits [S, V] into S tokens.  Algorithmic bytes: the
     logits once (S * V * 4); the kernel is one workgroup per stream."""
     import numpy as np
@@ -288,7 +291,7 @@ def bench_sample(args, dev) -> int:
         cpu = {"value": round(n / secs, 1), "unit": "tokens/s", "cores": 1, "kind": "oracle",
                "sample": f"oracle sampling of streams [0,{n}) of {s} (vocabulary {v}), 1 pass in "
                          f"{secs:.2f} s", "cpu_model": cpu_model(), "host_cpus": os.cpu_count()}
-    print(json.dumps({
+    line = {
         "metric": "sampled tokens/s (one launch per batch of streams)",
         "value": round(s / (ms_per_step * 1e-3), 1),
         "unit": "tokens/s",
@@ -307,8 +310,11 @@ def bench_sample(args, dev) -> int:
         "logits_gbps": round(nbytes / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
-    }))
-    return 0
+    }
+    if emit:
+        print(json.dumps(line))
+        return 0
+    return line
 
 
 def bench_decode(args, dev, workload, full=True, layerwise=False):
@@ -628,7 +634,7 @@ def main() -> int:
                     help="time the step as one vox_decode_plan and a vox_decode_layer call per layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true",
-                    help="headline workload only: skip the cfg4 / cfg2 / cfg5 records of the default run")
+                    help="headline workload only: skip the records of the other workloads in the default run")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
 
@@ -666,6 +672,21 @@ def main() -> int:
         gc.collect()
         torch.cuda.empty_cache()
         line["also"].append(bench_decode(args, dev, "cfg5", full=False, layerwise=True))
+        # the steps next to the decode step (multi-token step, sampling), one short record each
+        import copy
+
+        for other in (*MULTI_WORKLOADS, *SAMPLE_WORKLOADS):
+            gc.collect()
+            torch.cuda.empty_cache()
+            a = copy.copy(args)
+            a.workload, a.no_cpu_baseline, a.copy_calibration = other, True, False
+            r = (bench_multi if other in MULTI_WORKLOADS else bench_sample)(a, dev, emit=False)
+            line["also"].append({
+                "workload": r["config"]["workload"], "metric": r["metric"], "value": r["value"],
+                "unit": r["unit"], "ms_per_step": r["ms_per_step"],
+                "kernel": r["roofline"]["kernel"], "kernel_ms": r["roofline"]["kernel_ms"],
+                "bound": r["roofline"]["bound"], "frac": r["roofline"]["frac"],
+                "traffic": r["roofline"]["traffic"]})
     print(json.dumps(line))
     return 0
 
