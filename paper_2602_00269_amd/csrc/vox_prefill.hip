@@ -380,10 +380,10 @@ struct MqMath {
 };
 
 // ---------------------------------------------------------------------------------------
-// Plan, three small kernels.
-//   scan:   per stream tiles_s = ceil(n_s / TQ) and steps_s = sum over its tiles of
-//           ceil(ctx_tile / 32); exclusive scans PT (tiles) and PS (steps, per kv head).
-//   tiles:  per tile its first global step, step count, TileInfo and the row -> tile map.
+// Plan, two kernels.
+//   plan:   per stream tiles_s = ceil(n_s / TQ) and steps_s = sum over its tiles of
+//           ceil(ctx_tile / 32), exclusive scans PT (tiles) and PS (steps, per kv head); per
+//           tile its first global step, step count and TileInfo; the waves' ranges.
 //   expand: per tile the descriptors of its steps.
 // New tokens of stream s as the plan sees them: in a mixed batch the streams that bring exactly
 // one token are left to the decode kernels.
